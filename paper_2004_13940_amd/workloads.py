@@ -1,0 +1,284 @@
+"""Seeded synthetic workloads for the factorization-machine pass.
+
+This module only *synthesises inputs* (a CSR matrix, labels, initial
+parameters, hyper-parameters).  It is shared by the tests, the benchmark and
+the smoke run, and is imported by neither the CPU oracle nor the HIP library.
+The five recipes stand in for the data sets the paper measures on (small dense
+regression/classification tables, a text-like matrix of real-sim's shape, and
+click logs of Criteo's structure; Section 5, Table "Dataset Characteristics",
+and the sizing argument in the abstract): those data sets are not available
+here and nothing of them is reproduced.
+
+Labels come from a *planted teacher*: a random factorization machine whose
+score is evaluated here with scipy.sparse products, then thresholded (or
+perturbed with noise for regression).  This is input synthesis; neither the
+oracle nor the HIP path calls it to produce any output.
+
+Every array is a deterministic function of ``(config index, seed, scale)``:
+``numpy.random.Generator(PCG64)`` streams spawned from
+``SeedSequence(13940 + index)`` (or the given seed).  Columns inside a row are
+distinct and ascending.
+"""
+from __future__ import annotations
+
+import hashlib
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, field
+
+import numpy as np
+import scipy.sparse as sp
+
+LOSS_SQUARED = 0
+LOSS_LOGISTIC = 1
+
+
+@dataclass
+class Workload:
+    name: str
+    N: int
+    D: int
+    K: int
+    rowptr: np.ndarray  # int64 [N+1]
+    col: np.ndarray  # int32 [nnz], ascending and distinct inside a row
+    val: np.ndarray  # float32 [nnz]
+    y: np.ndarray  # float32 [N]
+    w0: np.float32
+    w: np.ndarray  # float32 [D]
+    V: np.ndarray  # float32 [D, K] row-major
+    loss: int
+    lambda_w: float
+    lambda_v: float
+    eta: float
+    loss_scale: float
+    epochs: int
+    P: int
+    update_w0: int = 1
+    notes: dict = field(default_factory=dict)
+
+    @property
+    def nnz(self) -> int:
+        return int(self.rowptr[-1])
+
+    def sha256(self) -> str:
+        h = hashlib.sha256()
+        for arr in (self.rowptr, self.col, self.val, self.y):
+            h.update(np.ascontiguousarray(arr).view(np.uint8))
+        return h.hexdigest()
+
+
+# --------------------------------------------------------------------------
+# helpers (sampling only)
+# --------------------------------------------------------------------------
+
+def _zipf_cdf(n: int, s: float) -> np.ndarray:
+    """CDF of the Zipf law with exponent ``s`` truncated to ranks 1..n."""
+    p = np.arange(1, n + 1, dtype=np.float64) ** (-s)
+    c = np.cumsum(p)
+    c /= c[-1]
+    return c
+
+
+def _zipf_draw(rng: np.random.Generator, cdf: np.ndarray, size: int) -> np.ndarray:
+    """0-based ranks drawn by inverse CDF."""
+    u = rng.random(size)
+    r = np.searchsorted(cdf, u, side="right")
+    np.minimum(r, len(cdf) - 1, out=r)
+    return r
+
+
+def _distinct_zipf_rows(rng, lengths: np.ndarray, cdf: np.ndarray,
+                        rank_to_col: np.ndarray | None) -> tuple[np.ndarray, np.ndarray]:
+    """Draw ``lengths[i]`` distinct Zipf columns for every row (collisions are
+    redrawn) and return (rowptr, sorted columns)."""
+    N = len(lengths)
+    rowptr = np.zeros(N + 1, dtype=np.int64)
+    np.cumsum(lengths, out=rowptr[1:])
+    nnz = int(rowptr[-1])
+    rows = np.repeat(np.arange(N, dtype=np.int64), lengths)
+    cols = _zipf_draw(rng, cdf, nnz).astype(np.int64)
+    Dn = len(cdf)
+    for _ in range(10_000):
+        key = rows * Dn + cols
+        order = np.argsort(key, kind="stable")
+        ks = key[order]
+        dup = np.zeros(nnz, dtype=bool)
+        dup[order[1:]] = ks[1:] == ks[:-1]
+        nd = int(dup.sum())
+        if nd == 0:
+            break
+        cols[dup] = _zipf_draw(rng, cdf, nd)
+    else:  # pragma: no cover
+        raise RuntimeError("could not make columns distinct")
+    if rank_to_col is not None:
+        cols = rank_to_col[cols]
+    key = rows * Dn + cols
+    key.sort()
+    cols = (key - rows * Dn).astype(np.int32)
+    return rowptr, cols
+
+
+def _teacher_score(rowptr, col, val, N, D, w_star, V_star) -> np.ndarray:
+    """Score of the planted teacher on every row (label synthesis only)."""
+    X = sp.csr_matrix((val.astype(np.float64), col, rowptr), shape=(N, D))
+    lin = X @ w_star
+    G = X @ V_star
+    X2 = X.copy()
+    X2.data **= 2
+    q = X2 @ (V_star ** 2).sum(axis=1)
+    return lin + 0.5 * ((G ** 2).sum(axis=1) - q)
+
+
+def _init_params(rng, D, K):
+    w0 = np.float32(0.0)
+    w = np.zeros(D, dtype=np.float32)
+    V = np.empty((D, K), dtype=np.float32)
+    step = max(1, (1 << 24) // max(K, 1))
+    for a in range(0, D, step):  # chunked: V can be several GB
+        b = min(D, a + step)
+        V[a:b] = rng.standard_normal((b - a, K), dtype=np.float32) * np.float32(0.01)
+    return w0, w, V
+
+
+def _scaled(n: int, scale: float, lo: int = 1) -> int:
+    return max(lo, int(round(n * scale)))
+
+
+# --------------------------------------------------------------------------
+# the five recipes
+# --------------------------------------------------------------------------
+
+def _cfg1(ss, scale):
+    rng_x, rng_t, rng_p = (np.random.Generator(np.random.PCG64(s)) for s in ss.spawn(3))
+    N, D, K, nz = _scaled(2000, scale, 8), 1000, 8, 10
+    pick = np.argpartition(rng_x.random((N, D)), nz, axis=1)[:, :nz]
+    pick.sort(axis=1)
+    col = pick.astype(np.int32).ravel()
+    rowptr = np.arange(N + 1, dtype=np.int64) * nz
+    val = rng_x.random(N * nz, dtype=np.float32)
+    w_star = rng_t.standard_normal(D)
+    V_star = rng_t.standard_normal((D, 8)) * 0.3
+    sc = _teacher_score(rowptr, col, val, N, D, w_star, V_star)
+    y = np.where(sc >= 0, 1.0, -1.0)
+    flip = rng_t.random(N) < 0.05
+    y[flip] = -y[flip]
+    w0, w, V = _init_params(rng_p, D, K)
+    return Workload("cfg1_tiny_binary", N, D, K, rowptr, col, val, y.astype(np.float32), w0, w, V,
+                    LOSS_LOGISTIC, 1e-4, 1e-4, 0.1, 1.0, 10, 4, 0,
+                    {"teacher_K": 8, "flip": 0.05})
+
+
+def _cfg2(ss, scale):
+    rng_x, rng_t, rng_p = (np.random.Generator(np.random.PCG64(s)) for s in ss.spawn(3))
+    N, D, K = _scaled(1_000_000, scale, 64), 64, 32
+    col = np.tile(np.arange(D, dtype=np.int32), N)
+    rowptr = np.arange(N + 1, dtype=np.int64) * D
+    val = rng_x.standard_normal(N * D, dtype=np.float32)
+    w_star = rng_t.standard_normal(D) / np.sqrt(D)
+    V_star = rng_t.standard_normal((D, 32)) * 0.3 / np.sqrt(D)
+    sc = _teacher_score(rowptr, col, val, N, D, w_star, V_star)
+    y = sc + 0.1 * rng_t.standard_normal(N)
+    w0, w, V = _init_params(rng_p, D, K)
+    return Workload("cfg2_dense_regression", N, D, K, rowptr, col, val, y.astype(np.float32), w0, w, V,
+                    LOSS_SQUARED, 1e-5, 1e-5, 0.05, 1.0 / N, 5, 16, 1,
+                    {"teacher_K": 32, "noise_std": 0.1})
+
+
+def _cfg3(ss, scale):
+    rng_x, rng_t, rng_p = (np.random.Generator(np.random.PCG64(s)) for s in ss.spawn(3))
+    N, D, K = _scaled(50_000, scale, 64), 20_000, 16
+    lengths = np.clip(rng_x.poisson(50, N), 1, D).astype(np.int64)
+    perm = rng_x.permutation(D).astype(np.int64)
+    rowptr, col = _distinct_zipf_rows(rng_x, lengths, _zipf_cdf(D, 1.0), perm)
+    nnz = int(rowptr[-1])
+    val = rng_x.lognormal(0.0, 1.0, nnz)
+    sq = np.add.reduceat(val * val, rowptr[:-1])
+    val = (val / np.sqrt(np.repeat(sq, lengths))).astype(np.float32)
+    w_star = rng_t.standard_normal(D)
+    V_star = rng_t.standard_normal((D, 16)) * 0.3
+    sc = _teacher_score(rowptr, col, val, N, D, w_star, V_star)
+    y = np.where(sc >= np.median(sc), 1.0, -1.0)
+    w0, w, V = _init_params(rng_p, D, K)
+    return Workload("cfg3_textlike_sparse", N, D, K, rowptr, col, val, y.astype(np.float32), w0, w, V,
+                    LOSS_LOGISTIC, 1e-4, 1e-4, 4.0, 1.0 / N, 10, 32, 1,
+                    {"teacher_K": 16, "zipf_s": 1.0})
+
+
+def _cfg4(ss, scale, threads=8):
+    N, D, K = _scaled(10_000_000, scale, 64), 1_000_000, 16
+    ND, NF, nz = 13, 26, 39
+    seeds = ss.spawn(NF + 3)
+    rng_d = np.random.Generator(np.random.PCG64(seeds[NF]))
+    rng_t = np.random.Generator(np.random.PCG64(seeds[NF + 1]))
+    rng_p = np.random.Generator(np.random.PCG64(seeds[NF + 2]))
+    col = np.empty((N, nz), dtype=np.int32)
+    val = np.ones((N, nz), dtype=np.float32)
+    col[:, :ND] = np.arange(ND, dtype=np.int32)
+    val[:, :ND] = np.log1p(rng_d.poisson(3.0, (N, ND))).astype(np.float32)
+    span = D - ND
+    starts = [ND + (f * span) // NF for f in range(NF + 1)]
+
+    def fill(f):
+        rng = np.random.Generator(np.random.PCG64(seeds[f]))
+        width = starts[f + 1] - starts[f]
+        col[:, ND + f] = starts[f] + _zipf_draw(rng, _zipf_cdf(width, 1.1), N)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(fill, range(NF)))
+    rowptr = np.arange(N + 1, dtype=np.int64) * nz
+    col = col.ravel()
+    val = val.ravel()
+    w_star = rng_t.standard_normal(D)
+    V_star = rng_t.standard_normal((D, 8)) * 0.3
+    sc = _teacher_score(rowptr, col, val, N, D, w_star, V_star)
+    thr = np.quantile(sc, 0.97)
+    y = np.where(sc > thr, 1.0, -1.0)
+    w0, w, V = _init_params(rng_p, D, K)
+    return Workload("cfg4_click_onehot", N, D, K, rowptr, col, val, y.astype(np.float32), w0, w, V,
+                    LOSS_LOGISTIC, 1e-6, 1e-6, 0.02, 1.0 / N, 3, 64, 1,
+                    {"teacher_K": 8, "positive_rate": 0.03, "zipf_s": 1.1})
+
+
+def _cfg5(ss, scale):
+    rng_x, rng_t, rng_p = (np.random.Generator(np.random.PCG64(s)) for s in ss.spawn(3))
+    N, D, K = _scaled(2_000_000, scale, 64), 20_000_000, 64
+    if scale < 1.0:  # keep V proportionally small for reduced runs
+        D = max(4096, int(round(D * scale)))
+    lengths = rng_x.integers(50, 151, N).astype(np.int64)
+    rowptr, col = _distinct_zipf_rows(rng_x, lengths, _zipf_cdf(D, 1.05), None)
+    val = np.ones(int(rowptr[-1]), dtype=np.float32)
+    w_star = rng_t.standard_normal(D) * 0.3
+    V_star = rng_t.standard_normal((D, 8)) * 0.1
+    sc = _teacher_score(rowptr, col, val, N, D, w_star, V_star)
+    y = np.where(sc >= np.median(sc), 1.0, -1.0)
+    w0, w, V = _init_params(rng_p, D, K)
+    return Workload("cfg5_hashed_stress", N, D, K, rowptr, col, val, y.astype(np.float32), w0, w, V,
+                    LOSS_LOGISTIC, 1e-6, 1e-6, 0.05, 1.0 / N, 2, 128, 1,
+                    {"teacher_K": 8, "zipf_s": 1.05})
+
+
+_RECIPES = {1: _cfg1, 2: _cfg2, 3: _cfg3, 4: _cfg4, 5: _cfg5}
+
+
+def make_config(index: int, seed: int | None = None, scale: float = 1.0) -> Workload:
+    """Build workload ``index`` (1..5).  ``scale`` shrinks the row count (and,
+    for workload 5, the column count) for quick checks; 1.0 is the full shape."""
+    if index not in _RECIPES:
+        raise ValueError("workload index must be 1..5")
+    ss = np.random.SeedSequence(13940 + index if seed is None else seed)
+    wl = _RECIPES[index](ss, float(scale))
+    wl.notes["scale"] = float(scale)
+    return wl
+
+
+def random_csr(rng: np.random.Generator, N: int, D: int, density: float,
+               empty_rows: bool = True) -> tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Small random CSR matrix with N(0,1) values for unit tests (rows may be
+    empty, columns may be empty)."""
+    mask = rng.random((N, D)) < density
+    if not empty_rows:
+        mask[np.arange(N), rng.integers(0, D, N)] = True
+    rowptr = np.zeros(N + 1, dtype=np.int64)
+    np.cumsum(mask.sum(axis=1), out=rowptr[1:])
+    col = np.nonzero(mask)[1].astype(np.int32)
+    val = rng.standard_normal(len(col)).astype(np.float32)
+    return rowptr, col, val

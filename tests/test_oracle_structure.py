@@ -1,0 +1,243 @@
+"""Pins for the oracle's integer structures (transpose, partition, per-stratum
+matrices) and for its stratified epoch."""
+import ctypes
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+from oracle import fm_oracle as O
+from paper_2004_13940_amd.workloads import random_csr
+
+
+def _rand_problem(seed, N, D, K, density, loss=O.LOSS_LOGISTIC):
+    rng = np.random.default_rng(seed)
+    rowptr, col, val = random_csr(rng, N, D, density)
+    X = O.make_matrix(N, D, rowptr, col, val)
+    Xs = sp.csr_matrix((val.astype(np.float64), col, rowptr), shape=(N, D))
+    y = np.where(rng.random(N) < 0.5, 1.0, -1.0) if loss == O.LOSS_LOGISTIC else rng.standard_normal(N)
+    w = rng.standard_normal(D) * 0.1
+    V = rng.standard_normal((D, K)) * 0.1
+    return rng, X, Xs, y, w, V
+
+
+def test_transpose_matches_dense_and_round_trips():
+    rng = np.random.default_rng(0)
+    N, D = 23, 17
+    rowptr, col, val = random_csr(rng, N, D, 0.3)
+    Xd = sp.csr_matrix((val.astype(np.float64), col, rowptr), shape=(N, D)).toarray()
+    colptr, row, cval = O.csr_to_csc(N, D, rowptr, col, val)
+    # brute force: walk the dense transpose
+    want_row, want_val, want_ptr = [], [], [0]
+    for j in range(D):
+        for i in range(N):
+            if Xd[i, j] != 0.0:
+                want_row.append(i)
+                want_val.append(Xd[i, j])
+        want_ptr.append(len(want_row))
+    np.testing.assert_array_equal(colptr, want_ptr)
+    np.testing.assert_array_equal(row, want_row)
+    np.testing.assert_array_equal(cval, want_val)
+    # transposing twice gives the input back
+    rp2, c2, v2 = O.csr_to_csc(D, N, colptr, row, cval)
+    np.testing.assert_array_equal(rp2, rowptr)
+    np.testing.assert_array_equal(c2, col)
+    np.testing.assert_array_equal(v2, val.astype(np.float64))
+    # rows ascend strictly inside every column
+    for j in range(D):
+        assert np.all(np.diff(row[colptr[j]:colptr[j + 1]]) > 0)
+
+
+@pytest.mark.parametrize("n,P", [(10, 3), (7, 7), (5, 8), (1000, 64), (1, 1), (20_000_000, 128)])
+def test_block_bounds_floor_split(n, P):
+    b = O.block_bounds(n, P)
+    assert b[0] == 0 and b[-1] == n and np.all(np.diff(b) >= 0)
+    for k in range(P + 1):
+        assert int(b[k]) == (k * n) // P  # python integers: exact at any size
+    assert np.diff(b).max() - np.diff(b).min() <= 1
+
+
+def test_block_bounds_do_not_overflow_64_bits():
+    n, P = (1 << 62) + 12345, 1000
+    lib = O._L()
+    for k in (1, 499, 999, 1000):
+        assert lib.oracle_block_bound(ctypes.c_int64(n), ctypes.c_int64(P), ctypes.c_int64(k)) == (k * n) // P
+
+
+@pytest.mark.parametrize("N,D,P", [(30, 20, 4), (17, 9, 5), (6, 3, 8), (12, 12, 1)])
+def test_cells_partition_every_entry_once_and_stratum_matrices(N, D, P):
+    rng = np.random.default_rng(N * 100 + D)
+    rowptr, col, val = random_csr(rng, N, D, 0.4)
+    X = O.make_matrix(N, D, rowptr, col, val)
+    Xd = sp.csr_matrix((val.astype(np.float64), col, rowptr), shape=(N, D)).toarray()
+    stored = sp.csr_matrix((np.ones(len(col)), col, rowptr), shape=(N, D)).toarray() > 0
+    rb, cb = [(k * N) // P for k in range(P + 1)], [(k * D) // P for k in range(P + 1)]
+    # brute-force cell table from dense masks
+    want = np.zeros((P, P), np.int64)
+    for p in range(P):
+        for q in range(P):
+            want[p, q] = stored[rb[p]:rb[p + 1], cb[q]:cb[q + 1]].sum()
+    got = O.cell_nnz(X, P)
+    np.testing.assert_array_equal(got, want)
+    assert got.sum() == len(col)
+    total = np.zeros((N, D))
+    count = np.zeros((N, D), np.int64)
+    for s in range(P):
+        mask = np.zeros((N, D), bool)
+        for p, q in O.stratum_cells(P, s):
+            mask[rb[p]:rb[p + 1], cb[q]:cb[q + 1]] = True
+        rp, c, v = O.stratum_csr(X, P, s)
+        S = sp.csr_matrix((v, c, rp), shape=(N, D))
+        np.testing.assert_array_equal(S.toarray(), Xd * mask)
+        assert len(c) == (stored & mask).sum()
+        cp, r, cv = O.stratum_csc(X, P, s)
+        T = sp.csc_matrix((cv, r, cp), shape=(N, D))
+        np.testing.assert_array_equal(T.toarray(), Xd * mask)
+        for j in range(D):
+            assert np.all(np.diff(r[cp[j]:cp[j + 1]]) > 0)
+        total += S.toarray()
+        count += mask
+    np.testing.assert_array_equal(total, Xd)
+    assert np.all(count == 1)  # the P strata tile the whole grid exactly once
+
+
+def test_ring_schedule_visits_each_cell_once_and_starts_on_diagonal():
+    P = 5
+    seen = set()
+    for s in range(P):
+        cells = O.stratum_cells(P, s)
+        assert sorted(p for p, _ in cells) == list(range(P))
+        assert sorted(q for _, q in cells) == list(range(P))  # disjoint rows and columns
+        seen.update(cells)
+    assert len(seen) == P * P
+    assert O.stratum_cells(P, 0) == [(p, p) for p in range(P)]
+
+
+@pytest.mark.parametrize("loss", [O.LOSS_SQUARED, O.LOSS_LOGISTIC])
+def test_single_block_stratified_epoch_is_full_gradient_epoch(loss):
+    rng, X, Xs, y, w, V = _rand_problem(21, 40, 18, 3, 0.3, loss)
+    kw = dict(loss=loss, s=1.0 / X.N, lambda_w=0.01, lambda_v=0.02, eta=0.3)
+    w0a, wa, Va, _ = O.full_epoch(X, y, 0.1, w, V, **kw)
+    w0b, wb, Vb, _, aux = O.stratified_epoch(X, y, 0.1, w, V, P=1, **kw)
+    np.testing.assert_allclose(wb, wa, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(Vb, Va, rtol=1e-13, atol=1e-15)
+    # the bias step of the stratified epoch uses the refreshed aggregates, so compare
+    # with the multiplier at the updated (w,V) and the old bias
+    _, _, _, yh = O.forward(X, 0.1, wa, Va)
+    _, r = O.loss_multiplier(loss, kw["s"], yh, y)
+    np.testing.assert_allclose(w0b, 0.1 - kw["eta"] * r.sum(), rtol=1e-12)
+    # with one block the refreshed aggregates are exact
+    np.testing.assert_allclose(aux["G"], Xs @ Vb, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(aux["a"], Xs @ wb, rtol=1e-12, atol=1e-14)
+
+
+def test_cell_order_inside_a_stratum_does_not_matter():
+    rng, X, Xs, y, w, V = _rand_problem(22, 50, 24, 4, 0.3)
+    P = 4
+    kw = dict(P=P, loss=O.LOSS_LOGISTIC, s=1.0, lambda_w=1e-3, lambda_v=1e-3, eta=0.05)
+    for all_rows in (False, True):
+        base = O.stratified_epoch(X, y, 0.0, w, V, refresh_all_rows=all_rows, **kw)
+        order = [list(rng.permutation(P)) for _ in range(P)]
+        perm = O.stratified_epoch(X, y, 0.0, w, V, refresh_all_rows=all_rows, cell_order=order, **kw)
+        assert base[0] == perm[0]
+        np.testing.assert_array_equal(base[1], perm[1])
+        np.testing.assert_array_equal(base[2], perm[2])
+        for k in ("a", "G", "q"):
+            np.testing.assert_array_equal(base[4][k], perm[4][k])
+
+
+def test_exact_refresh_keeps_aggregates_equal_to_fresh_recomputation():
+    rng, X, Xs, y, w, V = _rand_problem(23, 45, 20, 3, 0.35)
+    X2 = Xs.multiply(Xs)
+    checked = []
+
+    def check(s, st):
+        np.testing.assert_allclose(st["G"], Xs @ st["V"], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(st["a"], Xs @ st["w"], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(st["q"], X2 @ (st["V"] ** 2).sum(axis=1), rtol=1e-11, atol=1e-13)
+        checked.append(s)
+
+    O.stratified_epoch(X, y, 0.0, w, V, P=5, loss=O.LOSS_LOGISTIC, s=1.0, lambda_w=1e-3, lambda_v=1e-3,
+                       eta=0.05, refresh_all_rows=True, on_stratum=check)
+    assert checked == list(range(5))
+
+
+def test_own_row_refresh_tracks_exactly_the_deltas_a_row_block_applied():
+    """With the paper's local refresh a row block's aggregates hold the epoch-start
+    parameters plus the changes that this row block itself made; changes made by
+    other row blocks are missing until the next re-computation."""
+    rng, X, Xs, y, w, V = _rand_problem(24, 48, 21, 3, 0.35)
+    P, N, D = 4, X.N, X.D
+    rb, cb = [(k * N) // P for k in range(P + 1)], [(k * D) // P for k in range(P + 1)]
+    own_dV = [np.zeros_like(V) for _ in range(P)]
+    own_dw = [np.zeros_like(w) for _ in range(P)]
+    stale_seen = []
+
+    def check(s, st):
+        for p, q in st["cells"]:
+            own_dV[p][cb[q]:cb[q + 1]] += st["dV"][cb[q]:cb[q + 1]]
+            own_dw[p][cb[q]:cb[q + 1]] += st["dw"][cb[q]:cb[q + 1]]
+        for p in range(P):
+            I = slice(rb[p], rb[p + 1])
+            np.testing.assert_allclose(st["G"][I], (Xs @ (V + own_dV[p]))[I], rtol=1e-11, atol=1e-13)
+            np.testing.assert_allclose(st["a"][I], (Xs @ (w + own_dw[p]))[I], rtol=1e-11, atol=1e-13)
+        stale_seen.append(np.abs(st["G"] - Xs @ st["V"]).max())
+
+    out = O.stratified_epoch(X, y, 0.0, w, V, P=P, loss=O.LOSS_LOGISTIC, s=1.0, lambda_w=1e-3,
+                             lambda_v=1e-3, eta=0.05, on_stratum=check)
+    assert max(stale_seen) > 1e-6  # the staleness is real
+    # every parameter moved by the sum of the deltas of the P row blocks
+    np.testing.assert_allclose(out[2], V + sum(own_dV), rtol=1e-12, atol=1e-14)
+
+
+def test_cell_gradients_sum_to_the_full_gradient_at_frozen_parameters():
+    rng, X, Xs, y, w, V = _rand_problem(25, 36, 16, 3, 0.4)
+    P, N, D, K = 4, X.N, X.D, V.shape[1]
+    s, lw, lv = 0.5, 0.02, 0.03
+    a, G, q, yhat = O.forward(X, 0.2, w, V)
+    _, r = O.loss_multiplier(O.LOSS_LOGISTIC, s, yhat, y)
+    gw0, gw, gV = O.gradient(X, r, G, w, V, lw, lv)
+    rb, cb = O.block_bounds(N, P), O.block_bounds(D, P)
+    acc_w, acc_V = np.zeros(D), np.zeros((D, K))
+    L = O._L()
+    f64, i64, i32, p_ = O._f64, O._i64, O._i32, O._p
+    for p in range(P):
+        for qb in range(P):
+            wc, Vc, rc = w.copy(), V.copy(), np.zeros(N)
+            dw, dV, dn = np.zeros(D), np.zeros((D, K)), np.zeros(D)
+            rho = (rb[p + 1] - rb[p]) / N
+            # eta = 1 at frozen copies: the recorded delta is minus the cell gradient
+            L.oracle_cell_update(i32(K), i32(O.LOSS_LOGISTIC), f64(s), f64(1.0), f64(rho), f64(lw), f64(lv),
+                                 i64(rb[p]), i64(rb[p + 1]), i64(cb[qb]), i64(cb[qb + 1]), p_(X.colptr),
+                                 p_(X.row), p_(X.cval), p_(y), f64(0.2), p_(a), p_(G), p_(q), p_(rc),
+                                 p_(wc), p_(Vc), p_(dw), p_(dV), p_(dn))
+            acc_w -= dw
+            acc_V -= dV
+            np.testing.assert_allclose(dn[cb[qb]:cb[qb + 1]],
+                                       (Vc ** 2).sum(1)[cb[qb]:cb[qb + 1]] - (V ** 2).sum(1)[cb[qb]:cb[qb + 1]],
+                                       rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(acc_w, gw, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(acc_V, gV, rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("all_rows", [False, True])
+def test_stratified_objective_decreases_for_small_step(all_rows):
+    rng, X, Xs, y, w, V = _rand_problem(26, 80, 30, 4, 0.25)
+    w0, prev = 0.0, np.inf
+    for _ in range(8):
+        w0, w, V, obj, _ = O.stratified_epoch(X, y, w0, w, V, P=4, loss=O.LOSS_LOGISTIC, s=1.0 / X.N,
+                                              lambda_w=1e-3, lambda_v=1e-3, eta=0.2,
+                                              refresh_all_rows=all_rows)
+        assert sum(obj) < prev
+        prev = sum(obj)
+
+
+def test_full_regulariser_per_cell_differs_only_by_the_regulariser_share():
+    rng, X, Xs, y, w, V = _rand_problem(27, 40, 16, 2, 0.3)
+    kw = dict(P=4, loss=O.LOSS_SQUARED, s=1.0 / X.N, eta=0.1)
+    a = O.stratified_epoch(X, y, 0.0, w, V, lambda_w=0.0, lambda_v=0.0, reg_share=True, **kw)
+    b = O.stratified_epoch(X, y, 0.0, w, V, lambda_w=0.0, lambda_v=0.0, reg_share=False, **kw)
+    np.testing.assert_array_equal(a[1], b[1])  # no regulariser: identical
+    c = O.stratified_epoch(X, y, 0.0, w, V, lambda_w=0.5, lambda_v=0.5, reg_share=False, **kw)
+    d = O.stratified_epoch(X, y, 0.0, w, V, lambda_w=0.5, lambda_v=0.5, reg_share=True, **kw)
+    assert np.linalg.norm(c[1]) < np.linalg.norm(d[1])  # full lambda per cell shrinks harder
