@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the FM pass on one MI355X.
+
+A step is one full-gradient epoch (forward, multipliers, gradient, update:
+fm_sgd_epoch) over the click-style workload (config 4: N=1e7, D=1e6, 39 nnz/row,
+K=16), inputs resident in HBM.  Prints ONE JSON line with the throughput in
+nonzeros/s, the roofline figures of the dominant kernel (timed with HIP events on
+the launch stream) and the oracle's CPU baseline on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(N, D, K, nnz, nnz_long, items, nlong):
+    """Bytes each kernel must move if every array is streamed once and every gather is
+    served from cache (fp32 values, int32 indices, int64 pointers)."""
+    fwd = 8 * nnz + 8 * (N + 1) + 4 * N + 4 * D * (K + 1) + 4 * N * (K + 1)
+    aux = 4 * N * (K + 1)                       # compulsory read of r and G by the column side
+    short = nnz - nnz_long
+    cols = 8 * short + 8 * (D + 1) + aux * (short / max(nnz, 1)) + 8 * (D - nlong) * (K + 1)
+    cols_long = 8 * nnz_long + 16 * items + aux * (nnz_long / max(nnz, 1)) + 4 * items * (K + 2)
+    cols_finish = 4 * items * (K + 2) + 12 * nlong + 8 * nlong * (K + 1)
+    return {"rows_forward": fwd, "cols": cols, "cols_long": cols_long, "cols_finish": cols_finish,
+            "epoch": 16 * nnz + 8 * N * (K + 1) + 12 * D * (K + 1) + 12 * N + 8 * D}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=4)
+    ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--cpu-rows", type=int, default=2_000_000, help="rows of the workload the oracle is timed on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stratified", action="store_true", help="also time fm_stratified_epoch (reported in extra)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); nothing here uses a second device")
+
+    import numpy as np
+    import torch
+    from paper_2004_13940_amd import binding as B
+    from paper_2004_13940_amd.workloads import make_config
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    wl = make_config(args.workload, scale=args.scale)
+    t_gen = time.time() - t0
+    print(f"[bench] workload {wl.name}: N={wl.N} D={wl.D} nnz={wl.nnz} K={wl.K} generated in {t_gen:.1f}s",
+          file=sys.stderr, flush=True)
+    t0 = time.time()
+    m = B.Matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
+    t_up = time.time() - t0
+    t0 = time.time()
+    m.fm_build_csc()
+    torch.cuda.synchronize()
+    t_csc = time.time() - t0
+    print(f"[bench] upload {t_up:.2f}s, CSC build {t_csc:.2f}s", file=sys.stderr, flush=True)
+
+    p = B.make_params(wl.K, wl.loss, wl.lambda_w, wl.lambda_v, wl.eta, wl.loss_scale, wl.update_w0)
+    w0 = torch.tensor([float(wl.w0)], device="cuda")
+    w = torch.from_numpy(wl.w).cuda()
+    V = torch.from_numpy(wl.V).cuda().reshape(-1)
+    y = torch.from_numpy(wl.y).cuda()
+
+    for _ in range(args.warmup):
+        m.fm_sgd_epoch(p, y, w0, w, V)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        m.fm_sgd_epoch(p, y, w0, w, V)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    value = wl.nnz * args.steps / dt
+    print(f"[bench] {ms_per_step:.3f} ms/epoch, {value:.4g} nnz/s", file=sys.stderr, flush=True)
+
+    # per-kernel durations from HIP events on the launch stream, over the same number of steps
+    m.fm_profile_enable(True)
+    for _ in range(args.steps):
+        m.fm_sgd_epoch(p, y, w0, w, V)
+    prof = m.fm_profile_read()
+    m.fm_profile_enable(False)
+    counts = np.bincount(wl.col, minlength=wl.D)
+    long_mask = counts > 512
+    nnz_long = int(counts[long_mask].sum())
+    nlong = int(long_mask.sum())
+    items = int(((counts[long_mask] + 511) // 512).sum())
+    ab = algorithmic_bytes(wl.N, wl.D, wl.K, wl.nnz, nnz_long, items, nlong)
+    kern = {k: {"launches": n, "avg_ms": ms / n} for k, (n, ms) in prof.items() if n > 0}
+    dominant = max(kern, key=lambda k: kern[k]["avg_ms"] * kern[k]["launches"])
+    dom_ms = kern[dominant]["avg_ms"]
+    achieved = ab[dominant] / (dom_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{wl.name}.json")
+    if args.scale == 1.0 and os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(dominant, {}).get("hbm_bytes_per_launch")
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "algorithmic_bytes_per_launch": ab[dominant], "avg_launch_ms": dom_ms,
+                "epoch_algorithmic_GBs": ab["epoch"] / (ms_per_step * 1e-3) / 1e9,
+                "epoch_frac": ab["epoch"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "kernels": {k: {"avg_ms": v["avg_ms"], "algorithmic_GBs": ab[k] / (v["avg_ms"] * 1e-3) / 1e9}
+                            for k, v in kern.items() if k in ab}}
+
+    extra = {"gen_s": t_gen, "upload_s": t_up, "csc_build_s": t_csc, "sha256": wl.sha256()[:16]}
+    if args.stratified:
+        m.fm_partition(wl.P)
+        m.fm_stratified_epoch(p, y, w0, w, V)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        m.fm_stratified_epoch(p, y, w0, w, V)
+        torch.cuda.synchronize()
+        ts = time.perf_counter() - t0
+        extra["stratified_ms_per_epoch"] = 1e3 * ts
+        extra["stratified_nnz_per_s"] = wl.nnz / ts
+        extra["P"] = wl.P
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import fm_oracle as O
+        n = min(wl.N, args.cpu_rows)
+        e = int(wl.rowptr[n])
+        X = O.make_matrix(n, wl.D, wl.rowptr[:n + 1], wl.col[:e], wl.val[:e])
+        kw = dict(loss=wl.loss, s=wl.loss_scale, lambda_w=wl.lambda_w, lambda_v=wl.lambda_v, eta=wl.eta,
+                  update_w0=bool(wl.update_w0))
+        ow0, ow, oV = float(wl.w0), wl.w, wl.V
+        reps = 2
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            ow0, ow, oV, _ = O.full_epoch(X, wl.y[:n], ow0, ow, oV, **kw)
+        tc = (time.perf_counter() - t0) / reps
+        cpu = {"value": e / tc, "unit": "nnz/s", "cores": O.threads(), "kind": "oracle",
+               "sample": f"first {n} rows ({e} nnz) of {wl.name}, {reps} full-gradient epochs, fp64, {tc:.2f} s/epoch"}
+
+    out = {"metric": "FM epoch (fwd+grad+update) nonzeros/sec at K=16", "value": value, "unit": "nnz/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{wl.name} scale={args.scale}", "N": wl.N, "D": wl.D, "nnz": wl.nnz, "K": wl.K,
+                      "loss": "logistic" if wl.loss == 1 else "squared"},
+           "roofline": roofline, "cpu_baseline": cpu, "extra": extra}
+    print(json.dumps(out))
+    m.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,170 @@
+/*
+ * fm.h -- C ABI of the MI355X factorization-machine (FM) pass of DS-FACTO.
+ *
+ * One GPU, gfx950.  Plain pointers and sizes only.  "HOST" marks host memory,
+ * "DEVICE" marks device memory owned by the caller (fp32, contiguous).  The
+ * library owns only what hangs off an fm_matrix handle.
+ *
+ * Notation (paper symbol in quotes where it differs):
+ *   X        N x D sparse data matrix, rows are examples        (Section 3)
+ *   w0,w,V   bias, linear weights [D], latent factors [D x K] row-major (Section 3.2)
+ *   a = X w                  linear aggregate                    (2nd term of eq. fm_model2)
+ *   G = X V  [N x K]         latent aggregate, the paper's "a_ik" (eq. compute_a_jk)
+ *   q_i = sum_j x_ij^2 |v_j|^2   the subtracted square term      (eq. fm_model2)
+ *   r [N]                    loss multiplier, the paper's "G_i"  (cases after eq. updates_v)
+ *
+ * Every function returns FM_OK (0) or a negative fm_status; none throws, aborts
+ * or prints.  fm_last_error() gives a message for the last failure on a handle.
+ * Work is enqueued on the given hipStream_t (passed as void*; NULL = default
+ * stream); only functions with HOST outputs wait for the stream.  One handle
+ * must be used by one thread at a time.
+ */
+#ifndef FM_MI355X_H
+#define FM_MI355X_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FM_OK = 0,
+    FM_EINVAL = -1,    /* bad argument (null pointer, K out of range, ...) */
+    FM_ENOMEM = -2,    /* device or host allocation failed */
+    FM_EUNSORTED = -3, /* rowptr not monotone, or columns not strictly ascending in a row */
+    FM_ERANGE = -4,    /* index outside [0,D), sizes outside the supported range */
+    FM_ESTATE = -5,    /* call needs a structure that was not built yet */
+    FM_EHIP = -6       /* a HIP runtime call failed */
+} fm_status;
+
+typedef enum { FM_LOSS_SQUARED = 0, FM_LOSS_LOGISTIC = 1 } fm_loss;
+
+typedef struct fm_matrix fm_matrix; /* opaque: device CSR, CSC, stratum index, aggregates, workspace */
+
+/* Hyper-parameters of Table "Notations" (K, lambda_w, lambda_v, eta) and the loss.
+ *   loss_scale s multiplies every r_i and the data term of the objective:
+ *     s = 1   gives the update equations as printed (eqs. updates_w, updates_v),
+ *     s = 1/N gives the normalised objective (eq. fm_obj).
+ *   K must be 1..64, or a multiple of 4 up to 256. */
+typedef struct {
+    int32_t K;
+    int32_t loss;              /* fm_loss */
+    float lambda_w, lambda_v;  /* regularisers of w and V */
+    float eta;                 /* step size */
+    float loss_scale;          /* s */
+    int32_t update_w0;         /* 0/1: take the bias step w0 -= eta * sum_i r_i */
+    int32_t reg_full_per_cell; /* stratified epoch: 0 = a cell step applies the share |I|/N of
+                                  lambda (one epoch's worth per epoch); 1 = full lambda each step */
+    int32_t refresh_all_rows;  /* stratified epoch: 0 = a cell refreshes only its own rows' aggregates
+                                  (Section 4.2: other row blocks stay stale until the re-computation);
+                                  1 = every stratum ends with an exact refresh of all rows */
+} fm_params;
+
+/* ---- building the data structures (Section 3: X is read by rows for the score,
+ *      by columns for the update of w_j, v_j; Section 4.3: double partition) ---- */
+
+/* Validate a HOST CSR matrix and copy it to the device.  rowptr[0]=0, rowptr[N]=nnz,
+ * monotone; inside a row columns strictly ascending and in [0,D).  Stored zeros are
+ * legal.  N, D < 2^31, nnz < 2^32.  *out receives a new handle (free with fm_destroy). */
+int fm_build_csr(int64_t N, int64_t D, int64_t nnz, const int64_t* rowptr /*HOST N+1*/,
+                 const int32_t* col /*HOST nnz*/, const float* val /*HOST nnz*/,
+                 void* hip_stream, fm_matrix** out);
+
+/* Device transpose into CSC: rows ascending inside each column (stable). */
+int fm_build_csc(fm_matrix* m, void* hip_stream);
+
+/* Double partition into P contiguous row blocks and P contiguous column blocks,
+ * block b of n items = [floor(b n/P), floor((b+1) n/P)) in 64-bit arithmetic, and the
+ * ring schedule: stratum s holds the P disjoint cells (p, (p+s) mod P), stratum 0 on
+ * the diagonal (Section 4.2, figure of the communication pattern).  Builds, for every
+ * stratum, the CSR and the CSC of the matrix restricted to that stratum's cells.
+ * Needs fm_build_csc.  1 <= P <= 4096. */
+int fm_partition(fm_matrix* m, int32_t P, void* hip_stream);
+
+/* Copies for bit-exact checks (HOST outputs, sized by the caller). */
+int fm_get_csc(const fm_matrix* m, int64_t* colptr /*D+1*/, int32_t* row /*nnz*/, float* val /*nnz*/);
+int fm_get_block_index(const fm_matrix* m, int64_t* row_bounds /*P+1*/, int64_t* col_bounds /*P+1*/,
+                       int64_t* cell_nnz /*P*P, [p*P+q]*/);
+int fm_get_stratum_nnz(const fm_matrix* m, int32_t s, int64_t* nnz_out /*HOST 1*/);
+int fm_get_stratum_csr(const fm_matrix* m, int32_t s, int64_t* rowptr /*N+1, starts at 0*/,
+                       int32_t* col, float* val);
+int fm_get_stratum_csc(const fm_matrix* m, int32_t s, int64_t* colptr /*D+1, starts at 0*/,
+                       int32_t* row, float* val);
+
+/* ---- the pass ---- */
+
+/* Steps 1-3: aggregates, predictions (eq. fm_model2), loss and multipliers.
+ *   yhat_i = w0 + a_i + 1/2 (sum_k G_ik^2 - q_i)
+ *   squared : l = 1/2 (yhat-y)^2,        r = s (yhat - y)
+ *   logistic: l = log(1+exp(-y yhat)),   r = -s y / (1+exp(y yhat)),  y in {-1,+1} (not checked)
+ * Any DEVICE output may be NULL.  r and loss_sum need y.  loss_sum (HOST, 1 double)
+ * receives sum_i l_i (unscaled) and makes the call wait for the stream. */
+int fm_forward(fm_matrix* m, const fm_params* p, const float* y /*DEVICE N, nullable*/,
+               const float* w0 /*DEVICE 1*/, const float* w /*DEVICE D*/, const float* V /*DEVICE D*K*/,
+               float* yhat /*DEVICE N*/, float* a /*DEVICE N*/, float* G /*DEVICE N*K*/,
+               float* q /*DEVICE N*/, float* r /*DEVICE N*/, double* loss_sum /*HOST*/,
+               void* hip_stream);
+
+/* Step 4: gradients of  s sum_i l_i + lambda_w/2 |w|^2 + lambda_v/2 |V|^2  from given r, G
+ * (eqs. updates_w0/updates_w/updates_v, regulariser with the sign of gradient descent):
+ *   grad_w0 = sum_i r_i
+ *   grad_w  = X^T r + lambda_w w
+ *   grad_V  = X^T (r . G) - diag((X o X)^T r) V + lambda_v V
+ * Atomic-free pass over the CSC copy; needs fm_build_csc.  Outputs may be NULL. */
+int fm_gradient(fm_matrix* m, const fm_params* p, const float* r /*DEVICE N*/, const float* G /*DEVICE N*K*/,
+                const float* w /*DEVICE D*/, const float* V /*DEVICE D*K*/,
+                float* grad_w0 /*DEVICE 1*/, float* grad_w /*DEVICE D*/, float* grad_V /*DEVICE D*K*/,
+                void* hip_stream);
+
+/* One full-gradient step (steps 1-5): forward, multipliers, gradient, and
+ * (w0, w, V) -= eta * gradient in place, the gradient never being stored.
+ * objective (HOST, 2 doubles, nullable): data term s sum_i l_i and regulariser
+ * lambda_w/2 |w|^2 + lambda_v/2 |V|^2, both at the parameters the call STARTED from;
+ * a non-NULL objective makes the call wait for the stream. */
+int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y /*DEVICE N*/,
+                 float* w0 /*DEVICE 1*/, float* w /*DEVICE D*/, float* V /*DEVICE D*K*/,
+                 double* objective /*HOST 2*/, void* hip_stream);
+
+/* One doubly-separable stratified epoch (Sections 4.2-4.3, synchronous ring):
+ *   aggregates a, G, q and multipliers r recomputed from scratch (the re-computation pass);
+ *   for s = 0..P-1, all P cells (I_p, J_(p+s) mod P) of the stratum concurrently:
+ *       block gradient of the cell's columns over the cell's rows, from r and G as they stand,
+ *       step on w_J, V_J (regulariser share per fm_params), deltas kept,
+ *       incremental refresh a_I += X_IJ dw_J, G_I += X_IJ dV_J, q_I likewise, r_I recomputed;
+ *   bias step from the multipliers as they stand (if update_w0).
+ * objective (HOST 2, nullable): data term and regulariser from a fresh forward at the
+ * FINAL parameters (costs one more pass).  Needs fm_partition. */
+int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float* y, float* w0, float* w, float* V,
+                        double* objective /*HOST 2*/, void* hip_stream);
+
+/* The three parts of fm_stratified_epoch, for callers that interleave their own work
+ * (or inspect the aggregates) between strata: begin = re-computation pass, step = one
+ * stratum s, end = bias step. */
+int fm_stratified_begin(fm_matrix* m, const fm_params* p, const float* y, const float* w0, const float* w,
+                        const float* V, void* hip_stream);
+int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const float* y, const float* w0,
+                       float* w, float* V, void* hip_stream);
+int fm_stratified_end(fm_matrix* m, const fm_params* p, float* w0, void* hip_stream);
+
+/* Copy the aggregates the handle holds (valid after fm_sgd_epoch or any stratified call)
+ * into caller DEVICE arrays; any may be NULL. */
+int fm_get_aux(const fm_matrix* m, float* a /*N*/, float* G /*N*K*/, float* q /*N*/, float* r /*N*/,
+               void* hip_stream);
+
+/* Per-kernel timing with HIP events on the launch stream.  While enabled, every kernel
+ * launch of this handle is bracketed by two events.  fm_profile_read waits for the
+ * stream, then reports for kernel id k (0 <= k < fm_profile_kernels()) the number of
+ * launches and their total time in milliseconds since the last reset, and resets. */
+int fm_profile_enable(fm_matrix* m, int32_t on);
+int fm_profile_kernels(void);
+const char* fm_profile_kernel_name(int32_t k);
+int fm_profile_read(fm_matrix* m, int64_t* launches /*HOST nk*/, double* total_ms /*HOST nk*/);
+
+int fm_destroy(fm_matrix* m);
+const char* fm_last_error(const fm_matrix* m); /* m may be NULL: last build error of this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FM_MI355X_H */

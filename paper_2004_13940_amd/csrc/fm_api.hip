@@ -1,0 +1,561 @@
+// C-ABI entry points and the epoch drivers.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+
+#include "fm_internal.h"
+
+static thread_local std::string g_build_error;
+
+int fm_fail(fm_matrix* m, int code, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    if (m != nullptr) m->err = buf; else g_build_error = buf;
+    return code;
+}
+
+int fm_dev_alloc(fm_matrix* m, void** p, size_t bytes)
+{
+    *p = nullptr;
+    if (bytes == 0) bytes = 16;
+    hipError_t e = hipMalloc(p, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fm_fail(m, FM_ENOMEM, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+    }
+    m->allocs.push_back(*p);
+    return FM_OK;
+}
+
+void fm_dev_free(fm_matrix* m, void* p)
+{
+    if (p == nullptr) return;
+    auto it = std::find(m->allocs.begin(), m->allocs.end(), p);
+    if (it != m->allocs.end()) m->allocs.erase(it);
+    (void)hipFree(p);
+}
+
+ProfScope::ProfScope(fm_matrix* m_, hipStream_t st_, int id_) : m(m_), st(st_), id(id_)
+{
+    if (!m->prof) return;
+    for (hipEvent_t* ev : {&a, &b}) {
+        if (!m->prof_pool.empty()) {
+            *ev = m->prof_pool.back();
+            m->prof_pool.pop_back();
+        } else if (hipEventCreate(ev) != hipSuccess) {
+            *ev = nullptr;
+        }
+    }
+    if (a != nullptr) (void)hipEventRecord(a, st);
+}
+
+ProfScope::~ProfScope()
+{
+    if (!m->prof || a == nullptr || b == nullptr) return;
+    (void)hipEventRecord(b, st);
+    m->prof_recs.push_back({id, a, b});
+}
+
+static const char* const kKernelNames[FMK_COUNT] = {
+    "rows_forward", "rows_refresh", "cols", "cols_long", "cols_finish", "reduce", "bias"};
+
+extern "C" int fm_profile_enable(fm_matrix* m, int32_t on)
+{
+    if (m == nullptr) return FM_EINVAL;
+    m->prof = on != 0;
+    return FM_OK;
+}
+extern "C" int fm_profile_kernels(void) { return FMK_COUNT; }
+extern "C" const char* fm_profile_kernel_name(int32_t k) { return (k >= 0 && k < FMK_COUNT) ? kKernelNames[k] : ""; }
+
+extern "C" int fm_profile_read(fm_matrix* m, int64_t* launches, double* total_ms)
+{
+    if (m == nullptr || launches == nullptr || total_ms == nullptr) return FM_EINVAL;
+    FM_HIP(m, hipDeviceSynchronize());
+    for (const ProfRec& r : m->prof_recs) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+            m->prof_launches[r.id] += 1;
+            m->prof_ms[r.id] += (double)ms;
+        }
+        m->prof_pool.push_back(r.a);
+        m->prof_pool.push_back(r.b);
+    }
+    m->prof_recs.clear();
+    for (int k = 0; k < FMK_COUNT; ++k) {
+        launches[k] = m->prof_launches[k];
+        total_ms[k] = m->prof_ms[k];
+        m->prof_launches[k] = 0;
+        m->prof_ms[k] = 0.0;
+    }
+    return FM_OK;
+}
+
+extern "C" const char* fm_last_error(const fm_matrix* m) { return m != nullptr ? m->err.c_str() : g_build_error.c_str(); }
+
+extern "C" int fm_destroy(fm_matrix* m)
+{
+    if (m == nullptr) return FM_OK;
+    (void)hipDeviceSynchronize();
+    for (void* p : m->allocs) (void)hipFree(p);
+    if (m->h_scal != nullptr) (void)hipHostFree(m->h_scal);
+    for (const ProfRec& r : m->prof_recs) {
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    for (hipEvent_t e : m->prof_pool) (void)hipEventDestroy(e);
+    delete m;
+    return FM_OK;
+}
+
+extern "C" int fm_build_csr(int64_t N, int64_t D, int64_t nnz, const int64_t* rowptr, const int32_t* col,
+                            const float* val, void* hip_stream, fm_matrix** out)
+{
+    if (out == nullptr) return fm_fail(nullptr, FM_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (N < 0 || D < 0 || nnz < 0 || rowptr == nullptr || (nnz > 0 && (col == nullptr || val == nullptr)))
+        return fm_fail(nullptr, FM_EINVAL, "bad sizes or NULL arrays");
+    if (N >= (1LL << 31) || D >= (1LL << 31) || nnz >= (1LL << 32))
+        return fm_fail(nullptr, FM_ERANGE, "N, D must be < 2^31 and nnz < 2^32");
+    if (rowptr[0] != 0 || rowptr[N] != nnz) return fm_fail(nullptr, FM_EUNSORTED, "rowptr[0] != 0 or rowptr[N] != nnz");
+    for (int64_t i = 0; i < N; ++i) {
+        const int64_t b = rowptr[i], e = rowptr[i + 1];
+        if (e < b || e > nnz) return fm_fail(nullptr, FM_EUNSORTED, "rowptr not monotone at row %lld", (long long)i);
+        for (int64_t t = b; t < e; ++t) {
+            const int64_t c = col[t];
+            if (c < 0 || c >= D)
+                return fm_fail(nullptr, FM_ERANGE, "column %lld of row %lld outside [0,%lld)", (long long)c,
+                               (long long)i, (long long)D);
+            if (t > b && col[t - 1] >= c)
+                return fm_fail(nullptr, FM_EUNSORTED, "columns of row %lld not strictly ascending", (long long)i);
+        }
+    }
+    hipStream_t st = (hipStream_t)hip_stream;
+    fm_matrix* m = new (std::nothrow) fm_matrix();
+    if (m == nullptr) return fm_fail(nullptr, FM_ENOMEM, "out of host memory");
+    m->N = N;
+    m->D = D;
+    m->nnz = nnz;
+    int rc = FM_OK;
+    auto up = [&](void** d, const void* h, size_t bytes) -> int {
+        FM_TRY(fm_dev_alloc(m, d, bytes));
+        if (bytes > 0) FM_HIP(m, hipMemcpyAsync(*d, h, bytes, hipMemcpyHostToDevice, st));
+        return FM_OK;
+    };
+    rc = up((void**)&m->rowptr, rowptr, (size_t)(N + 1) * sizeof(int64_t));
+    if (rc == FM_OK) rc = up((void**)&m->col, col, (size_t)nnz * sizeof(int32_t));
+    if (rc == FM_OK) rc = up((void**)&m->val, val, (size_t)nnz * sizeof(float));
+    if (rc == FM_OK) rc = fm_dev_alloc(m, (void**)&m->scal, (8 + 2048) * sizeof(double));
+    if (rc == FM_OK && hipHostMalloc((void**)&m->h_scal, 8 * sizeof(double)) != hipSuccess)
+        rc = fm_fail(m, FM_ENOMEM, "pinned allocation failed");
+    if (rc == FM_OK && hipStreamSynchronize(st) != hipSuccess) rc = fm_fail(m, FM_EHIP, "upload failed");
+    if (rc != FM_OK) {
+        g_build_error = m->err;
+        fm_destroy(m);
+        return rc;
+    }
+    *out = m;
+    return FM_OK;
+}
+
+extern "C" int fm_get_csc(const fm_matrix* m, int64_t* colptr, int32_t* row, float* val)
+{
+    if (m == nullptr) return FM_EINVAL;
+    fm_matrix* mm = const_cast<fm_matrix*>(m);
+    if (!m->has_csc) return fm_fail(mm, FM_ESTATE, "CSC not built");
+    FM_HIP(mm, hipDeviceSynchronize());
+    if (colptr) FM_HIP(mm, hipMemcpy(colptr, m->colptr, (size_t)(m->D + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (row && m->nnz) FM_HIP(mm, hipMemcpy(row, m->crow, (size_t)m->nnz * sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (val && m->nnz) FM_HIP(mm, hipMemcpy(val, m->cval, (size_t)m->nnz * sizeof(float), hipMemcpyDeviceToHost));
+    return FM_OK;
+}
+
+extern "C" int fm_get_block_index(const fm_matrix* m, int64_t* row_bounds, int64_t* col_bounds, int64_t* cell_nnz)
+{
+    if (m == nullptr) return FM_EINVAL;
+    fm_matrix* mm = const_cast<fm_matrix*>(m);
+    if (m->P == 0) return fm_fail(mm, FM_ESTATE, "matrix not partitioned");
+    if (row_bounds) memcpy(row_bounds, m->h_rb.data(), (size_t)(m->P + 1) * sizeof(int64_t));
+    if (col_bounds) memcpy(col_bounds, m->h_cb.data(), (size_t)(m->P + 1) * sizeof(int64_t));
+    if (cell_nnz) memcpy(cell_nnz, m->h_cell_nnz.data(), (size_t)m->P * m->P * sizeof(int64_t));
+    return FM_OK;
+}
+
+extern "C" int fm_get_stratum_nnz(const fm_matrix* m, int32_t s, int64_t* nnz_out)
+{
+    if (m == nullptr || nnz_out == nullptr) return FM_EINVAL;
+    fm_matrix* mm = const_cast<fm_matrix*>(m);
+    if (m->P == 0) return fm_fail(mm, FM_ESTATE, "matrix not partitioned");
+    if (s < 0 || s >= m->P) return fm_fail(mm, FM_EINVAL, "stratum %d outside [0,%d)", s, m->P);
+    *nnz_out = m->h_strat_nnz_off[s + 1] - m->h_strat_nnz_off[s];
+    return FM_OK;
+}
+
+static int get_stratum(const fm_matrix* m, int32_t s, bool by_rows, int64_t* ptr, int32_t* ind, float* val)
+{
+    if (m == nullptr) return FM_EINVAL;
+    fm_matrix* mm = const_cast<fm_matrix*>(m);
+    if (m->P == 0) return fm_fail(mm, FM_ESTATE, "matrix not partitioned");
+    if (s < 0 || s >= m->P) return fm_fail(mm, FM_EINVAL, "stratum %d outside [0,%d)", s, m->P);
+    FM_HIP(mm, hipDeviceSynchronize());
+    const int64_t nmaj = by_rows ? m->N : m->D;
+    const int64_t off = m->h_strat_nnz_off[s], cnt = m->h_strat_nnz_off[s + 1] - off;
+    if (ptr) {
+        FM_HIP(mm, hipMemcpy(ptr, (by_rows ? m->s_rowptr : m->s_colptr) + (int64_t)s * nmaj,
+                             (size_t)(nmaj + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
+        for (int64_t k = 0; k <= nmaj; ++k) ptr[k] -= off;
+    }
+    if (ind && cnt)
+        FM_HIP(mm, hipMemcpy(ind, (by_rows ? m->s_col : m->s_row) + off, (size_t)cnt * sizeof(int32_t),
+                             hipMemcpyDeviceToHost));
+    if (val && cnt)
+        FM_HIP(mm, hipMemcpy(val, (by_rows ? m->s_val : m->s_cval) + off, (size_t)cnt * sizeof(float),
+                             hipMemcpyDeviceToHost));
+    return FM_OK;
+}
+
+extern "C" int fm_get_stratum_csr(const fm_matrix* m, int32_t s, int64_t* rowptr, int32_t* col, float* val)
+{
+    return get_stratum(m, s, true, rowptr, col, val);
+}
+extern "C" int fm_get_stratum_csc(const fm_matrix* m, int32_t s, int64_t* colptr, int32_t* row, float* val)
+{
+    return get_stratum(m, s, false, colptr, row, val);
+}
+
+// ------------------------------------------------------------ workspace ----
+
+static int check_params(fm_matrix* m, const fm_params* p)
+{
+    if (p == nullptr) return fm_fail(m, FM_EINVAL, "params is NULL");
+    int vec, lanes;
+    if (!fm_shape_for_K(p->K, &vec, &lanes))
+        return fm_fail(m, FM_EINVAL, "K=%d unsupported (1..64, or a multiple of 4 up to 256)", p->K);
+    if (p->loss != FM_LOSS_SQUARED && p->loss != FM_LOSS_LOGISTIC) return fm_fail(m, FM_EINVAL, "unknown loss %d", p->loss);
+    return FM_OK;
+}
+
+void fm_drop_workspace(fm_matrix* m)
+{
+    for (void* p : {(void*)m->G, (void*)m->a, (void*)m->q, (void*)m->r, (void*)m->dV, (void*)m->dwn,
+                    (void*)m->part_acc, (void*)m->part_gs, (void*)m->row_part, (void*)m->col_part})
+        fm_dev_free(m, p);
+    m->G = m->a = m->q = m->r = m->dV = m->part_acc = m->row_part = m->col_part = nullptr;
+    m->dwn = nullptr;
+    m->part_gs = nullptr;
+    m->wsK = 0;
+    m->aux_full = false;
+}
+
+// (re)allocate the per-K workspace
+static int ensure_ws(fm_matrix* m, int32_t K)
+{
+    if (m->wsK == K) return FM_OK;
+    fm_drop_workspace(m);
+    const size_t N = (size_t)m->N, D = (size_t)m->D;
+    FM_TRY(fm_dev_alloc(m, (void**)&m->G, N * K * sizeof(float)));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->a, N * sizeof(float)));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->q, N * sizeof(float)));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->r, N * sizeof(float)));
+    const int64_t items = std::max<int64_t>(m->lfull.nitems, m->lstrat.nitems);
+    FM_TRY(fm_dev_alloc(m, (void**)&m->part_acc, (size_t)std::max<int64_t>(items, 1) * K * sizeof(float)));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->part_gs, (size_t)std::max<int64_t>(items, 1) * sizeof(float2)));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->row_part, (size_t)std::max<int64_t>(fm_rows_grid(m->N, K), 1) * 2 * sizeof(float)));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->col_part, (size_t)std::max<int64_t>(fm_cols_grid(m->D, K), 1) * 2 * sizeof(float)));
+    if (m->P > 0) {
+        FM_TRY(fm_dev_alloc(m, (void**)&m->dV, D * K * sizeof(float)));
+        FM_TRY(fm_dev_alloc(m, (void**)&m->dwn, D * sizeof(float2)));
+    }
+    m->wsK = K;
+    return FM_OK;
+}
+
+static int ensure_strat_ws(fm_matrix* m, int32_t K)
+{
+    return ensure_ws(m, K);  // fm_partition dropped any older workspace, so dV/dwn are there
+}
+
+static void fill_long(ColArgs& A, const LongIndex& li, int32_t s, bool strat)
+{
+    const int64_t l0 = strat ? li.h_long_off[s] : 0, l1 = strat ? li.h_long_off[s + 1] : li.nlong;
+    const int64_t i0 = strat ? li.h_item_off[s] : 0, i1 = strat ? li.h_item_off[s + 1] : li.nitems;
+    A.nlong = l1 - l0;
+    A.nitems = i1 - i0;
+    A.long_base = l0;
+    A.item_base = i0;
+    A.long_col = li.long_col;
+    A.long_first = li.long_first;
+    A.item_col = li.item_col;
+    A.item_beg = li.item_beg;
+    A.item_len = li.item_len;
+}
+
+// ---------------------------------------------------------------- forward ----
+
+static int run_forward(fm_matrix* m, const fm_params* p, const float* y, const float* w0, const float* w,
+                       const float* V, float* yhat, float* a, float* G, float* q, float* r, bool want_sums,
+                       hipStream_t st)
+{
+    RowArgs A;
+    memset(&A, 0, sizeof(A));
+    A.N = m->N;
+    A.K = p->K;
+    A.rowptr = m->rowptr;
+    A.col = m->col;
+    A.val = m->val;
+    A.w0 = w0;
+    A.w = w;
+    A.V = V;
+    A.y = y;
+    A.yhat = yhat;
+    A.a = a;
+    A.G = G;
+    A.q = q;
+    A.r = r;
+    A.row_part = (want_sums && y != nullptr) ? m->row_part : nullptr;
+    A.loss = p->loss;
+    A.s = p->loss_scale;
+    FM_TRY(fm_launch_rows(m, A, false, st));
+    if (A.row_part != nullptr) FM_TRY(fm_reduce_pairs(m, m->row_part, fm_rows_grid(m->N, p->K), m->scal + 0, st));
+    return FM_OK;
+}
+
+extern "C" int fm_forward(fm_matrix* m, const fm_params* p, const float* y, const float* w0, const float* w,
+                          const float* V, float* yhat, float* a, float* G, float* q, float* r, double* loss_sum,
+                          void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    FM_TRY(check_params(m, p));
+    if (w0 == nullptr || w == nullptr || V == nullptr) return fm_fail(m, FM_EINVAL, "w0, w, V must not be NULL");
+    if ((r != nullptr || loss_sum != nullptr) && y == nullptr) return fm_fail(m, FM_EINVAL, "r and loss_sum need y");
+    hipStream_t st = (hipStream_t)hip_stream;
+    FM_TRY(ensure_ws(m, p->K));
+    if (m->N == 0) {
+        if (loss_sum) *loss_sum = 0.0;
+        return FM_OK;
+    }
+    FM_TRY(run_forward(m, p, y, w0, w, V, yhat, a, G, q, r, loss_sum != nullptr, st));
+    if (loss_sum != nullptr) {
+        FM_HIP(m, hipMemcpyAsync(m->h_scal, m->scal, 2 * sizeof(double), hipMemcpyDeviceToHost, st));
+        FM_HIP(m, hipStreamSynchronize(st));
+        *loss_sum = m->h_scal[0];
+    }
+    return FM_OK;
+}
+
+// --------------------------------------------------------------- gradient ----
+
+static void base_col_args(fm_matrix* m, const fm_params* p, ColArgs& A)
+{
+    memset(&A, 0, sizeof(A));
+    A.D = m->D;
+    A.K = p->K;
+    A.lambda_w = p->lambda_w;
+    A.lambda_v = p->lambda_v;
+    A.eta = p->eta;
+    A.N = m->N;
+    A.part_acc = m->part_acc;
+    A.part_gs = m->part_gs;
+}
+
+extern "C" int fm_gradient(fm_matrix* m, const fm_params* p, const float* r, const float* G, const float* w,
+                           const float* V, float* grad_w0, float* grad_w, float* grad_V, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    FM_TRY(check_params(m, p));
+    if (!m->has_csc) return fm_fail(m, FM_ESTATE, "fm_gradient needs fm_build_csc first");
+    if (r == nullptr || G == nullptr || w == nullptr || V == nullptr)
+        return fm_fail(m, FM_EINVAL, "r, G, w, V must not be NULL");
+    hipStream_t st = (hipStream_t)hip_stream;
+    FM_TRY(ensure_ws(m, p->K));
+    if (grad_w0 != nullptr) {
+        FM_TRY(fm_reduce_sum(m, r, m->N, false, m->scal + 1, st));
+        FM_TRY(fm_bias_step(m, nullptr, m->scal + 1, 0.f, grad_w0, st));
+    }
+    if (m->D == 0 || (grad_w == nullptr && grad_V == nullptr)) return FM_OK;
+    ColArgs A;
+    base_col_args(m, p, A);
+    A.ptr = m->colptr;
+    A.row = m->crow;
+    A.val = m->cval;
+    A.r = r;
+    A.G = G;
+    A.w = const_cast<float*>(w);
+    A.V = const_cast<float*>(V);
+    A.grad_w = grad_w;
+    A.grad_V = grad_V;
+    fill_long(A, m->lfull, 0, false);
+    return fm_launch_cols(m, A, false, st);
+}
+
+// ------------------------------------------------------------ full epoch ----
+
+extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, float* w0, float* w, float* V,
+                            double* objective, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    FM_TRY(check_params(m, p));
+    if (!m->has_csc) return fm_fail(m, FM_ESTATE, "fm_sgd_epoch needs fm_build_csc first");
+    if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
+        return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
+    hipStream_t st = (hipStream_t)hip_stream;
+    FM_TRY(ensure_ws(m, p->K));
+    if (m->N == 0 || m->D == 0) {
+        if (objective) objective[0] = objective[1] = 0.0;
+        return FM_OK;
+    }
+    // steps 1-3: G, r, loss and sum r
+    FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, m->G, nullptr, m->r, true, st));
+    m->aux_full = false;
+    // steps 4-5 fused: gradient of every column and the step on w, V
+    ColArgs A;
+    base_col_args(m, p, A);
+    A.ptr = m->colptr;
+    A.row = m->crow;
+    A.val = m->cval;
+    A.r = m->r;
+    A.G = m->G;
+    A.w = w;
+    A.V = V;
+    A.col_part = objective != nullptr ? m->col_part : nullptr;
+    fill_long(A, m->lfull, 0, false);
+    FM_TRY(fm_launch_cols(m, A, true, st));
+    if (objective != nullptr) FM_TRY(fm_reduce_pairs(m, m->col_part, fm_cols_grid(m->D, p->K), m->scal + 2, st));
+    if (p->update_w0) FM_TRY(fm_bias_step(m, w0, m->scal + 1, p->eta, nullptr, st));
+    if (objective != nullptr) {
+        FM_HIP(m, hipMemcpyAsync(m->h_scal, m->scal, 4 * sizeof(double), hipMemcpyDeviceToHost, st));
+        FM_HIP(m, hipStreamSynchronize(st));
+        objective[0] = (double)p->loss_scale * m->h_scal[0];
+        objective[1] = 0.5 * (double)p->lambda_w * m->h_scal[2] + 0.5 * (double)p->lambda_v * m->h_scal[3];
+    }
+    return FM_OK;
+}
+
+// ------------------------------------------------------- stratified epoch ----
+
+extern "C" int fm_stratified_begin(fm_matrix* m, const fm_params* p, const float* y, const float* w0,
+                                   const float* w, const float* V, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    FM_TRY(check_params(m, p));
+    if (m->P == 0) return fm_fail(m, FM_ESTATE, "stratified calls need fm_partition first");
+    if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
+        return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
+    hipStream_t st = (hipStream_t)hip_stream;
+    FM_TRY(ensure_strat_ws(m, p->K));
+    FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, m->a, m->G, m->q, m->r, false, st));
+    m->aux_full = true;
+    return FM_OK;
+}
+
+extern "C" int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const float* y, const float* w0,
+                                  float* w, float* V, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    FM_TRY(check_params(m, p));
+    if (m->P == 0) return fm_fail(m, FM_ESTATE, "stratified calls need fm_partition first");
+    if (s < 0 || s >= m->P) return fm_fail(m, FM_EINVAL, "stratum %d outside [0,%d)", s, m->P);
+    if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
+        return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
+    if (m->wsK != p->K || !m->aux_full) return fm_fail(m, FM_ESTATE, "call fm_stratified_begin first");
+    hipStream_t st = (hipStream_t)hip_stream;
+    // phase A: block gradients of the stratum's P cells and the step on every column block
+    ColArgs A;
+    base_col_args(m, p, A);
+    A.ptr = m->s_colptr + (int64_t)s * m->D;
+    A.row = m->s_row;
+    A.val = m->s_cval;
+    A.r = m->r;
+    A.G = m->G;
+    A.w = w;
+    A.V = V;
+    A.dV = m->dV;
+    A.dwn = m->dwn;
+    if (!p->reg_full_per_cell) {
+        A.rb = m->d_rb;
+        A.P = m->P;
+        A.s = s;
+    }
+    fill_long(A, m->lstrat, s, true);
+    FM_TRY(fm_launch_cols(m, A, true, st));
+    // phase B: incremental refresh of the aggregates and multipliers
+    RowArgs R;
+    memset(&R, 0, sizeof(R));
+    R.N = m->N;
+    R.K = p->K;
+    if (p->refresh_all_rows) {
+        R.rowptr = m->rowptr;
+        R.col = m->col;
+        R.val = m->val;
+    } else {
+        R.rowptr = m->s_rowptr + (int64_t)s * m->N;
+        R.col = m->s_col;
+        R.val = m->s_val;
+    }
+    R.w0 = w0;
+    R.V = m->dV;
+    R.dwn = m->dwn;
+    R.y = y;
+    R.a = m->a;
+    R.G = m->G;
+    R.q = m->q;
+    R.r = m->r;
+    R.loss = p->loss;
+    R.s = p->loss_scale;
+    return fm_launch_rows(m, R, true, st);
+}
+
+extern "C" int fm_stratified_end(fm_matrix* m, const fm_params* p, float* w0, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    FM_TRY(check_params(m, p));
+    if (m->wsK != p->K || !m->aux_full) return fm_fail(m, FM_ESTATE, "call fm_stratified_begin first");
+    if (w0 == nullptr) return fm_fail(m, FM_EINVAL, "w0 must not be NULL");
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (p->update_w0) {
+        FM_TRY(fm_reduce_sum(m, m->r, m->N, false, m->scal + 1, st));
+        FM_TRY(fm_bias_step(m, w0, m->scal + 1, p->eta, nullptr, st));
+    }
+    return FM_OK;
+}
+
+extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float* y, float* w0, float* w, float* V,
+                                   double* objective, void* hip_stream)
+{
+    FM_TRY(fm_stratified_begin(m, p, y, w0, w, V, hip_stream));
+    for (int32_t s = 0; s < m->P; ++s) FM_TRY(fm_stratified_step(m, p, s, y, w0, w, V, hip_stream));
+    FM_TRY(fm_stratified_end(m, p, w0, hip_stream));
+    if (objective != nullptr) {
+        hipStream_t st = (hipStream_t)hip_stream;
+        FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, m->a, m->G, m->q, m->r, true, st));
+        FM_TRY(fm_reduce_sum(m, w, m->D, true, m->scal + 2, st));
+        FM_TRY(fm_reduce_sum(m, V, m->D * (int64_t)p->K, true, m->scal + 3, st));
+        FM_HIP(m, hipMemcpyAsync(m->h_scal, m->scal, 4 * sizeof(double), hipMemcpyDeviceToHost, st));
+        FM_HIP(m, hipStreamSynchronize(st));
+        objective[0] = (double)p->loss_scale * m->h_scal[0];
+        objective[1] = 0.5 * (double)p->lambda_w * m->h_scal[2] + 0.5 * (double)p->lambda_v * m->h_scal[3];
+    }
+    return FM_OK;
+}
+
+extern "C" int fm_get_aux(const fm_matrix* m, float* a, float* G, float* q, float* r, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    fm_matrix* mm = const_cast<fm_matrix*>(m);
+    if (m->wsK == 0) return fm_fail(mm, FM_ESTATE, "no aggregates held yet");
+    if ((a != nullptr || q != nullptr) && !m->aux_full)
+        return fm_fail(mm, FM_ESTATE, "a and q are only held after a stratified call");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t N = (size_t)m->N;
+    if (a) FM_HIP(mm, hipMemcpyAsync(a, m->a, N * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (G) FM_HIP(mm, hipMemcpyAsync(G, m->G, N * m->wsK * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (q) FM_HIP(mm, hipMemcpyAsync(q, m->q, N * sizeof(float), hipMemcpyDeviceToDevice, st));
+    if (r) FM_HIP(mm, hipMemcpyAsync(r, m->r, N * sizeof(float), hipMemcpyDeviceToDevice, st));
+    return FM_OK;
+}

@@ -1,0 +1,551 @@
+// Integer-only builders: exclusive scan, stable LSD radix sort, CSR->CSC transpose,
+// the per-stratum matrices of the double partition, and the work-item lists for long
+// columns.  Everything here is deterministic (integer atomics are only used for
+// counts, whose totals do not depend on the order of the additions).
+#include "fm_device.h"
+#include "fm_internal.h"
+
+namespace {
+
+// ------------------------------------------------------------------ scan ----
+constexpr int SCAN_T = 256;
+constexpr int SCAN_E = 8;
+constexpr int SCAN_TILE = SCAN_T * SCAN_E;
+
+// exclusive prefix of one int64 per thread across the 256 threads of a block
+__device__ __forceinline__ int64_t block_exclusive_256(int64_t v, int64_t (*sh)[SCAN_T], int64_t* total)
+{
+    const int t = threadIdx.x;
+    sh[0][t] = v;
+    __syncthreads();
+    int cur = 0;
+    for (int o = 1; o < SCAN_T; o <<= 1) {
+        int64_t x = sh[cur][t];
+        if (t >= o) x += sh[cur][t - o];
+        sh[cur ^ 1][t] = x;
+        __syncthreads();
+        cur ^= 1;
+    }
+    const int64_t incl = sh[cur][t];
+    if (total != nullptr) *total = sh[cur][SCAN_T - 1];
+    __syncthreads();
+    return incl - v;
+}
+
+__global__ __launch_bounds__(SCAN_T) void k_scan_sums(const int64_t* __restrict__ d, int64_t n,
+                                                      int64_t* __restrict__ sums)
+{
+    __shared__ int64_t sh[2][SCAN_T];
+    const int64_t base = (int64_t)blockIdx.x * SCAN_TILE;
+    int64_t v = 0;
+    for (int u = 0; u < SCAN_E; ++u) {
+        const int64_t i = base + (int64_t)u * SCAN_T + threadIdx.x;
+        if (i < n) v += d[i];
+    }
+    int64_t total;
+    block_exclusive_256(v, sh, &total);
+    if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(SCAN_T) void k_scan_apply(int64_t* __restrict__ d, int64_t n,
+                                                       const int64_t* __restrict__ offs)
+{
+    __shared__ int64_t sh[2][SCAN_T];
+    const int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_E;
+    int64_t x[SCAN_E];
+    int64_t tot = 0;
+#pragma unroll
+    for (int u = 0; u < SCAN_E; ++u) {
+        x[u] = (base + u < n) ? d[base + u] : 0;
+        tot += x[u];
+    }
+    int64_t run = block_exclusive_256(tot, sh, nullptr) + (offs != nullptr ? offs[blockIdx.x] : 0);
+#pragma unroll
+    for (int u = 0; u < SCAN_E; ++u) {
+        if (base + u < n) d[base + u] = run;
+        run += x[u];
+    }
+}
+
+// ------------------------------------------------------------ radix sort ----
+constexpr int RS_T = 256;
+constexpr int RS_ROUNDS = 8;
+constexpr int RS_TILE = RS_T * RS_ROUNDS;
+
+__global__ __launch_bounds__(RS_T) void k_radix_hist(const uint32_t* __restrict__ keys, int64_t n, int shift,
+                                                     int64_t* __restrict__ hist, int64_t nblocks)
+{
+    __shared__ unsigned int h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * RS_TILE;
+    for (int u = 0; u < RS_ROUNDS; ++u) {
+        const int64_t i = base + (int64_t)u * RS_T + threadIdx.x;
+        if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = (int64_t)h[threadIdx.x];
+}
+
+// Stable scatter: elements of a block are taken in memory order (round by round,
+// lane by lane); an element's slot is the scanned start of (digit, block) plus the
+// number of same-digit elements before it in the block.
+__global__ __launch_bounds__(RS_T) void k_radix_scatter(const uint32_t* __restrict__ keys_in,
+                                                        const uint32_t* __restrict__ idx_in,
+                                                        uint32_t* __restrict__ keys_out,
+                                                        uint32_t* __restrict__ idx_out, int64_t n, int shift,
+                                                        const int64_t* __restrict__ hist, int64_t nblocks)
+{
+    __shared__ int64_t base[256];
+    __shared__ unsigned int wcnt[RS_T / 64][256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    base[tid] = hist[(int64_t)tid * nblocks + blockIdx.x];
+    const int64_t tile = (int64_t)blockIdx.x * RS_TILE;
+    for (int u = 0; u < RS_ROUNDS; ++u) {
+#pragma unroll
+        for (int k = 0; k < RS_T / 64; ++k) wcnt[k][tid] = 0;
+        __syncthreads();
+        const int64_t i = tile + (int64_t)u * RS_T + tid;
+        const bool valid = i < n;
+        const uint32_t key = valid ? keys_in[i] : 0u;
+        const uint32_t dg = (key >> shift) & 255u;
+        unsigned long long mask = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const bool bb = (dg >> bit) & 1u;
+            const unsigned long long bal = __ballot(bb);
+            mask &= bb ? bal : ~bal;
+        }
+        const unsigned int rank = __popcll(mask & ((1ull << lane) - 1ull));
+        if (valid && rank == 0) wcnt[wave][dg] = (unsigned int)__popcll(mask);
+        __syncthreads();
+        if (valid) {
+            unsigned int off = 0;
+            for (int k = 0; k < wave; ++k) off += wcnt[k][dg];
+            const int64_t dst = base[dg] + off + rank;
+            keys_out[dst] = key;
+            idx_out[dst] = idx_in[i];
+        }
+        __syncthreads();
+        unsigned int add = 0;
+#pragma unroll
+        for (int k = 0; k < RS_T / 64; ++k) add += wcnt[k][tid];
+        base[tid] += add;
+    }
+}
+
+// ------------------------------------------------------------- transpose ----
+__global__ void k_init_keys(const int32_t* __restrict__ col, uint32_t* __restrict__ keys,
+                            uint32_t* __restrict__ idx, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        keys[i] = (uint32_t)col[i];
+        idx[i] = (uint32_t)i;
+    }
+}
+
+// owner of entry e in a pointer array ptr[0..n]: the k with ptr[k] <= e < ptr[k+1]
+__device__ __forceinline__ int64_t owner_of(const int64_t* __restrict__ ptr, int64_t n, int64_t e)
+{
+    int64_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (ptr[mid] <= e) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void k_gather_transposed(const uint32_t* __restrict__ perm, const int64_t* __restrict__ ptr, int64_t nown,
+                                    const float* __restrict__ val, int32_t* __restrict__ owner_out,
+                                    float* __restrict__ val_out, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        const int64_t e = perm[i];
+        owner_out[i] = (int32_t)owner_of(ptr, nown, e);
+        val_out[i] = val[e];
+    }
+}
+
+// ptr[j] = number of sorted keys smaller than j, j = 0..ncols
+__global__ void k_ptr_from_sorted(const uint32_t* __restrict__ keys, int64_t n, int64_t ncols,
+                                  int64_t* __restrict__ ptr)
+{
+    const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j > ncols) return;
+    int64_t lo = 0, hi = n;  // first position with key >= j
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)keys[mid] < j) lo = mid + 1; else hi = mid;
+    }
+    ptr[j] = lo;
+}
+
+// -------------------------------------------------------------- partition ----
+// Stratum of every stored entry; `major` is the pointer array of the orientation
+// being processed (rowptr for CSR, colptr for CSC) and `minor` its index array.
+__global__ void k_stratum_keys(const int64_t* __restrict__ major, int64_t nmajor, const int32_t* __restrict__ minor,
+                               int64_t n, int64_t N, int64_t D, int32_t P, int by_rows,
+                               uint32_t* __restrict__ keys, uint32_t* __restrict__ idx,
+                               unsigned long long* __restrict__ cnt)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n) return;
+    const int64_t mj = owner_of(major, nmajor, e);
+    const int64_t mn = minor[e];
+    const int64_t i = by_rows ? mj : mn;
+    const int64_t j = by_rows ? mn : mj;
+    const int32_t p = fm_block_of(i, N, P);
+    const int32_t q = fm_block_of(j, D, P);
+    int32_t s = (q - p) % P;
+    if (s < 0) s += P;
+    keys[e] = (uint32_t)s;
+    idx[e] = (uint32_t)e;
+    atomicAdd(&cnt[(int64_t)s * nmajor + mj], 1ull);
+}
+
+__global__ void k_gather_pairs(const uint32_t* __restrict__ perm, const int32_t* __restrict__ ind,
+                               const float* __restrict__ val, int32_t* __restrict__ ind_out,
+                               float* __restrict__ val_out, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        const int64_t e = perm ? (int64_t)perm[i] : i;
+        ind_out[i] = ind[e];
+        val_out[i] = val[e];
+    }
+}
+
+// out[s*(P+1)+q] = s_colptr[s*D + cb[q]]
+__global__ void k_cell_starts(const int64_t* __restrict__ s_colptr, const int64_t* __restrict__ cb, int64_t D,
+                              int32_t P, int64_t* __restrict__ out)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)P * (P + 1)) return;
+    const int64_t s = t / (P + 1), q = t % (P + 1);
+    out[t] = s_colptr[s * D + cb[q]];
+}
+
+// ------------------------------------------------------------ long index ----
+constexpr int LI_T = 256;
+constexpr int LI_E = 4;
+constexpr int LI_TILE = LI_T * LI_E;
+
+__global__ __launch_bounds__(LI_T) void k_long_count(const int64_t* __restrict__ ptr, int64_t ncols,
+                                                     int64_t* __restrict__ tile_long, int64_t* __restrict__ tile_items)
+{
+    __shared__ int64_t sh[2][SCAN_T];
+    const int64_t base = (int64_t)blockIdx.x * LI_TILE + (int64_t)threadIdx.x * LI_E;
+    int64_t nl = 0, ni = 0;
+    for (int u = 0; u < LI_E; ++u) {
+        const int64_t c = base + u;
+        if (c < ncols) {
+            const int64_t len = ptr[c + 1] - ptr[c];
+            if (len > FM_SEG) {
+                nl += 1;
+                ni += (len + FM_SEG - 1) / FM_SEG;
+            }
+        }
+    }
+    int64_t t0, t1;
+    block_exclusive_256(nl, sh, &t0);
+    block_exclusive_256(ni, sh, &t1);
+    if (threadIdx.x == 0) {
+        tile_long[blockIdx.x] = t0;
+        tile_items[blockIdx.x] = t1;
+    }
+}
+
+__global__ __launch_bounds__(LI_T) void k_long_fill(const int64_t* __restrict__ ptr, int64_t ncols, int64_t D,
+                                                    const int64_t* __restrict__ tile_long,
+                                                    const int64_t* __restrict__ tile_items,
+                                                    int32_t* __restrict__ long_col, int64_t* __restrict__ long_vcol,
+                                                    int64_t* __restrict__ long_first, int32_t* __restrict__ item_col,
+                                                    int64_t* __restrict__ item_beg, int32_t* __restrict__ item_len)
+{
+    __shared__ int64_t sh[2][SCAN_T];
+    const int64_t base = (int64_t)blockIdx.x * LI_TILE + (int64_t)threadIdx.x * LI_E;
+    int64_t nl = 0, ni = 0;
+    for (int u = 0; u < LI_E; ++u) {
+        const int64_t c = base + u;
+        if (c < ncols) {
+            const int64_t len = ptr[c + 1] - ptr[c];
+            if (len > FM_SEG) {
+                nl += 1;
+                ni += (len + FM_SEG - 1) / FM_SEG;
+            }
+        }
+    }
+    int64_t lpos = block_exclusive_256(nl, sh, nullptr) + tile_long[blockIdx.x];
+    int64_t ipos = block_exclusive_256(ni, sh, nullptr) + tile_items[blockIdx.x];
+    for (int u = 0; u < LI_E; ++u) {
+        const int64_t c = base + u;
+        if (c >= ncols) break;
+        const int64_t b = ptr[c], len = ptr[c + 1] - b;
+        if (len <= FM_SEG) continue;
+        const int32_t j = (int32_t)(c % D);
+        long_col[lpos] = j;
+        long_vcol[lpos] = c;
+        long_first[lpos] = ipos;
+        ++lpos;
+        for (int64_t o = 0; o < len; o += FM_SEG) {
+            item_col[ipos] = j;
+            item_beg[ipos] = b + o;
+            item_len[ipos] = (int32_t)((len - o) < FM_SEG ? (len - o) : FM_SEG);
+            ++ipos;
+        }
+    }
+}
+
+inline unsigned blocks_for(int64_t n, int t) { return (unsigned)((n + t - 1) / t); }
+
+}  // namespace
+
+// ---------------------------------------------------------------- hosts ----
+
+int fm_scan_exclusive_i64(fm_matrix* m, int64_t* d, int64_t n, hipStream_t st)
+{
+    if (n <= 0) return FM_OK;
+    const int64_t ntiles = (n + SCAN_TILE - 1) / SCAN_TILE;
+    if (ntiles == 1) {
+        hipLaunchKernelGGL(k_scan_apply, dim3(1), dim3(SCAN_T), 0, st, d, n, (const int64_t*)nullptr);
+        FM_HIP(m, hipGetLastError());
+        return FM_OK;
+    }
+    int64_t* sums = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&sums, (size_t)ntiles * sizeof(int64_t)));
+    hipLaunchKernelGGL(k_scan_sums, dim3((unsigned)ntiles), dim3(SCAN_T), 0, st, (const int64_t*)d, n, sums);
+    FM_HIP(m, hipGetLastError());
+    int rc = fm_scan_exclusive_i64(m, sums, ntiles, st);
+    if (rc == FM_OK) {
+        hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)ntiles), dim3(SCAN_T), 0, st, d, n, (const int64_t*)sums);
+        if (hipGetLastError() != hipSuccess) rc = fm_fail(m, FM_EHIP, "scan apply launch failed");
+    }
+    if (hipStreamSynchronize(st) != hipSuccess && rc == FM_OK) rc = fm_fail(m, FM_EHIP, "scan failed");
+    fm_dev_free(m, sums);
+    return rc;
+}
+
+int fm_sort_by_key_u32(fm_matrix* m, uint32_t* keys, uint32_t* idx, uint32_t* keys_alt, uint32_t* idx_alt,
+                       int64_t n, int bits, hipStream_t st, bool* result_in_alt)
+{
+    *result_in_alt = false;
+    if (n <= 0 || bits <= 0) return FM_OK;
+    const int64_t nblocks = (n + RS_TILE - 1) / RS_TILE;
+    int64_t* hist = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&hist, (size_t)(256 * nblocks) * sizeof(int64_t)));
+    int rc = FM_OK;
+    uint32_t *ki = keys, *ii = idx, *ko = keys_alt, *io = idx_alt;
+    for (int shift = 0; shift < bits && rc == FM_OK; shift += 8) {
+        hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)nblocks), dim3(RS_T), 0, st, (const uint32_t*)ki, n, shift,
+                           hist, nblocks);
+        if (hipGetLastError() != hipSuccess) { rc = fm_fail(m, FM_EHIP, "radix hist launch failed"); break; }
+        rc = fm_scan_exclusive_i64(m, hist, 256 * nblocks, st);
+        if (rc != FM_OK) break;
+        hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)nblocks), dim3(RS_T), 0, st, (const uint32_t*)ki,
+                           (const uint32_t*)ii, ko, io, n, shift, (const int64_t*)hist, nblocks);
+        if (hipGetLastError() != hipSuccess) { rc = fm_fail(m, FM_EHIP, "radix scatter launch failed"); break; }
+        uint32_t* t = ki; ki = ko; ko = t;
+        t = ii; ii = io; io = t;
+        *result_in_alt = !*result_in_alt;
+    }
+    if (hipStreamSynchronize(st) != hipSuccess && rc == FM_OK) rc = fm_fail(m, FM_EHIP, "radix sort failed");
+    fm_dev_free(m, hist);
+    return rc;
+}
+
+int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
+                        LongIndex* out, hipStream_t st)
+{
+    out->nlong = out->nitems = 0;
+    out->h_long_off.assign(nstrata + 1, 0);
+    out->h_item_off.assign(nstrata + 1, 0);
+    if (ncols_total <= 0) return FM_OK;
+    const int64_t ntiles = (ncols_total + LI_TILE - 1) / LI_TILE;
+    int64_t *tl = nullptr, *ti = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&tl, (size_t)(ntiles + 1) * sizeof(int64_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&ti, (size_t)(ntiles + 1) * sizeof(int64_t)));
+    FM_HIP(m, hipMemsetAsync(tl, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
+    FM_HIP(m, hipMemsetAsync(ti, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
+    hipLaunchKernelGGL(k_long_count, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, tl, ti);
+    FM_HIP(m, hipGetLastError());
+    FM_TRY(fm_scan_exclusive_i64(m, tl, ntiles + 1, st));
+    FM_TRY(fm_scan_exclusive_i64(m, ti, ntiles + 1, st));
+    int64_t nlong = 0, nitems = 0;
+    FM_HIP(m, hipMemcpyAsync(&nlong, tl + ntiles, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    FM_HIP(m, hipMemcpyAsync(&nitems, ti + ntiles, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    FM_HIP(m, hipStreamSynchronize(st));
+    out->nlong = nlong;
+    out->nitems = nitems;
+    if (nlong > 0) {
+        int64_t* vcol = nullptr;
+        FM_TRY(fm_dev_alloc(m, (void**)&out->long_col, (size_t)nlong * sizeof(int32_t)));
+        FM_TRY(fm_dev_alloc(m, (void**)&out->long_first, (size_t)(nlong + 1) * sizeof(int64_t)));
+        FM_TRY(fm_dev_alloc(m, (void**)&out->item_col, (size_t)nitems * sizeof(int32_t)));
+        FM_TRY(fm_dev_alloc(m, (void**)&out->item_beg, (size_t)nitems * sizeof(int64_t)));
+        FM_TRY(fm_dev_alloc(m, (void**)&out->item_len, (size_t)nitems * sizeof(int32_t)));
+        FM_TRY(fm_dev_alloc(m, (void**)&vcol, (size_t)nlong * sizeof(int64_t)));
+        hipLaunchKernelGGL(k_long_fill, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, D,
+                           (const int64_t*)tl, (const int64_t*)ti, out->long_col, vcol, out->long_first,
+                           out->item_col, out->item_beg, out->item_len);
+        FM_HIP(m, hipGetLastError());
+        FM_HIP(m, hipMemcpyAsync(out->long_first + nlong, &nitems, sizeof(int64_t), hipMemcpyHostToDevice, st));
+        std::vector<int64_t> h_vcol((size_t)nlong), h_first((size_t)nlong + 1);
+        FM_HIP(m, hipMemcpyAsync(h_vcol.data(), vcol, (size_t)nlong * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+        FM_HIP(m, hipStreamSynchronize(st));
+        FM_HIP(m, hipMemcpy(h_first.data(), out->long_first, (size_t)(nlong + 1) * sizeof(int64_t),
+                            hipMemcpyDeviceToHost));
+        // per-stratum ranges of the concatenated lists
+        int64_t k = 0;
+        for (int32_t s = 0; s <= nstrata; ++s) {
+            while (k < nlong && h_vcol[(size_t)k] < (int64_t)s * D) ++k;
+            out->h_long_off[s] = k;
+            out->h_item_off[s] = h_first[(size_t)k];
+        }
+        fm_dev_free(m, vcol);
+    }
+    fm_dev_free(m, tl);
+    fm_dev_free(m, ti);
+    return FM_OK;
+}
+
+static int bits_for(int64_t maxval)
+{
+    int b = 0;
+    while (b < 32 && ((int64_t)1 << b) <= maxval) ++b;
+    return b;
+}
+
+extern "C" int fm_build_csc(fm_matrix* m, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (m->has_csc) return FM_OK;
+    const int64_t n = m->nnz;
+    FM_TRY(fm_dev_alloc(m, (void**)&m->colptr, (size_t)(m->D + 1) * sizeof(int64_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->crow, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->cval, (size_t)(n > 0 ? n : 1) * sizeof(float)));
+    if (n == 0) {
+        FM_HIP(m, hipMemsetAsync(m->colptr, 0, (size_t)(m->D + 1) * sizeof(int64_t), st));
+    } else {
+        uint32_t *k0 = nullptr, *i0 = nullptr, *k1 = nullptr, *i1 = nullptr;
+        FM_TRY(fm_dev_alloc(m, (void**)&k0, (size_t)n * 4));
+        FM_TRY(fm_dev_alloc(m, (void**)&i0, (size_t)n * 4));
+        FM_TRY(fm_dev_alloc(m, (void**)&k1, (size_t)n * 4));
+        FM_TRY(fm_dev_alloc(m, (void**)&i1, (size_t)n * 4));
+        hipLaunchKernelGGL(k_init_keys, dim3(blocks_for(n, 256)), dim3(256), 0, st, (const int32_t*)m->col, k0, i0, n);
+        FM_HIP(m, hipGetLastError());
+        bool alt = false;
+        FM_TRY(fm_sort_by_key_u32(m, k0, i0, k1, i1, n, bits_for(m->D - 1), st, &alt));
+        const uint32_t* sk = alt ? k1 : k0;
+        const uint32_t* perm = alt ? i1 : i0;
+        hipLaunchKernelGGL(k_gather_transposed, dim3(blocks_for(n, 256)), dim3(256), 0, st, perm,
+                           (const int64_t*)m->rowptr, m->N, (const float*)m->val, m->crow, m->cval, n);
+        FM_HIP(m, hipGetLastError());
+        hipLaunchKernelGGL(k_ptr_from_sorted, dim3(blocks_for(m->D + 1, 256)), dim3(256), 0, st, sk, n, m->D,
+                           m->colptr);
+        FM_HIP(m, hipGetLastError());
+        FM_HIP(m, hipStreamSynchronize(st));
+        fm_dev_free(m, k0);
+        fm_dev_free(m, i0);
+        fm_dev_free(m, k1);
+        fm_dev_free(m, i1);
+    }
+    FM_TRY(fm_build_long_index(m, m->colptr, m->D, m->D, 1, &m->lfull, st));
+    FM_HIP(m, hipStreamSynchronize(st));
+    m->has_csc = true;
+    fm_drop_workspace(m);
+    return FM_OK;
+}
+
+// One orientation of the per-stratum matrices.
+static int build_strata_side(fm_matrix* m, bool by_rows, hipStream_t st, int64_t** sptr_out, int32_t** sind_out,
+                             float** sval_out)
+{
+    const int64_t n = m->nnz;
+    const int64_t nmajor = by_rows ? m->N : m->D;
+    const int64_t* major = by_rows ? m->rowptr : m->colptr;
+    const int32_t* minor = by_rows ? m->col : m->crow;
+    const float* val = by_rows ? m->val : m->cval;
+    const int32_t P = m->P;
+    const size_t np = (size_t)P * (size_t)nmajor + 1;
+    FM_TRY(fm_dev_alloc(m, (void**)sptr_out, np * sizeof(int64_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)sind_out, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)sval_out, (size_t)(n > 0 ? n : 1) * sizeof(float)));
+    FM_HIP(m, hipMemsetAsync(*sptr_out, 0, np * sizeof(int64_t), st));
+    if (n == 0) return FM_OK;
+    uint32_t *k0 = nullptr, *i0 = nullptr, *k1 = nullptr, *i1 = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&k0, (size_t)n * 4));
+    FM_TRY(fm_dev_alloc(m, (void**)&i0, (size_t)n * 4));
+    FM_TRY(fm_dev_alloc(m, (void**)&k1, (size_t)n * 4));
+    FM_TRY(fm_dev_alloc(m, (void**)&i1, (size_t)n * 4));
+    hipLaunchKernelGGL(k_stratum_keys, dim3(blocks_for(n, 256)), dim3(256), 0, st, major, nmajor, minor, n, m->N,
+                       m->D, P, by_rows ? 1 : 0, k0, i0, (unsigned long long*)*sptr_out);
+    FM_HIP(m, hipGetLastError());
+    FM_TRY(fm_scan_exclusive_i64(m, *sptr_out, (int64_t)np, st));
+    bool alt = false;
+    FM_TRY(fm_sort_by_key_u32(m, k0, i0, k1, i1, n, bits_for(P - 1), st, &alt));
+    const uint32_t* perm = alt ? i1 : i0;
+    hipLaunchKernelGGL(k_gather_pairs, dim3(blocks_for(n, 256)), dim3(256), 0, st, perm, minor, val, *sind_out,
+                       *sval_out, n);
+    FM_HIP(m, hipGetLastError());
+    FM_HIP(m, hipStreamSynchronize(st));
+    fm_dev_free(m, k0);
+    fm_dev_free(m, i0);
+    fm_dev_free(m, k1);
+    fm_dev_free(m, i1);
+    return FM_OK;
+}
+
+extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (!m->has_csc) return fm_fail(m, FM_ESTATE, "fm_partition needs fm_build_csc first");
+    if (P < 1 || P > FM_MAXP) return fm_fail(m, FM_EINVAL, "P=%d outside 1..%d", P, FM_MAXP);
+    if (m->P != 0) return fm_fail(m, FM_ESTATE, "matrix is already partitioned (P=%d)", m->P);
+    if (m->N < 1 || m->D < 1) return fm_fail(m, FM_EINVAL, "cannot partition an empty matrix");
+    m->P = P;
+    m->h_rb.resize(P + 1);
+    m->h_cb.resize(P + 1);
+    for (int32_t b = 0; b <= P; ++b) {
+        m->h_rb[b] = (int64_t)(((__int128)b * (__int128)m->N) / (__int128)P);
+        m->h_cb[b] = (int64_t)(((__int128)b * (__int128)m->D) / (__int128)P);
+    }
+    int64_t* d_cb = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&m->d_rb, (size_t)(P + 1) * sizeof(int64_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&d_cb, (size_t)(P + 1) * sizeof(int64_t)));
+    FM_HIP(m, hipMemcpy(m->d_rb, m->h_rb.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
+    FM_HIP(m, hipMemcpy(d_cb, m->h_cb.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
+
+    FM_TRY(build_strata_side(m, true, st, &m->s_rowptr, &m->s_col, &m->s_val));
+    FM_TRY(build_strata_side(m, false, st, &m->s_colptr, &m->s_row, &m->s_cval));
+
+    // cell table: in stratum s column block q only holds entries of row block (q-s) mod P
+    const int64_t nt = (int64_t)P * (P + 1);
+    int64_t* d_starts = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&d_starts, (size_t)nt * sizeof(int64_t)));
+    hipLaunchKernelGGL(k_cell_starts, dim3(blocks_for(nt, 256)), dim3(256), 0, st, (const int64_t*)m->s_colptr,
+                       (const int64_t*)d_cb, m->D, P, d_starts);
+    FM_HIP(m, hipGetLastError());
+    std::vector<int64_t> h_starts((size_t)nt);
+    FM_HIP(m, hipMemcpyAsync(h_starts.data(), d_starts, (size_t)nt * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    FM_HIP(m, hipStreamSynchronize(st));
+    m->h_cell_nnz.assign((size_t)P * P, 0);
+    m->h_strat_nnz_off.assign(P + 1, 0);
+    for (int32_t s = 0; s < P; ++s) {
+        m->h_strat_nnz_off[s] = h_starts[(size_t)s * (P + 1)];
+        for (int32_t q = 0; q < P; ++q) {
+            const int32_t p = ((q - s) % P + P) % P;
+            m->h_cell_nnz[(size_t)p * P + q] = h_starts[(size_t)s * (P + 1) + q + 1] - h_starts[(size_t)s * (P + 1) + q];
+        }
+    }
+    m->h_strat_nnz_off[P] = m->nnz;
+    fm_dev_free(m, d_starts);
+    fm_dev_free(m, d_cb);
+    FM_TRY(fm_build_long_index(m, m->s_colptr, (int64_t)P * m->D, m->D, P, &m->lstrat, st));
+    FM_HIP(m, hipStreamSynchronize(st));
+    fm_drop_workspace(m);
+    return FM_OK;
+}

@@ -1,0 +1,187 @@
+// Internal declarations shared by the translation units of libfm_mi355x.so.
+// gfx950 only: 64-lane wavefronts are assumed throughout.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "fm.h"
+
+constexpr int FM_WAVE = 64;
+constexpr int FM_BLOCK = 256;             // threads per workgroup of the pass kernels
+constexpr int FM_WAVES = FM_BLOCK / FM_WAVE;
+constexpr int FM_SEG = 512;               // entries per work item of a long column
+constexpr int FM_MAXP = 4096;
+
+enum fm_kernel_id {
+    FMK_ROWS_FORWARD = 0,
+    FMK_ROWS_REFRESH,
+    FMK_COLS,
+    FMK_COLS_LONG,
+    FMK_COLS_FINISH,
+    FMK_REDUCE,
+    FMK_BIAS,
+    FMK_COUNT
+};
+
+// Work items for columns longer than FM_SEG entries (of one matrix, or of all strata
+// concatenated).  Offsets in item_beg are global offsets into the entry arrays.
+struct LongIndex {
+    int64_t nlong = 0, nitems = 0;
+    int32_t* long_col = nullptr;    // [nlong] column id
+    int64_t* long_first = nullptr;  // [nlong+1] first item of each long column
+    int32_t* item_col = nullptr;    // [nitems]
+    int64_t* item_beg = nullptr;    // [nitems]
+    int32_t* item_len = nullptr;    // [nitems]
+    std::vector<int64_t> h_long_off, h_item_off;  // per-stratum ranges (size P+1), or {0,nlong}
+};
+
+struct ProfRec {
+    int id;
+    hipEvent_t a, b;
+};
+
+struct fm_matrix {
+    int64_t N = 0, D = 0, nnz = 0;
+    // CSR
+    int64_t* rowptr = nullptr;
+    int32_t* col = nullptr;
+    float* val = nullptr;
+    // CSC
+    bool has_csc = false;
+    int64_t* colptr = nullptr;
+    int32_t* crow = nullptr;
+    float* cval = nullptr;
+    LongIndex lfull;
+    // double partition and per-stratum matrices
+    int32_t P = 0;
+    std::vector<int64_t> h_rb, h_cb, h_cell_nnz, h_strat_nnz_off;  // bounds, P*P table, P+1 offsets
+    int64_t* d_rb = nullptr;
+    int64_t* s_rowptr = nullptr;  // [P*N+1] global offsets into s_col/s_val
+    int32_t* s_col = nullptr;
+    float* s_val = nullptr;
+    int64_t* s_colptr = nullptr;  // [P*D+1] global offsets into s_row/s_cval
+    int32_t* s_row = nullptr;
+    float* s_cval = nullptr;
+    LongIndex lstrat;
+    // workspace, sized for wsK
+    int32_t wsK = 0;
+    float *G = nullptr, *a = nullptr, *q = nullptr, *r = nullptr;
+    float* dV = nullptr;    // [D*K] last step's change of V
+    float2* dwn = nullptr;  // [D] (change of w_j, change of |v_j|^2)
+    float* part_acc = nullptr;  // [max items * K]
+    float2* part_gs = nullptr;  // [max items]
+    float* row_part = nullptr;  // [2 * row blocks]: loss, sum r
+    float* col_part = nullptr;  // [2 * col blocks]: sum w^2, sum V^2
+    double* scal = nullptr;     // device scalars: 0 loss, 1 sum r, 2 |w|^2, 3 |V|^2
+    double* h_scal = nullptr;   // pinned mirror
+    bool aux_full = false;      // a, q valid (not only G, r)
+    // profiling
+    bool prof = false;
+    std::vector<ProfRec> prof_recs;
+    std::vector<hipEvent_t> prof_pool;
+    int64_t prof_launches[FMK_COUNT] = {0};
+    double prof_ms[FMK_COUNT] = {0};
+    // bookkeeping
+    std::vector<void*> allocs;
+    std::string err;
+};
+
+// ---- helpers (fm_api.hip) ----
+int fm_fail(fm_matrix* m, int code, const char* fmt, ...);
+int fm_dev_alloc(fm_matrix* m, void** p, size_t bytes);
+void fm_dev_free(fm_matrix* m, void* p);
+void fm_drop_workspace(fm_matrix* m);  // forces reallocation after the structures changed
+
+#define FM_HIP(m, expr)                                                                  \
+    do {                                                                                 \
+        hipError_t e__ = (expr);                                                         \
+        if (e__ != hipSuccess)                                                           \
+            return fm_fail((m), FM_EHIP, "%s failed: %s", #expr, hipGetErrorString(e__)); \
+    } while (0)
+
+#define FM_TRY(expr)          \
+    do {                      \
+        int rc__ = (expr);    \
+        if (rc__ != FM_OK) return rc__; \
+    } while (0)
+
+struct ProfScope {
+    fm_matrix* m;
+    hipStream_t st;
+    int id;
+    hipEvent_t a = nullptr, b = nullptr;
+    ProfScope(fm_matrix* m_, hipStream_t st_, int id_);
+    ~ProfScope();
+};
+
+// ---- build (fm_build.hip) ----
+int fm_scan_exclusive_i64(fm_matrix* m, int64_t* d, int64_t n, hipStream_t st);
+int fm_sort_by_key_u32(fm_matrix* m, uint32_t* keys, uint32_t* idx, uint32_t* keys_alt, uint32_t* idx_alt,
+                       int64_t n, int bits, hipStream_t st, bool* result_in_alt);
+int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
+                        LongIndex* out, hipStream_t st);
+
+// ---- pass kernels (fm_rows.hip / fm_cols.hip / fm_reduce.hip) ----
+struct RowArgs {
+    int64_t N;
+    int32_t K;
+    const int64_t* rowptr;
+    const int32_t* col;
+    const float* val;
+    const float* w0;    // device scalar
+    const float* w;     // forward: weights
+    const float* V;     // forward: factors ; refresh: dV
+    const float2* dwn;  // refresh: (dw_j, dn_j)
+    const float* y;     // nullable
+    float *yhat, *a, *G, *q, *r;  // forward: nullable outputs ; refresh: in/out aggregates
+    float* row_part;    // nullable: [2*gridDim] loss and sum r per block
+    int32_t loss;
+    float s;
+};
+int fm_launch_rows(fm_matrix* m, const RowArgs& A, bool refresh, hipStream_t st);
+int64_t fm_rows_grid(int64_t N, int32_t K);
+
+struct ColArgs {
+    int64_t D;
+    int32_t K;
+    const int64_t* ptr;  // [D+1] global offsets
+    const int32_t* row;
+    const float* val;
+    const float* r;
+    const float* G;
+    float* w;        // updated in place when update
+    float* V;
+    float* grad_w;   // !update: outputs (nullable)
+    float* grad_V;
+    float* dV;       // delta outputs (nullable)
+    float2* dwn;
+    float* col_part;  // nullable: [2*gridDim] sum w^2, sum V^2 per block (kernel over all columns only)
+    float lambda_w, lambda_v, eta;
+    // regulariser share: rho = 1 when rb == nullptr, else |I_p|/N with p = (colblock(j) - s) mod P
+    const int64_t* rb;
+    int64_t N;
+    int32_t P, s;
+    // long-column items
+    const int32_t* long_col;
+    const int64_t* long_first;
+    const int32_t* item_col;
+    const int64_t* item_beg;
+    const int32_t* item_len;
+    int64_t nlong, nitems;        // counts of this launch
+    int64_t long_base, item_base;  // first long column / first item of this launch (absolute ids)
+    float* part_acc;                // indexed by absolute item id
+    float2* part_gs;
+};
+int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st);
+int64_t fm_cols_grid(int64_t D, int32_t K);
+
+int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st);
+int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, bool square, double* out1, hipStream_t st);
+int fm_bias_step(fm_matrix* m, float* w0, const double* rsum, float eta, float* grad_w0_out, hipStream_t st);
+
+// lanes per row/column group and floats per lane for a given K; false if K unsupported
+bool fm_shape_for_K(int32_t K, int* vec, int* lanes);

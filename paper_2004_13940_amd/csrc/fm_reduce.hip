@@ -1,0 +1,109 @@
+// Deterministic reductions (fixed order, fp64 accumulation) and the bias step.
+#include "fm_device.h"
+#include "fm_internal.h"
+
+namespace {
+
+constexpr int RED_THREADS = 1024;
+constexpr int RED_BLOCKS = 2048;
+
+__device__ __forceinline__ double block_sum_1024(double v, double* sh)
+{
+    v = fm_wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) sh[wave] = v;
+    __syncthreads();
+    double t = 0.0;
+    if (threadIdx.x == 0)
+        for (int i = 0; i < RED_THREADS / 64; ++i) t += sh[i];
+    __syncthreads();
+    return t;  // valid in thread 0
+}
+
+// part holds nblocks interleaved pairs (x0,x1); out2 receives the two totals.
+__global__ __launch_bounds__(RED_THREADS) void k_reduce_pairs(const float* __restrict__ part, int64_t nblocks,
+                                                              double* __restrict__ out2)
+{
+    __shared__ double sh[RED_THREADS / 64];
+    double s0 = 0.0, s1 = 0.0;
+    const float2* p2 = reinterpret_cast<const float2*>(part);
+    for (int64_t i = threadIdx.x; i < nblocks; i += RED_THREADS) {
+        const float2 v = p2[i];
+        s0 += (double)v.x;
+        s1 += (double)v.y;
+    }
+    const double t0 = block_sum_1024(s0, sh);
+    const double t1 = block_sum_1024(s1, sh);
+    if (threadIdx.x == 0) {
+        out2[0] = t0;
+        out2[1] = t1;
+    }
+}
+
+__global__ __launch_bounds__(RED_THREADS) void k_reduce_stage1(const float* __restrict__ x, int64_t n, int square,
+                                                               double* __restrict__ tmp)
+{
+    __shared__ double sh[RED_THREADS / 64];
+    const int64_t chunk = (n + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = (int64_t)blockIdx.x * chunk;
+    const int64_t hi = lo + chunk < n ? lo + chunk : n;
+    double s = 0.0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += RED_THREADS) {
+        const double v = (double)x[i];
+        s += square ? v * v : v;
+    }
+    const double t = block_sum_1024(s, sh);
+    if (threadIdx.x == 0) tmp[blockIdx.x] = t;
+}
+
+__global__ __launch_bounds__(RED_THREADS) void k_reduce_stage2(const double* __restrict__ tmp, int nb,
+                                                               double* __restrict__ out1)
+{
+    __shared__ double sh[RED_THREADS / 64];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < nb; i += RED_THREADS) s += tmp[i];
+    const double t = block_sum_1024(s, sh);
+    if (threadIdx.x == 0) out1[0] = t;
+}
+
+__global__ void k_bias(float* w0, const double* rsum, float eta, float* grad_out)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        const float g = (float)rsum[0];
+        if (grad_out != nullptr) grad_out[0] = g;
+        if (w0 != nullptr) w0[0] = w0[0] - eta * g;
+    }
+}
+
+}  // namespace
+
+int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st)
+{
+    ProfScope ps(m, st, FMK_REDUCE);
+    hipLaunchKernelGGL(k_reduce_pairs, dim3(1), dim3(RED_THREADS), 0, st, part, nblocks, out2);
+    FM_HIP(m, hipGetLastError());
+    return FM_OK;
+}
+
+int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, bool square, double* out1, hipStream_t st)
+{
+    // scal[8..8+RED_BLOCKS) is the stage-1 scratch
+    double* tmp = m->scal + 8;
+    int nb = (int)((n + 16 * RED_THREADS - 1) / (16 * RED_THREADS));
+    if (nb < 1) nb = 1;
+    if (nb > RED_BLOCKS) nb = RED_BLOCKS;
+    ProfScope ps(m, st, FMK_REDUCE);
+    hipLaunchKernelGGL(k_reduce_stage1, dim3(nb), dim3(RED_THREADS), 0, st, x, n, square ? 1 : 0, tmp);
+    FM_HIP(m, hipGetLastError());
+    hipLaunchKernelGGL(k_reduce_stage2, dim3(1), dim3(RED_THREADS), 0, st, (const double*)tmp, nb, out1);
+    FM_HIP(m, hipGetLastError());
+    return FM_OK;
+}
+
+int fm_bias_step(fm_matrix* m, float* w0, const double* rsum, float eta, float* grad_w0_out, hipStream_t st)
+{
+    ProfScope ps(m, st, FMK_BIAS);
+    hipLaunchKernelGGL(k_bias, dim3(1), dim3(64), 0, st, w0, rsum, eta, grad_w0_out);
+    FM_HIP(m, hipGetLastError());
+    return FM_OK;
+}
