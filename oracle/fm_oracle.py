@@ -166,6 +166,15 @@ def full_epoch(X: Matrix, y, w0, w, V, *, loss, s, lambda_w, lambda_v, eta, upda
     return float(w0), w, V, obj
 
 
+def multiplier_from_aux(loss, s, w0, a, G, q, y):
+    """r for every row from stored aggregates (prediction by eq. fm_model2, no pass over X)."""
+    a, G, q, y = _c(a, np.float64), _c(G, np.float64), _c(q, np.float64), _c(y, np.float64)
+    r = np.empty(len(a))
+    _L().oracle_multiplier_from_aux(_i64(len(a)), _i32(G.shape[1]), _i32(loss), _f64(s), _f64(w0), _p(a), _p(G),
+                                    _p(q), _p(y), _p(r))
+    return r
+
+
 def block_bounds(n, P):
     """Boundaries of the contiguous floor split of n items into P blocks."""
     return np.array([_L().oracle_block_bound(_i64(n), _i64(P), _i64(b)) for b in range(P + 1)], np.int64)

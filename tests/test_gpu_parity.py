@@ -257,8 +257,13 @@ def _run_stratified_epochs(B, wl, m, p, X, dev, host, epochs, check_strata=False
                 m.fm_stratified_step(p, s, d_y, d_w0, d_w, d_V)
                 m.fm_get_aux(wl.K, a, G, q, r)
                 torch.cuda.synchronize()
-                for name, t in (("a", a), ("G", G), ("q", q), ("r", r), ("w", d_w), ("V", d_V)):
+                for name, t in (("a", a), ("G", G), ("q", q), ("w", d_w), ("V", d_V)):
                     assert_close(t.cpu().numpy(), snaps[s][name], f"{name} after stratum {s} of epoch {ep}")
+                # the library keeps r current with the refreshed aggregates; the oracle recomputes it
+                # at the start of the next cell step: same function of the same aggregates
+                want_r = O.multiplier_from_aux(wl.loss, wl.loss_scale, w0, snaps[s]["a"], snaps[s]["G"],
+                                               snaps[s]["q"], wl.y)
+                assert_close(r.cpu().numpy(), want_r, f"r after stratum {s} of epoch {ep}")
             m.fm_stratified_end(p, d_w0)
             obj = None
         else:
