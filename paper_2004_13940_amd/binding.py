@@ -49,6 +49,9 @@ def load() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2004_13940_amd.build` "
                                     "(there is no CPU fallback)")
+        # PyTorch ships its own HIP runtime under the same soname; it must be the one this
+        # library binds to, so that streams and device pointers of torch tensors are valid here
+        import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
         for name in EXPORTS:
             getattr(lib, name).restype = ctypes.c_int
