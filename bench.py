@@ -42,6 +42,8 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=2_000_000, help="rows of the workload the oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stratified", action="store_true", help="also time fm_stratified_epoch (reported in extra)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch a plain 1 GiB device copy three times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); nothing here uses a second device")
@@ -74,6 +76,13 @@ def main():
     V = torch.from_numpy(wl.V).cuda().reshape(-1)
     y = torch.from_numpy(wl.y).cuda()
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         m.fm_sgd_epoch(p, y, w0, w, V)
     torch.cuda.synchronize()
@@ -93,10 +102,11 @@ def main():
     prof = m.fm_profile_read()
     m.fm_profile_enable(False)
     counts = np.bincount(wl.col, minlength=wl.D)
-    long_mask = counts > 512
+    seg = int(os.environ.get("FM_SEG", "128"))  # the library's default item length
+    long_mask = counts > seg
     nnz_long = int(counts[long_mask].sum())
     nlong = int(long_mask.sum())
-    items = int(((counts[long_mask] + 511) // 512).sum())
+    items = int(((counts[long_mask] + seg - 1) // seg).sum())  # lower bound: panel cuts add a few
     ab = algorithmic_bytes(wl.N, wl.D, wl.K, wl.nnz, nnz_long, items, nlong)
     kern = {k: {"launches": n, "avg_ms": ms / n} for k, (n, ms) in prof.items() if n > 0}
     dominant = max(kern, key=lambda k: kern[k]["avg_ms"] * kern[k]["launches"])

@@ -243,10 +243,10 @@ static int check_params(fm_matrix* m, const fm_params* p)
 
 void fm_drop_workspace(fm_matrix* m)
 {
-    for (void* p : {(void*)m->G, (void*)m->a, (void*)m->q, (void*)m->r, (void*)m->dV, (void*)m->dwn,
-                    (void*)m->part_acc, (void*)m->part_gs, (void*)m->row_part, (void*)m->col_part})
+    for (void* p : {(void*)m->aux, (void*)m->dV, (void*)m->dwn, (void*)m->part_acc, (void*)m->part_gs,
+                    (void*)m->row_part, (void*)m->col_part})
         fm_dev_free(m, p);
-    m->G = m->a = m->q = m->r = m->dV = m->part_acc = m->row_part = m->col_part = nullptr;
+    m->aux = m->dV = m->part_acc = m->row_part = m->col_part = nullptr;
     m->dwn = nullptr;
     m->part_gs = nullptr;
     m->wsK = 0;
@@ -259,10 +259,7 @@ static int ensure_ws(fm_matrix* m, int32_t K)
     if (m->wsK == K) return FM_OK;
     fm_drop_workspace(m);
     const size_t N = (size_t)m->N, D = (size_t)m->D;
-    FM_TRY(fm_dev_alloc(m, (void**)&m->G, N * K * sizeof(float)));
-    FM_TRY(fm_dev_alloc(m, (void**)&m->a, N * sizeof(float)));
-    FM_TRY(fm_dev_alloc(m, (void**)&m->q, N * sizeof(float)));
-    FM_TRY(fm_dev_alloc(m, (void**)&m->r, N * sizeof(float)));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->aux, N * (size_t)fm_aux_stride(K) * sizeof(float)));
     const int64_t items = std::max<int64_t>(m->lfull.nitems, m->lstrat.nitems);
     FM_TRY(fm_dev_alloc(m, (void**)&m->part_acc, (size_t)std::max<int64_t>(items, 1) * K * sizeof(float)));
     FM_TRY(fm_dev_alloc(m, (void**)&m->part_gs, (size_t)std::max<int64_t>(items, 1) * sizeof(float2)));
@@ -294,12 +291,31 @@ static void fill_long(ColArgs& A, const LongIndex& li, int32_t s, bool strat)
     A.item_col = li.item_col;
     A.item_beg = li.item_beg;
     A.item_len = li.item_len;
+    A.order = strat ? nullptr : li.order;
+    for (int x = 0; x <= FM_XCDS; ++x) A.list_off[x] = li.list_off[x];
+    A.vlong = strat ? nullptr : li.vlong;
+    A.nvlong = strat ? 0 : li.nvlong;
+    A.vlong_items = fm_tune().vlong;
+    A.seg = fm_tune().seg;
+}
+
+// RowArgs outputs pointing into the handle's aggregate rows [G | r | a | q | pad]
+static void aux_outputs(fm_matrix* m, int32_t K, RowArgs& A, bool with_aq)
+{
+    const int64_t gs = fm_aux_stride(K);
+    A.G = m->aux;
+    A.gs = gs;
+    A.ss = gs;
+    A.r = m->aux + K;
+    A.a = with_aq ? m->aux + K + 1 : nullptr;
+    A.q = with_aq ? m->aux + K + 2 : nullptr;
 }
 
 // ---------------------------------------------------------------- forward ----
 
+// mode 0: caller arrays (dense); 1: handle's aggregate rows, G and r; 2: handle's rows, G r a q
 static int run_forward(fm_matrix* m, const fm_params* p, const float* y, const float* w0, const float* w,
-                       const float* V, float* yhat, float* a, float* G, float* q, float* r, bool want_sums,
+                       const float* V, float* yhat, float* a, float* G, float* q, float* r, int mode, bool want_sums,
                        hipStream_t st)
 {
     RowArgs A;
@@ -314,10 +330,16 @@ static int run_forward(fm_matrix* m, const fm_params* p, const float* y, const f
     A.V = V;
     A.y = y;
     A.yhat = yhat;
-    A.a = a;
-    A.G = G;
-    A.q = q;
-    A.r = r;
+    if (mode == 0) {
+        A.a = a;
+        A.G = G;
+        A.q = q;
+        A.r = r;
+        A.gs = p->K;
+        A.ss = 1;
+    } else {
+        aux_outputs(m, p->K, A, mode == 2);
+    }
     A.row_part = (want_sums && y != nullptr) ? m->row_part : nullptr;
     A.loss = p->loss;
     A.s = p->loss_scale;
@@ -340,7 +362,7 @@ extern "C" int fm_forward(fm_matrix* m, const fm_params* p, const float* y, cons
         if (loss_sum) *loss_sum = 0.0;
         return FM_OK;
     }
-    FM_TRY(run_forward(m, p, y, w0, w, V, yhat, a, G, q, r, loss_sum != nullptr, st));
+    FM_TRY(run_forward(m, p, y, w0, w, V, yhat, a, G, q, r, 0, loss_sum != nullptr, st));
     if (loss_sum != nullptr) {
         FM_HIP(m, hipMemcpyAsync(m->h_scal, m->scal, 2 * sizeof(double), hipMemcpyDeviceToHost, st));
         FM_HIP(m, hipStreamSynchronize(st));
@@ -375,7 +397,7 @@ extern "C" int fm_gradient(fm_matrix* m, const fm_params* p, const float* r, con
     hipStream_t st = (hipStream_t)hip_stream;
     FM_TRY(ensure_ws(m, p->K));
     if (grad_w0 != nullptr) {
-        FM_TRY(fm_reduce_sum(m, r, m->N, false, m->scal + 1, st));
+        FM_TRY(fm_reduce_sum(m, r, m->N, 1, false, m->scal + 1, st));
         FM_TRY(fm_bias_step(m, nullptr, m->scal + 1, 0.f, grad_w0, st));
     }
     if (m->D == 0 || (grad_w == nullptr && grad_V == nullptr)) return FM_OK;
@@ -386,6 +408,8 @@ extern "C" int fm_gradient(fm_matrix* m, const fm_params* p, const float* r, con
     A.val = m->cval;
     A.r = r;
     A.G = G;
+    A.gs = p->K;
+    A.rs = 1;
     A.w = const_cast<float*>(w);
     A.V = const_cast<float*>(V);
     A.grad_w = grad_w;
@@ -411,7 +435,7 @@ extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, fl
         return FM_OK;
     }
     // steps 1-3: G, r, loss and sum r
-    FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, m->G, nullptr, m->r, true, st));
+    FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, nullptr, nullptr, nullptr, 1, true, st));
     m->aux_full = false;
     // steps 4-5 fused: gradient of every column and the step on w, V
     ColArgs A;
@@ -419,8 +443,9 @@ extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, fl
     A.ptr = m->colptr;
     A.row = m->crow;
     A.val = m->cval;
-    A.r = m->r;
-    A.G = m->G;
+    A.r = m->aux + p->K;
+    A.G = m->aux;
+    A.gs = A.rs = fm_aux_stride(p->K);
     A.w = w;
     A.V = V;
     A.col_part = objective != nullptr ? m->col_part : nullptr;
@@ -449,7 +474,7 @@ extern "C" int fm_stratified_begin(fm_matrix* m, const fm_params* p, const float
         return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
     hipStream_t st = (hipStream_t)hip_stream;
     FM_TRY(ensure_strat_ws(m, p->K));
-    FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, m->a, m->G, m->q, m->r, false, st));
+    FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, nullptr, nullptr, nullptr, 2, false, st));
     m->aux_full = true;
     return FM_OK;
 }
@@ -471,8 +496,9 @@ extern "C" int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, c
     A.ptr = m->s_colptr + (int64_t)s * m->D;
     A.row = m->s_row;
     A.val = m->s_cval;
-    A.r = m->r;
-    A.G = m->G;
+    A.r = m->aux + p->K;
+    A.G = m->aux;
+    A.gs = A.rs = fm_aux_stride(p->K);
     A.w = w;
     A.V = V;
     A.dV = m->dV;
@@ -502,10 +528,7 @@ extern "C" int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, c
     R.V = m->dV;
     R.dwn = m->dwn;
     R.y = y;
-    R.a = m->a;
-    R.G = m->G;
-    R.q = m->q;
-    R.r = m->r;
+    aux_outputs(m, p->K, R, true);
     R.loss = p->loss;
     R.s = p->loss_scale;
     return fm_launch_rows(m, R, true, st);
@@ -519,7 +542,7 @@ extern "C" int fm_stratified_end(fm_matrix* m, const fm_params* p, float* w0, vo
     if (w0 == nullptr) return fm_fail(m, FM_EINVAL, "w0 must not be NULL");
     hipStream_t st = (hipStream_t)hip_stream;
     if (p->update_w0) {
-        FM_TRY(fm_reduce_sum(m, m->r, m->N, false, m->scal + 1, st));
+        FM_TRY(fm_reduce_sum(m, m->aux + p->K, m->N, fm_aux_stride(p->K), false, m->scal + 1, st));
         FM_TRY(fm_bias_step(m, w0, m->scal + 1, p->eta, nullptr, st));
     }
     return FM_OK;
@@ -533,9 +556,9 @@ extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float
     FM_TRY(fm_stratified_end(m, p, w0, hip_stream));
     if (objective != nullptr) {
         hipStream_t st = (hipStream_t)hip_stream;
-        FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, m->a, m->G, m->q, m->r, true, st));
-        FM_TRY(fm_reduce_sum(m, w, m->D, true, m->scal + 2, st));
-        FM_TRY(fm_reduce_sum(m, V, m->D * (int64_t)p->K, true, m->scal + 3, st));
+        FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, nullptr, nullptr, nullptr, 2, true, st));
+        FM_TRY(fm_reduce_sum(m, w, m->D, 1, true, m->scal + 2, st));
+        FM_TRY(fm_reduce_sum(m, V, m->D * (int64_t)p->K, 1, true, m->scal + 3, st));
         FM_HIP(m, hipMemcpyAsync(m->h_scal, m->scal, 4 * sizeof(double), hipMemcpyDeviceToHost, st));
         FM_HIP(m, hipStreamSynchronize(st));
         objective[0] = (double)p->loss_scale * m->h_scal[0];
@@ -552,10 +575,6 @@ extern "C" int fm_get_aux(const fm_matrix* m, float* a, float* G, float* q, floa
     if ((a != nullptr || q != nullptr) && !m->aux_full)
         return fm_fail(mm, FM_ESTATE, "a and q are only held after a stratified call");
     hipStream_t st = (hipStream_t)hip_stream;
-    const size_t N = (size_t)m->N;
-    if (a) FM_HIP(mm, hipMemcpyAsync(a, m->a, N * sizeof(float), hipMemcpyDeviceToDevice, st));
-    if (G) FM_HIP(mm, hipMemcpyAsync(G, m->G, N * m->wsK * sizeof(float), hipMemcpyDeviceToDevice, st));
-    if (q) FM_HIP(mm, hipMemcpyAsync(q, m->q, N * sizeof(float), hipMemcpyDeviceToDevice, st));
-    if (r) FM_HIP(mm, hipMemcpyAsync(r, m->r, N * sizeof(float), hipMemcpyDeviceToDevice, st));
+    FM_TRY(fm_unpack_aux(mm, a, G, q, r, st));
     return FM_OK;
 }

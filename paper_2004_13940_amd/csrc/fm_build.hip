@@ -2,6 +2,8 @@
 // the per-stratum matrices of the double partition, and the work-item lists for long
 // columns.  Everything here is deterministic (integer atomics are only used for
 // counts, whose totals do not depend on the order of the additions).
+#include <stdlib.h>
+
 #include "fm_device.h"
 #include "fm_internal.h"
 
@@ -232,7 +234,7 @@ constexpr int LI_T = 256;
 constexpr int LI_E = 4;
 constexpr int LI_TILE = LI_T * LI_E;
 
-__global__ __launch_bounds__(LI_T) void k_long_count(const int64_t* __restrict__ ptr, int64_t ncols,
+__global__ __launch_bounds__(LI_T) void k_long_count(const int64_t* __restrict__ ptr, int64_t ncols, int seg,
                                                      int64_t* __restrict__ tile_long, int64_t* __restrict__ tile_items)
 {
     __shared__ int64_t sh[2][SCAN_T];
@@ -242,9 +244,9 @@ __global__ __launch_bounds__(LI_T) void k_long_count(const int64_t* __restrict__
         const int64_t c = base + u;
         if (c < ncols) {
             const int64_t len = ptr[c + 1] - ptr[c];
-            if (len > FM_SEG) {
+            if (len > seg) {
                 nl += 1;
-                ni += (len + FM_SEG - 1) / FM_SEG;
+                ni += (len + seg - 1) / seg;
             }
         }
     }
@@ -258,6 +260,7 @@ __global__ __launch_bounds__(LI_T) void k_long_count(const int64_t* __restrict__
 }
 
 __global__ __launch_bounds__(LI_T) void k_long_fill(const int64_t* __restrict__ ptr, int64_t ncols, int64_t D,
+                                                    int seg, int with_items,
                                                     const int64_t* __restrict__ tile_long,
                                                     const int64_t* __restrict__ tile_items,
                                                     int32_t* __restrict__ long_col, int64_t* __restrict__ long_vcol,
@@ -271,9 +274,9 @@ __global__ __launch_bounds__(LI_T) void k_long_fill(const int64_t* __restrict__ 
         const int64_t c = base + u;
         if (c < ncols) {
             const int64_t len = ptr[c + 1] - ptr[c];
-            if (len > FM_SEG) {
+            if (len > seg) {
                 nl += 1;
-                ni += (len + FM_SEG - 1) / FM_SEG;
+                ni += (len + seg - 1) / seg;
             }
         }
     }
@@ -283,19 +286,115 @@ __global__ __launch_bounds__(LI_T) void k_long_fill(const int64_t* __restrict__ 
         const int64_t c = base + u;
         if (c >= ncols) break;
         const int64_t b = ptr[c], len = ptr[c + 1] - b;
-        if (len <= FM_SEG) continue;
+        if (len <= seg) continue;
         const int32_t j = (int32_t)(c % D);
         long_col[lpos] = j;
         long_vcol[lpos] = c;
-        long_first[lpos] = ipos;
         ++lpos;
-        for (int64_t o = 0; o < len; o += FM_SEG) {
+        if (!with_items) continue;
+        long_first[lpos - 1] = ipos;
+        for (int64_t o = 0; o < len; o += seg) {
             item_col[ipos] = j;
             item_beg[ipos] = b + o;
-            item_len[ipos] = (int32_t)((len - o) < FM_SEG ? (len - o) : FM_SEG);
+            item_len[ipos] = (int32_t)((len - o) < seg ? (len - o) : seg);
             ++ipos;
         }
     }
+}
+
+
+// ---------------------------------------------------- full-matrix items ----
+// first position in rows[beg,end) (ascending) whose row is >= bound
+__device__ __forceinline__ int64_t first_row_at_least(const int32_t* __restrict__ rows, int64_t beg, int64_t end,
+                                                      int64_t bound)
+{
+    int64_t lo = beg, hi = end;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)rows[mid] < bound) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// Items of every long column of the full matrix.  A column with fewer than heavy_min
+// entries is cut into consecutive segments of `seg` entries.  A heavy column is first
+// cut at the boundaries of the row panels [b*panel, (b+1)*panel) and every piece then
+// into segments of `seg`; its items carry the key (b % FM_XCDS, b / FM_XCDS) so that the
+// stable sort by key hands panel b to XCD b % FM_XCDS in ascending panel order.  Other
+// items get the last position of the list (slot % FM_XCDS) and run after the panels.
+// One workgroup per long column; pass 0 counts, pass 1 fills.
+__global__ __launch_bounds__(256) void k_full_items(const int64_t* __restrict__ colptr, const int32_t* __restrict__ crow,
+                                                    const int32_t* __restrict__ long_col, int64_t N, int seg,
+                                                    int64_t panel, int64_t heavy_min, int64_t maxpos, int pass,
+                                                    int64_t* __restrict__ nitems, const int64_t* __restrict__ long_first,
+                                                    int32_t* __restrict__ item_col, int64_t* __restrict__ item_beg,
+                                                    int32_t* __restrict__ item_len, uint32_t* __restrict__ item_key)
+{
+    __shared__ int64_t sh[2][SCAN_T];
+    const int64_t lc = blockIdx.x;
+    const int32_t j = long_col[lc];
+    const int64_t beg = colptr[j], end = colptr[j + 1], cnt = end - beg;
+    const int64_t first = pass ? long_first[lc] : 0;
+    if (cnt < heavy_min) {
+        const int64_t nit = (cnt + seg - 1) / seg;
+        if (!pass) {
+            if (threadIdx.x == 0) nitems[lc] = nit;
+            return;
+        }
+        for (int64_t k = threadIdx.x; k < nit; k += blockDim.x) {
+            const int64_t slot = first + k;
+            item_col[slot] = j;
+            item_beg[slot] = beg + k * seg;
+            item_len[slot] = (int32_t)((cnt - k * seg) < seg ? (cnt - k * seg) : seg);
+            item_key[slot] = (uint32_t)((slot % FM_XCDS) * (maxpos + 1) + maxpos);
+        }
+        return;
+    }
+    const int64_t npanels = (N + panel - 1) / panel;
+    int64_t running = 0;
+    for (int64_t b0 = 0; b0 < npanels; b0 += blockDim.x) {
+        const int64_t b = b0 + threadIdx.x;
+        int64_t lo = 0, hi = 0;
+        if (b < npanels) {
+            lo = first_row_at_least(crow, beg, end, b * panel);
+            hi = first_row_at_least(crow, lo, end, (b + 1) * panel);
+        }
+        const int64_t nb = (hi - lo + seg - 1) / seg;
+        int64_t total;
+        const int64_t off = block_exclusive_256(nb, sh, &total);
+        if (pass) {
+            for (int64_t k = 0; k < nb; ++k) {
+                const int64_t slot = first + running + off + k;
+                item_col[slot] = j;
+                item_beg[slot] = lo + k * seg;
+                item_len[slot] = (int32_t)((hi - lo - k * seg) < seg ? (hi - lo - k * seg) : seg);
+                item_key[slot] = (uint32_t)((b % FM_XCDS) * (maxpos + 1) + b / FM_XCDS);
+            }
+        }
+        running += total;
+    }
+    if (!pass && threadIdx.x == 0) nitems[lc] = running;
+}
+
+__global__ void k_iota_u32(uint32_t* __restrict__ x, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) x[i] = (uint32_t)i;
+}
+
+// list_off[x] = number of sorted keys smaller than x * (maxpos+1), x = 0..FM_XCDS
+__global__ void k_list_offsets(const uint32_t* __restrict__ keys, int64_t n, int64_t maxpos,
+                               int64_t* __restrict__ list_off)
+{
+    const int x = threadIdx.x;
+    if (x > FM_XCDS) return;
+    const int64_t bound = (int64_t)x * (maxpos + 1);
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)keys[mid] < bound) lo = mid + 1; else hi = mid;
+    }
+    list_off[x] = lo;
 }
 
 inline unsigned blocks_for(int64_t n, int t) { return (unsigned)((n + t - 1) / t); }
@@ -303,6 +402,13 @@ inline unsigned blocks_for(int64_t n, int t) { return (unsigned)((n + t - 1) / t
 }  // namespace
 
 // ---------------------------------------------------------------- hosts ----
+
+static int bits_for(int64_t maxval)
+{
+    int b = 0;
+    while (b < 32 && ((int64_t)1 << b) <= maxval) ++b;
+    return b;
+}
 
 int fm_scan_exclusive_i64(fm_matrix* m, int64_t* d, int64_t n, hipStream_t st)
 {
@@ -368,7 +474,8 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
     FM_TRY(fm_dev_alloc(m, (void**)&ti, (size_t)(ntiles + 1) * sizeof(int64_t)));
     FM_HIP(m, hipMemsetAsync(tl, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
     FM_HIP(m, hipMemsetAsync(ti, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
-    hipLaunchKernelGGL(k_long_count, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, tl, ti);
+    const int seg = fm_tune().seg;
+    hipLaunchKernelGGL(k_long_count, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, seg, tl, ti);
     FM_HIP(m, hipGetLastError());
     FM_TRY(fm_scan_exclusive_i64(m, tl, ntiles + 1, st));
     FM_TRY(fm_scan_exclusive_i64(m, ti, ntiles + 1, st));
@@ -386,7 +493,7 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
         FM_TRY(fm_dev_alloc(m, (void**)&out->item_beg, (size_t)nitems * sizeof(int64_t)));
         FM_TRY(fm_dev_alloc(m, (void**)&out->item_len, (size_t)nitems * sizeof(int32_t)));
         FM_TRY(fm_dev_alloc(m, (void**)&vcol, (size_t)nlong * sizeof(int64_t)));
-        hipLaunchKernelGGL(k_long_fill, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, D,
+        hipLaunchKernelGGL(k_long_fill, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, D, seg, 1,
                            (const int64_t*)tl, (const int64_t*)ti, out->long_col, vcol, out->long_first,
                            out->item_col, out->item_beg, out->item_len);
         FM_HIP(m, hipGetLastError());
@@ -410,11 +517,124 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
     return FM_OK;
 }
 
-static int bits_for(int64_t maxval)
+
+
+static int env_int(const char* name, int dflt, int lo, int hi)
 {
-    int b = 0;
-    while (b < 32 && ((int64_t)1 << b) <= maxval) ++b;
-    return b;
+    const char* e = getenv(name);
+    if (e == nullptr || *e == 0) return dflt;
+    const long v = strtol(e, nullptr, 10);
+    return (int)(v < lo ? lo : v > hi ? hi : v);
+}
+
+const FmTune& fm_tune()
+{
+    static const FmTune t = {env_int("FM_SEG", 128, 16, 1 << 20), env_int("FM_PANEL", 8192, 64, 1 << 30),
+                             env_int("FM_HEAVY_PER_PANEL", 4, 1, 1 << 20), env_int("FM_VLONG", 512, 1, 1 << 30)};
+    return t;
+}
+
+int fm_build_full_index(fm_matrix* m, hipStream_t st)
+{
+    LongIndex* out = &m->lfull;
+    const FmTune& T = fm_tune();
+    out->nlong = out->nitems = 0;
+    out->h_long_off.assign(2, 0);
+    out->h_item_off.assign(2, 0);
+    const int64_t D = m->D;
+    if (D <= 0 || m->nnz == 0) return FM_OK;
+    // 1. the long columns, in column order
+    const int64_t ntiles = (D + LI_TILE - 1) / LI_TILE;
+    int64_t *tl = nullptr, *ti = nullptr, *vcol = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&tl, (size_t)(ntiles + 1) * sizeof(int64_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&ti, (size_t)(ntiles + 1) * sizeof(int64_t)));
+    FM_HIP(m, hipMemsetAsync(tl, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
+    FM_HIP(m, hipMemsetAsync(ti, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
+    hipLaunchKernelGGL(k_long_count, dim3((unsigned)ntiles), dim3(LI_T), 0, st, (const int64_t*)m->colptr, D, T.seg, tl, ti);
+    FM_HIP(m, hipGetLastError());
+    FM_TRY(fm_scan_exclusive_i64(m, tl, ntiles + 1, st));
+    int64_t nlong = 0;
+    FM_HIP(m, hipMemcpyAsync(&nlong, tl + ntiles, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    FM_HIP(m, hipStreamSynchronize(st));
+    if (nlong == 0) {
+        fm_dev_free(m, tl);
+        fm_dev_free(m, ti);
+        return FM_OK;
+    }
+    if (nlong > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "too many long columns");
+    FM_TRY(fm_dev_alloc(m, (void**)&out->long_col, (size_t)nlong * sizeof(int32_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&out->long_first, (size_t)(nlong + 1) * sizeof(int64_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&vcol, (size_t)nlong * sizeof(int64_t)));
+    hipLaunchKernelGGL(k_long_fill, dim3((unsigned)ntiles), dim3(LI_T), 0, st, (const int64_t*)m->colptr, D, D, T.seg, 0,
+                       (const int64_t*)tl, (const int64_t*)ti, out->long_col, vcol, (int64_t*)nullptr,
+                       (int32_t*)nullptr, (int64_t*)nullptr, (int32_t*)nullptr);
+    FM_HIP(m, hipGetLastError());
+    // 2. items per long column, then their first ids
+    const int64_t npanels = (m->N + T.panel - 1) / T.panel;
+    // the panel order pays off only when there are many more panels than XCDs
+    const int64_t heavy_min = npanels >= 8 * FM_XCDS
+                                  ? std::max<int64_t>((int64_t)T.heavy_per_panel * npanels, (int64_t)T.seg + 1)
+                                  : INT64_MAX;
+    const int64_t maxpos = (npanels + FM_XCDS - 1) / FM_XCDS;
+    FM_HIP(m, hipMemsetAsync(out->long_first, 0, (size_t)(nlong + 1) * sizeof(int64_t), st));
+    hipLaunchKernelGGL(k_full_items, dim3((unsigned)nlong), dim3(256), 0, st, (const int64_t*)m->colptr,
+                       (const int32_t*)m->crow, (const int32_t*)out->long_col, m->N, T.seg, (int64_t)T.panel, heavy_min,
+                       maxpos, 0, out->long_first, (const int64_t*)nullptr, (int32_t*)nullptr, (int64_t*)nullptr,
+                       (int32_t*)nullptr, (uint32_t*)nullptr);
+    FM_HIP(m, hipGetLastError());
+    FM_TRY(fm_scan_exclusive_i64(m, out->long_first, nlong + 1, st));
+    std::vector<int64_t> h_first((size_t)nlong + 1);
+    FM_HIP(m, hipMemcpyAsync(h_first.data(), out->long_first, (size_t)(nlong + 1) * sizeof(int64_t),
+                             hipMemcpyDeviceToHost, st));
+    FM_HIP(m, hipStreamSynchronize(st));
+    const int64_t nitems = h_first[(size_t)nlong];
+    if (nitems >= (1LL << 32)) return fm_fail(m, FM_ERANGE, "too many column items");
+    FM_TRY(fm_dev_alloc(m, (void**)&out->item_col, (size_t)nitems * sizeof(int32_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&out->item_beg, (size_t)nitems * sizeof(int64_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&out->item_len, (size_t)nitems * sizeof(int32_t)));
+    uint32_t *k0 = nullptr, *i0 = nullptr, *k1 = nullptr, *i1 = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&k0, (size_t)nitems * 4));
+    FM_TRY(fm_dev_alloc(m, (void**)&i0, (size_t)nitems * 4));
+    FM_TRY(fm_dev_alloc(m, (void**)&k1, (size_t)nitems * 4));
+    FM_TRY(fm_dev_alloc(m, (void**)&i1, (size_t)nitems * 4));
+    hipLaunchKernelGGL(k_full_items, dim3((unsigned)nlong), dim3(256), 0, st, (const int64_t*)m->colptr,
+                       (const int32_t*)m->crow, (const int32_t*)out->long_col, m->N, T.seg, (int64_t)T.panel, heavy_min,
+                       maxpos, 1, (int64_t*)nullptr, (const int64_t*)out->long_first, out->item_col, out->item_beg,
+                       out->item_len, k0);
+    FM_HIP(m, hipGetLastError());
+    // 3. processing order: stable sort of the item ids by (XCD list, panel position)
+    hipLaunchKernelGGL(k_iota_u32, dim3(blocks_for(nitems, 256)), dim3(256), 0, st, i0, nitems);
+    FM_HIP(m, hipGetLastError());
+    bool alt = false;
+    FM_TRY(fm_sort_by_key_u32(m, k0, i0, k1, i1, nitems, bits_for((int64_t)FM_XCDS * (maxpos + 1)), st, &alt));
+    int64_t* d_off = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&d_off, (FM_XCDS + 1) * sizeof(int64_t)));
+    hipLaunchKernelGGL(k_list_offsets, dim3(1), dim3(64), 0, st, (const uint32_t*)(alt ? k1 : k0), nitems, maxpos, d_off);
+    FM_HIP(m, hipGetLastError());
+    FM_HIP(m, hipMemcpyAsync(out->list_off, d_off, (FM_XCDS + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    FM_HIP(m, hipStreamSynchronize(st));
+    out->order = alt ? i1 : i0;
+    fm_dev_free(m, alt ? i0 : i1);
+    fm_dev_free(m, k0);
+    fm_dev_free(m, k1);
+    fm_dev_free(m, d_off);
+    // 4. columns with very many items get a workgroup each in the finish step
+    std::vector<int32_t> h_vlong;
+    for (int64_t lc = 0; lc < nlong; ++lc)
+        if (h_first[(size_t)lc + 1] - h_first[(size_t)lc] > T.vlong) h_vlong.push_back((int32_t)lc);
+    out->nvlong = (int64_t)h_vlong.size();
+    if (out->nvlong > 0) {
+        FM_TRY(fm_dev_alloc(m, (void**)&out->vlong, h_vlong.size() * sizeof(int32_t)));
+        FM_HIP(m, hipMemcpy(out->vlong, h_vlong.data(), h_vlong.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    }
+    out->nlong = nlong;
+    out->nitems = nitems;
+    out->h_long_off[1] = nlong;
+    out->h_item_off[1] = nitems;
+    fm_dev_free(m, vcol);
+    fm_dev_free(m, tl);
+    fm_dev_free(m, ti);
+    return FM_OK;
 }
 
 extern "C" int fm_build_csc(fm_matrix* m, void* hip_stream)
@@ -452,7 +672,7 @@ extern "C" int fm_build_csc(fm_matrix* m, void* hip_stream)
         fm_dev_free(m, k1);
         fm_dev_free(m, i1);
     }
-    FM_TRY(fm_build_long_index(m, m->colptr, m->D, m->D, 1, &m->lfull, st));
+    FM_TRY(fm_build_full_index(m, st));
     FM_HIP(m, hipStreamSynchronize(st));
     m->has_csc = true;
     fm_drop_workspace(m);

@@ -8,18 +8,15 @@
 //   grad_V_jk = gV_jk - s2_j v_jk + rho lambda_v v_jk
 //
 // A group of L lanes owns one column (lane `sub` holds VEC latent dimensions).
-// Columns longer than FM_SEG entries are cut into fixed segments: k_cols skips them,
-// k_cols_long writes one partial per segment and k_cols_finish adds the partials of a
-// column in a fixed order, so results are bit-reproducible from run to run.
+// Columns longer than `seg` entries are cut into items: k_cols skips them, k_cols_long
+// writes one partial sum per item, and the finish kernels add the partials of a column
+// in a fixed order, so results are bit-reproducible from run to run.  Items of heavy
+// columns are cut at row-panel boundaries and handed out panel by panel, one panel at a
+// time per XCD, so that the gathered rows of G stay in that XCD's L2.
 #include "fm_device.h"
 #include "fm_internal.h"
 
 namespace {
-
-template <int L>
-struct Chunk {
-    static constexpr int CH = (16 / L) > 0 ? (16 / L) : 1;
-};
 
 // Accumulate one run of entries [beg,end) of a column into acc/gw/s2 (per-lane
 // partials for gw, s2; complete sums for acc's latent slice).
@@ -27,37 +24,16 @@ template <int VEC, int L>
 __device__ __forceinline__ void accumulate_entries(const ColArgs& A, int64_t beg, int64_t end, int sub, int kbase,
                                                    bool kact, float (&acc)[VEC], float& gw, float& s2)
 {
-    constexpr int CH = Chunk<L>::CH;
-    const int K = A.K;
-    for (int64_t e = beg; e < end; e += L * CH) {
-        int ir[CH];
-        float xr[CH];
-#pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const int64_t my = e + u * L + sub;
-            const bool has = my < end;
-            ir[u] = has ? A.row[my] : 0;
-            const float x = has ? A.val[my] : 0.f;
-            const float ri = has ? A.r[ir[u]] : 0.f;
-            xr[u] = x * ri;
-            gw += xr[u];
-            s2 += x * xr[u];
-        }
-#pragma unroll
-        for (int u = 0; u < CH; ++u) {
-#pragma unroll
-            for (int t = 0; t < L; ++t) {
-                const int it = fm_group_bcast<L>(ir[u], t);
-                const float xrt = fm_group_bcast<L>(xr[u], t);
-                if (e + u * L + t < end && kact) {
-                    float g[VEC];
-                    fm_load_vec<VEC>(A.G + (int64_t)it * K + kbase, g);
-#pragma unroll
-                    for (int z = 0; z < VEC; ++z) acc[z] += xrt * g[z];
-                }
-            }
-        }
-    }
+    const float* __restrict__ r = A.r;
+    const int64_t rs = A.rs;
+    float unused = 0.f;
+    fm_gather_accumulate<VEC, L, false>(A.row, A.val, beg, end, A.G, A.gs, sub, kact ? kbase : 0, acc, unused,
+                                        [&](int i, float x) {
+                                            const float xr = x * r[(int64_t)i * rs];
+                                            gw += xr;
+                                            s2 += x * xr;
+                                            return xr;
+                                        });
 }
 
 __device__ __forceinline__ float reg_share(const ColArgs& A, int64_t j)
@@ -113,7 +89,7 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
     }
 }
 
-// All columns; those longer than FM_SEG entries are left to the two kernels below.
+// All columns; those longer than `seg` entries are left to the kernels below.
 template <int VEC, int L, bool UPDATE>
 __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
 {
@@ -129,7 +105,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
         beg = A.ptr[j];
         end = A.ptr[j + 1];
     }
-    const bool is_long = (end - beg) > FM_SEG;
+    const bool is_long = (end - beg) > A.seg;
     if (is_long) end = beg;
     const int kbase = sub * VEC;
     const bool kact = kbase < A.K;
@@ -179,7 +155,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
     }
 }
 
-// One group per segment of a long column: partial sums only.
+// One group per item of a long column: partial sums only.  With an order array,
+// workgroup b takes its items from list b % FM_XCDS (the XCD it runs on).
 template <int VEC, int L>
 __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
 {
@@ -188,8 +165,17 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
     const int wave = threadIdx.x / FM_WAVE;
     const int sub = lane & (L - 1);
     const int grp = lane / L;
-    const int64_t it = A.item_base + (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
-    const bool valid = it < A.item_base + A.nitems;
+    const int slot_in_block = wave * R + grp;
+    int64_t it = -1;
+    if (A.order != nullptr) {
+        const int x = blockIdx.x % FM_XCDS;
+        const int64_t pos = A.list_off[x] + (int64_t)(blockIdx.x / FM_XCDS) * (FM_WAVES * R) + slot_in_block;
+        if (pos < A.list_off[x + 1]) it = A.order[pos];
+    } else {
+        const int64_t pos = (int64_t)blockIdx.x * (FM_WAVES * R) + slot_in_block;
+        if (pos < A.nitems) it = A.item_base + pos;
+    }
+    const bool valid = it >= 0;
     int64_t beg = 0, end = 0;
     if (valid) {
         beg = A.item_beg[it];
@@ -210,24 +196,12 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
     }
 }
 
-// One workgroup per long column: group g adds items g, g+NG, g+2NG, ... in fp64,
-// the NG group totals are then added in ascending g by group 0, which finishes the column.
-template <int VEC, int L, bool UPDATE>
-__global__ __launch_bounds__(FM_BLOCK) void k_cols_finish(const ColArgs A)
+// Sum of the partials first, first+step, ... < last of one column, in fp64.
+template <int VEC>
+__device__ __forceinline__ void add_partials(const ColArgs& A, int64_t first, int64_t last, int64_t step, int kbase,
+                                             bool kact, double (&acc)[VEC], double& gw, double& s2)
 {
-    constexpr int NG = FM_BLOCK / L;  // groups per workgroup
-    const int sub = threadIdx.x & (L - 1);
-    const int grp = threadIdx.x / L;
-    const int64_t lc = A.long_base + blockIdx.x;
-    const int64_t j = A.long_col[lc];
-    const int64_t first = A.long_first[lc], last = A.long_first[lc + 1];
-    const int kbase = sub * VEC;
-    const bool kact = kbase < A.K;
-    double acc[VEC];
-#pragma unroll
-    for (int z = 0; z < VEC; ++z) acc[z] = 0.0;
-    double gw = 0.0, s2 = 0.0;
-    for (int64_t it = first + grp; it < last; it += NG) {
+    for (int64_t it = first; it < last; it += step) {
         if (kact) {
             float p[VEC];
             fm_load_vec<VEC>(A.part_acc + it * A.K + kbase, p);
@@ -238,6 +212,67 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_finish(const ColArgs A)
         gw += (double)gs.x;
         s2 += (double)gs.y;
     }
+}
+
+// One wavefront per long column: group g adds items g, g+R, g+2R, ...; the R group
+// totals are then combined by a fixed butterfly and group 0 finishes the column.
+// Columns with more than vlong_items items are left to k_cols_finish_block (if a list
+// of them was given).
+template <int VEC, int L, bool UPDATE>
+__global__ __launch_bounds__(FM_BLOCK) void k_cols_finish_wave(const ColArgs A)
+{
+    constexpr int R = FM_WAVE / L;
+    const int lane = threadIdx.x & (FM_WAVE - 1);
+    const int wave = threadIdx.x / FM_WAVE;
+    const int sub = lane & (L - 1);
+    const int grp = lane / L;
+    const int64_t rel = (int64_t)blockIdx.x * FM_WAVES + wave;
+    if (rel >= A.nlong) return;  // whole wavefront leaves together
+    const int64_t lc = A.long_base + rel;
+    const int64_t first = A.long_first[lc], last = A.long_first[lc + 1];
+    if (A.vlong != nullptr && last - first > A.vlong_items) return;
+    const int64_t j = A.long_col[lc];
+    const int kbase = sub * VEC;
+    const bool kact = kbase < A.K;
+    double acc[VEC];
+#pragma unroll
+    for (int z = 0; z < VEC; ++z) acc[z] = 0.0;
+    double gw = 0.0, s2 = 0.0;
+    add_partials<VEC>(A, first + grp, last, R, kbase, kact, acc, gw, s2);
+    // combine the R groups: lanes with equal `sub` hold the same latent slice
+#pragma unroll
+    for (int o = L; o < FM_WAVE; o <<= 1) {
+#pragma unroll
+        for (int z = 0; z < VEC; ++z) acc[z] += __shfl_xor(acc[z], o, FM_WAVE);
+        gw += __shfl_xor(gw, o, FM_WAVE);
+        s2 += __shfl_xor(s2, o, FM_WAVE);
+    }
+    if (grp == 0) {
+        float accf[VEC];
+#pragma unroll
+        for (int z = 0; z < VEC; ++z) accf[z] = (float)acc[z];
+        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)gw, (float)s2);
+    }
+}
+
+// One workgroup per very long column: group g adds items g, g+NG, g+2NG, ... in fp64,
+// the NG group totals are then added in ascending g by group 0, which finishes the column.
+template <int VEC, int L, bool UPDATE>
+__global__ __launch_bounds__(FM_BLOCK) void k_cols_finish_block(const ColArgs A)
+{
+    constexpr int NG = FM_BLOCK / L;  // groups per workgroup
+    const int sub = threadIdx.x & (L - 1);
+    const int grp = threadIdx.x / L;
+    const int64_t lc = A.vlong[blockIdx.x];
+    const int64_t j = A.long_col[lc];
+    const int64_t first = A.long_first[lc], last = A.long_first[lc + 1];
+    const int kbase = sub * VEC;
+    const bool kact = kbase < A.K;
+    double acc[VEC];
+#pragma unroll
+    for (int z = 0; z < VEC; ++z) acc[z] = 0.0;
+    double gw = 0.0, s2 = 0.0;
+    add_partials<VEC>(A, first + grp, last, NG, kbase, kact, acc, gw, s2);
     __shared__ double sh[FM_BLOCK * VEC + 2 * NG];
     double* sh_gs = sh + FM_BLOCK * VEC;
 #pragma unroll
@@ -281,7 +316,15 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
         FM_HIP(m, hipGetLastError());
     }
     if (A.nitems > 0) {
-        const int64_t g2 = (A.nitems + per - 1) / per;
+        int64_t g2;
+        if (A.order != nullptr) {
+            int64_t longest = 0;
+            for (int x = 0; x < FM_XCDS; ++x)
+                longest = std::max<int64_t>(longest, A.list_off[x + 1] - A.list_off[x]);
+            g2 = FM_XCDS * ((longest + per - 1) / per);
+        } else {
+            g2 = (A.nitems + per - 1) / per;
+        }
         if (g2 > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "item grid too large");
         {
             ProfScope ps(m, st, FMK_COLS_LONG);
@@ -290,11 +333,21 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
         }
         {
             ProfScope ps(m, st, FMK_COLS_FINISH);
+            const int64_t g3 = (A.nlong + FM_WAVES - 1) / FM_WAVES;
             if (update)
-                hipLaunchKernelGGL((k_cols_finish<VEC, L, true>), dim3((unsigned)A.nlong), dim3(FM_BLOCK), 0, st, A);
+                hipLaunchKernelGGL((k_cols_finish_wave<VEC, L, true>), dim3((unsigned)g3), dim3(FM_BLOCK), 0, st, A);
             else
-                hipLaunchKernelGGL((k_cols_finish<VEC, L, false>), dim3((unsigned)A.nlong), dim3(FM_BLOCK), 0, st, A);
+                hipLaunchKernelGGL((k_cols_finish_wave<VEC, L, false>), dim3((unsigned)g3), dim3(FM_BLOCK), 0, st, A);
             FM_HIP(m, hipGetLastError());
+            if (A.vlong != nullptr && A.nvlong > 0) {
+                if (update)
+                    hipLaunchKernelGGL((k_cols_finish_block<VEC, L, true>), dim3((unsigned)A.nvlong), dim3(FM_BLOCK),
+                                       0, st, A);
+                else
+                    hipLaunchKernelGGL((k_cols_finish_block<VEC, L, false>), dim3((unsigned)A.nvlong), dim3(FM_BLOCK),
+                                       0, st, A);
+                FM_HIP(m, hipGetLastError());
+            }
         }
     }
     return FM_OK;

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 template <int VEC>
 __device__ __forceinline__ void fm_load_vec(const float* __restrict__ p, float (&v)[VEC])
 {
@@ -49,20 +51,121 @@ __device__ __forceinline__ T fm_wave_sum(T v)
     return v;
 }
 
-// Value of `v` held by lane `t` of the caller's L-lane group.
-template <int L, typename T>
-__device__ __forceinline__ T fm_group_bcast(T v, int t)
-{
-    if constexpr (L == 1) {
-        return v;
-    } else {
-        return __shfl(v, t, L);
-    }
-}
-
 // Block b of the floor split of n items into P blocks that holds index i:
 // b = floor(((i+1) P - 1) / n)   (inverse of the bound floor(b n / P)).
 __device__ __forceinline__ int32_t fm_block_of(int64_t i, int64_t n, int32_t P)
 {
     return (int32_t)(((i + 1) * (int64_t)P - 1) / n);
+}
+
+// Compile-time loop: f(std::integral_constant<int, I>) for I = 0..N-1.
+template <int I, int N, class F>
+__device__ __forceinline__ void fm_static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        fm_static_for<I + 1, N>(f);
+    }
+}
+
+// Value of `v` held by lane T of the caller's L-lane group, T known at compile time:
+// a DPP quad permute for groups of up to four lanes (no LDS traffic), the LDS crossbar
+// (ds_bpermute) for wider groups.
+template <int L, int T>
+__device__ __forceinline__ int fm_bcast_i(int v)
+{
+    if constexpr (L == 1) {
+        return v;
+    } else if constexpr (L == 2) {
+        return __builtin_amdgcn_mov_dpp(v, T == 0 ? 0xA0 : 0xF5, 0xf, 0xf, true);
+    } else if constexpr (L == 4) {
+        return __builtin_amdgcn_mov_dpp(v, T * 0x55, 0xf, 0xf, true);
+    } else {
+        return __shfl(v, T, L);
+    }
+}
+template <int L, int T>
+__device__ __forceinline__ float fm_bcast_f(float v)
+{
+    return __int_as_float(fm_bcast_i<L, T>(__float_as_int(v)));
+}
+
+// Entry slots per lane and iteration so that a group keeps 16 row gathers in flight.
+template <int L>
+struct FmChunk {
+    static constexpr int CH = (16 / L) > 0 ? (16 / L) : 1;
+};
+
+// S entry slots (slot s = entry s%L of lane-slot s/L): broadcast each entry's index and
+// multiplier inside the group, gather the rows with at most 16 loads in flight, then
+// accumulate.
+template <int VEC, int L, bool SQ, int S, class IX, class MU>
+__device__ __forceinline__ void fm_gather_slots(const IX& ix, const MU& mu, const float* __restrict__ src,
+                                                int64_t stride, int kb, float (&acc)[VEC], float& sq)
+{
+    constexpr int B = S < 16 ? S : 16;
+    fm_static_for<0, S / B>([&](auto bc) {
+        constexpr int B0 = decltype(bc)::value * B;
+        float g[B][VEC];
+        float mt[B];
+        fm_static_for<0, B>([&](auto sc) {
+            constexpr int s = B0 + decltype(sc)::value;
+            constexpr int u = s / L, T = s % L;
+            const int it = fm_bcast_i<L, T>(ix[u]);
+            mt[s - B0] = fm_bcast_f<L, T>(mu[u]);
+            fm_load_vec<VEC>(src + (int64_t)it * stride + kb, g[s - B0]);
+        });
+#pragma unroll
+        for (int s = 0; s < B; ++s) {
+#pragma unroll
+            for (int z = 0; z < VEC; ++z) {
+                acc[z] += mt[s] * g[s][z];
+                if constexpr (SQ) sq += (mt[s] * mt[s]) * (g[s][z] * g[s][z]);
+            }
+        }
+    });
+}
+
+// The common inner loop of the row and the column kernels.  A group of L lanes walks
+// the entries [beg,end) of one sparse row (or column): idx[e] names a row of `src`
+// (`stride` floats apart) and val[e] its coefficient.  Lane `sub` of the group
+//   * loads entry e+sub of every L-entry slot (coalesced) and calls
+//       m = own(index, value)      -- per-entry work of that lane, linear in the value;
+//                                     returns the multiplier of the gathered row
+//   * receives every entry's (index, m) by broadcast and accumulates
+//       acc[z] += m * src[index*stride + kb + z]     (and, if SQ, sq += m^2 * src[..]^2).
+// Full chunks of L*CH entries run without masking; the tail runs in L-entry slots whose
+// missing entries repeat the last entry with value 0.  `kb` must be a valid offset for
+// every lane (idle lanes pass 0 and discard acc).
+template <int VEC, int L, bool SQ, class Own>
+__device__ __forceinline__ void fm_gather_accumulate(const int32_t* __restrict__ idx, const float* __restrict__ val,
+                                                     int64_t beg, int64_t end, const float* __restrict__ src,
+                                                     int64_t stride, int sub, int kb, float (&acc)[VEC], float& sq,
+                                                     Own&& own)
+{
+    constexpr int CH = FmChunk<L>::CH;
+    int64_t e = beg;
+    for (; e + L * CH <= end; e += L * CH) {
+        int ix[CH];
+        float mu[CH];
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int64_t my = e + u * L + sub;
+            ix[u] = idx[my];
+            mu[u] = val[my];
+        }
+#pragma unroll
+        for (int u = 0; u < CH; ++u) mu[u] = own(ix[u], mu[u]);
+        fm_gather_slots<VEC, L, SQ, CH * L>(ix, mu, src, stride, kb, acc, sq);
+    }
+    for (; e < end; e += L) {
+        const int64_t want = e + sub;
+        const bool has = want < end;
+        const int64_t my = has ? want : end - 1;
+        int ix[1];
+        float mu[1];
+        ix[0] = idx[my];
+        mu[0] = own(ix[0], has ? val[my] : 0.f);
+        fm_gather_slots<VEC, L, SQ, L>(ix, mu, src, stride, kb, acc, sq);
+    }
 }

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -13,8 +14,21 @@
 constexpr int FM_WAVE = 64;
 constexpr int FM_BLOCK = 256;             // threads per workgroup of the pass kernels
 constexpr int FM_WAVES = FM_BLOCK / FM_WAVE;
-constexpr int FM_SEG = 512;               // entries per work item of a long column
 constexpr int FM_MAXP = 4096;
+constexpr int FM_XCDS = 8;                // L2 domains; workgroup b runs on XCD b % 8
+
+// Tunables of the column-side work decomposition (read once from the environment:
+// FM_SEG, FM_PANEL, FM_HEAVY_PER_PANEL, FM_VLONG).
+struct FmTune {
+    int seg;              // entries per work item of a long column
+    int panel;            // rows per panel of the L2-blocked traversal of heavy columns
+    int heavy_per_panel;  // a column is heavy if it averages at least this many entries per panel
+    int vlong;            // columns with more items than this are finished by a whole workgroup
+};
+const FmTune& fm_tune();
+
+// internal aggregate row: [G_0..G_{K-1}, r, a, q, pad] with a stride that is a multiple of 16 floats
+inline int64_t fm_aux_stride(int32_t K) { return ((int64_t)K + 3 + 15) / 16 * 16; }
 
 enum fm_kernel_id {
     FMK_ROWS_FORWARD = 0,
@@ -27,8 +41,9 @@ enum fm_kernel_id {
     FMK_COUNT
 };
 
-// Work items for columns longer than FM_SEG entries (of one matrix, or of all strata
-// concatenated).  Offsets in item_beg are global offsets into the entry arrays.
+// Work items for columns longer than `seg` entries (of one matrix, or of all strata
+// concatenated).  Offsets in item_beg are global offsets into the entry arrays.  Items of
+// a column are numbered consecutively (long_first); partial sums live at the item id.
 struct LongIndex {
     int64_t nlong = 0, nitems = 0;
     int32_t* long_col = nullptr;    // [nlong] column id
@@ -37,6 +52,12 @@ struct LongIndex {
     int64_t* item_beg = nullptr;    // [nitems]
     int32_t* item_len = nullptr;    // [nitems]
     std::vector<int64_t> h_long_off, h_item_off;  // per-stratum ranges (size P+1), or {0,nlong}
+    // processing order of the full matrix: FM_XCDS lists of item ids, list x walked by the
+    // workgroups that run on XCD x, heavy columns panel by panel (order == nullptr: id order)
+    uint32_t* order = nullptr;      // [nitems]
+    int64_t list_off[FM_XCDS + 1] = {0};
+    int32_t* vlong = nullptr;       // [nvlong] indices into long_col of columns with > vlong items
+    int64_t nvlong = 0;
 };
 
 struct ProfRec {
@@ -69,7 +90,7 @@ struct fm_matrix {
     LongIndex lstrat;
     // workspace, sized for wsK
     int32_t wsK = 0;
-    float *G = nullptr, *a = nullptr, *q = nullptr, *r = nullptr;
+    float* aux = nullptr;   // [N * fm_aux_stride(K)] rows [G | r | a | q | pad]
     float* dV = nullptr;    // [D*K] last step's change of V
     float2* dwn = nullptr;  // [D] (change of w_j, change of |v_j|^2)
     float* part_acc = nullptr;  // [max items * K]
@@ -124,6 +145,7 @@ int fm_sort_by_key_u32(fm_matrix* m, uint32_t* keys, uint32_t* idx, uint32_t* ke
                        int64_t n, int bits, hipStream_t st, bool* result_in_alt);
 int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
                         LongIndex* out, hipStream_t st);
+int fm_build_full_index(fm_matrix* m, hipStream_t st);  // lfull, with the panel order of heavy columns
 
 // ---- pass kernels (fm_rows.hip / fm_cols.hip / fm_reduce.hip) ----
 struct RowArgs {
@@ -138,12 +160,15 @@ struct RowArgs {
     const float2* dwn;  // refresh: (dw_j, dn_j)
     const float* y;     // nullable
     float *yhat, *a, *G, *q, *r;  // forward: nullable outputs ; refresh: in/out aggregates
+    int64_t gs;         // floats between consecutive rows of G
+    int64_t ss;         // floats between consecutive rows of r, a, q (1, or the aggregate row stride)
     float* row_part;    // nullable: [2*gridDim] loss and sum r per block
     int32_t loss;
     float s;
 };
 int fm_launch_rows(fm_matrix* m, const RowArgs& A, bool refresh, hipStream_t st);
 int64_t fm_rows_grid(int64_t N, int32_t K);
+int fm_unpack_aux(fm_matrix* m, float* a, float* G, float* q, float* r, hipStream_t st);
 
 struct ColArgs {
     int64_t D;
@@ -153,6 +178,8 @@ struct ColArgs {
     const float* val;
     const float* r;
     const float* G;
+    int64_t gs, rs;  // row strides of G and r in floats
+    int32_t seg;     // columns longer than this are split into items
     float* w;        // updated in place when update
     float* V;
     float* grad_w;   // !update: outputs (nullable)
@@ -173,6 +200,11 @@ struct ColArgs {
     const int32_t* item_len;
     int64_t nlong, nitems;        // counts of this launch
     int64_t long_base, item_base;  // first long column / first item of this launch (absolute ids)
+    const uint32_t* order;         // nullable: item ids in processing order, FM_XCDS lists
+    int64_t list_off[FM_XCDS + 1];
+    const int32_t* vlong;          // nullable: long columns finished by a whole workgroup
+    int64_t nvlong;
+    int32_t vlong_items;           // threshold that defines vlong
     float* part_acc;                // indexed by absolute item id
     float2* part_gs;
 };
@@ -180,7 +212,7 @@ int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st);
 int64_t fm_cols_grid(int64_t D, int32_t K);
 
 int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st);
-int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, bool square, double* out1, hipStream_t st);
+int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, int64_t stride, bool square, double* out1, hipStream_t st);
 int fm_bias_step(fm_matrix* m, float* w0, const double* rsum, float eta, float* grad_w0_out, hipStream_t st);
 
 // lanes per row/column group and floats per lane for a given K; false if K unsupported

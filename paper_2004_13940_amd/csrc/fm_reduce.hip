@@ -40,8 +40,8 @@ __global__ __launch_bounds__(RED_THREADS) void k_reduce_pairs(const float* __res
     }
 }
 
-__global__ __launch_bounds__(RED_THREADS) void k_reduce_stage1(const float* __restrict__ x, int64_t n, int square,
-                                                               double* __restrict__ tmp)
+__global__ __launch_bounds__(RED_THREADS) void k_reduce_stage1(const float* __restrict__ x, int64_t n, int64_t stride,
+                                                               int square, double* __restrict__ tmp)
 {
     __shared__ double sh[RED_THREADS / 64];
     const int64_t chunk = (n + gridDim.x - 1) / gridDim.x;
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(RED_THREADS) void k_reduce_stage1(const float* __re
     const int64_t hi = lo + chunk < n ? lo + chunk : n;
     double s = 0.0;
     for (int64_t i = lo + threadIdx.x; i < hi; i += RED_THREADS) {
-        const double v = (double)x[i];
+        const double v = (double)x[i * stride];
         s += square ? v * v : v;
     }
     const double t = block_sum_1024(s, sh);
@@ -85,7 +85,7 @@ int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* ou
     return FM_OK;
 }
 
-int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, bool square, double* out1, hipStream_t st)
+int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, int64_t stride, bool square, double* out1, hipStream_t st)
 {
     // scal[8..8+RED_BLOCKS) is the stage-1 scratch
     double* tmp = m->scal + 8;
@@ -93,7 +93,7 @@ int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, bool square, double* 
     if (nb < 1) nb = 1;
     if (nb > RED_BLOCKS) nb = RED_BLOCKS;
     ProfScope ps(m, st, FMK_REDUCE);
-    hipLaunchKernelGGL(k_reduce_stage1, dim3(nb), dim3(RED_THREADS), 0, st, x, n, square ? 1 : 0, tmp);
+    hipLaunchKernelGGL(k_reduce_stage1, dim3(nb), dim3(RED_THREADS), 0, st, x, n, stride, square ? 1 : 0, tmp);
     FM_HIP(m, hipGetLastError());
     hipLaunchKernelGGL(k_reduce_stage2, dim3(1), dim3(RED_THREADS), 0, st, (const double*)tmp, nb, out1);
     FM_HIP(m, hipGetLastError());

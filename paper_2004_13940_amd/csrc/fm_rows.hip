@@ -13,11 +13,6 @@ namespace {
 
 enum { MODE_FORWARD = 0, MODE_REFRESH = 1 };
 
-template <int L>
-struct Chunk {
-    static constexpr int CH = (16 / L) > 0 ? (16 / L) : 1;  // entry slots per lane and iteration
-};
-
 // Loss value and multiplier for one example (cases after eq. updates_v; the loss
 // constants make the printed multiplier the exact derivative).  expf only ever sees
 // a non-positive argument.
@@ -45,7 +40,6 @@ template <int VEC, int L, int MODE>
 __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
 {
     constexpr int R = FM_WAVE / L;  // rows per wavefront
-    constexpr int CH = Chunk<L>::CH;
     const int lane = threadIdx.x & (FM_WAVE - 1);
     const int wave = threadIdx.x / FM_WAVE;
     const int sub = lane & (L - 1);
@@ -65,46 +59,29 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
 #pragma unroll
     for (int u = 0; u < VEC; ++u) acc[u] = 0.f;
     float a_acc = 0.f, q_acc = 0.f;
-
-    for (int64_t e = beg; e < end; e += L * CH) {
-        int c[CH];
-        float x[CH];
+    const int kb = kact ? kbase : 0;
+    if constexpr (MODE == MODE_FORWARD) {
+        const float* __restrict__ w = A.w;
+        fm_gather_accumulate<VEC, L, true>(A.col, A.val, beg, end, A.V, K, sub, kb, acc, q_acc,
+                                           [&](int c, float x) {
+                                               a_acc += w[c] * x;
+                                               return x;
+                                           });
+    } else {
+        const float2* __restrict__ dwn = A.dwn;
+        float unused = 0.f;
+        fm_gather_accumulate<VEC, L, false>(A.col, A.val, beg, end, A.V, K, sub, kb, acc, unused,
+                                            [&](int c, float x) {
+                                                const float2 d = dwn[c];
+                                                a_acc += d.x * x;
+                                                q_acc += d.y * (x * x);
+                                                return x;
+                                            });
+    }
+    if (!kact) {  // idle lanes of a group wider than K/VEC worked on a valid but foreign slice
 #pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const int64_t my = e + u * L + sub;
-            const bool has = my < end;
-            c[u] = has ? A.col[my] : 0;
-            x[u] = has ? A.val[my] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            if (e + u * L + sub < end) {
-                if constexpr (MODE == MODE_FORWARD) {
-                    a_acc += A.w[c[u]] * x[u];
-                } else {
-                    const float2 d = A.dwn[c[u]];
-                    a_acc += d.x * x[u];
-                    q_acc += d.y * x[u] * x[u];
-                }
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < CH; ++u) {
-#pragma unroll
-            for (int t = 0; t < L; ++t) {
-                const int ct = fm_group_bcast<L>(c[u], t);
-                const float xt = fm_group_bcast<L>(x[u], t);
-                if (e + u * L + t < end && kact) {
-                    float v[VEC];
-                    fm_load_vec<VEC>(A.V + (int64_t)ct * K + kbase, v);
-#pragma unroll
-                    for (int z = 0; z < VEC; ++z) {
-                        acc[z] += v[z] * xt;
-                        if constexpr (MODE == MODE_FORWARD) q_acc += v[z] * v[z] * (xt * xt);
-                    }
-                }
-            }
-        }
+        for (int u = 0; u < VEC; ++u) acc[u] = 0.f;
+        if constexpr (MODE == MODE_FORWARD) q_acc = 0.f;
     }
 
     float l_i = 0.f, r_i = 0.f;
@@ -117,14 +94,14 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
         pair = fm_group_sum<L>(pair);
         const float yh = A.w0[0] + a_i + 0.5f * (pair - q_i);
         if (valid) {
-            if (A.G != nullptr && kact) fm_store_vec<VEC>(A.G + row * K + kbase, acc);
+            if (A.G != nullptr && kact) fm_store_vec<VEC>(A.G + row * A.gs + kbase, acc);
             if (sub == 0) {
-                if (A.a != nullptr) A.a[row] = a_i;
-                if (A.q != nullptr) A.q[row] = q_i;
+                if (A.a != nullptr) A.a[row * A.ss] = a_i;
+                if (A.q != nullptr) A.q[row * A.ss] = q_i;
                 if (A.yhat != nullptr) A.yhat[row] = yh;
                 if (A.y != nullptr) {
                     loss_and_multiplier(A.loss, A.s, yh, A.y[row], l_i, r_i);
-                    if (A.r != nullptr) A.r[row] = r_i;
+                    if (A.r != nullptr) A.r[row * A.ss] = r_i;
                 }
             }
         }
@@ -136,24 +113,24 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
         float pair = 0.f;
         if (touched && kact) {
             float g[VEC];
-            fm_load_vec<VEC>(A.G + row * K + kbase, g);
+            fm_load_vec<VEC>(A.G + row * A.gs + kbase, g);
 #pragma unroll
             for (int z = 0; z < VEC; ++z) {
                 g[z] += acc[z];
                 pair += g[z] * g[z];
             }
-            fm_store_vec<VEC>(A.G + row * K + kbase, g);
+            fm_store_vec<VEC>(A.G + row * A.gs + kbase, g);
         }
         pair = fm_group_sum<L>(pair);
         if (touched && sub == 0) {
-            const float a_i = A.a[row] + da;
-            const float q_i = A.q[row] + dq;
-            A.a[row] = a_i;
-            A.q[row] = q_i;
+            const float a_i = A.a[row * A.ss] + da;
+            const float q_i = A.q[row * A.ss] + dq;
+            A.a[row * A.ss] = a_i;
+            A.q[row * A.ss] = q_i;
             const float yh = A.w0[0] + a_i + 0.5f * (pair - q_i);
             if (A.yhat != nullptr) A.yhat[row] = yh;
             loss_and_multiplier(A.loss, A.s, yh, A.y[row], l_i, r_i);
-            A.r[row] = r_i;
+            A.r[row * A.ss] = r_i;
         }
     }
 
@@ -212,6 +189,40 @@ int launch_rows_v(fm_matrix* m, int lanes, const RowArgs& A, bool refresh, hipSt
 }
 
 }  // namespace
+
+namespace {
+__global__ void k_unpack_aux(const float* __restrict__ aux, int64_t N, int32_t K, int64_t gs, float* a, float* G,
+                             float* q, float* r)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t per = K + 3;
+    if (t >= N * per) return;
+    const int64_t i = t / per;
+    const int c = (int)(t % per);
+    const float v = aux[i * gs + c];
+    if (c < K) {
+        if (G != nullptr) G[i * K + c] = v;
+    } else if (c == K) {
+        if (r != nullptr) r[i] = v;
+    } else if (c == K + 1) {
+        if (a != nullptr) a[i] = v;
+    } else {
+        if (q != nullptr) q[i] = v;
+    }
+}
+}  // namespace
+
+int fm_unpack_aux(fm_matrix* m, float* a, float* G, float* q, float* r, hipStream_t st)
+{
+    const int64_t total = m->N * (int64_t)(m->wsK + 3);
+    if (total <= 0) return FM_OK;
+    const int64_t grid = (total + 255) / 256;
+    if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "aggregate copy too large");
+    hipLaunchKernelGGL(k_unpack_aux, dim3((unsigned)grid), dim3(256), 0, st, (const float*)m->aux, m->N, m->wsK,
+                       fm_aux_stride(m->wsK), a, G, q, r);
+    FM_HIP(m, hipGetLastError());
+    return FM_OK;
+}
 
 bool fm_shape_for_K(int32_t K, int* vec, int* lanes)
 {
