@@ -102,7 +102,7 @@ def main():
     prof = m.fm_profile_read()
     m.fm_profile_enable(False)
     counts = np.bincount(wl.col, minlength=wl.D)
-    seg = int(os.environ.get("FM_SEG", "128"))  # the library's default item length
+    seg = int(os.environ.get("FM_SEG", "256"))  # the library's default item length
     long_mask = counts > seg
     nnz_long = int(counts[long_mask].sum())
     nlong = int(long_mask.sum())

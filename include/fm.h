@@ -161,6 +161,16 @@ int fm_profile_kernels(void);
 const char* fm_profile_kernel_name(int32_t k);
 int fm_profile_read(fm_matrix* m, int64_t* launches /*HOST nk*/, double* total_ms /*HOST nk*/);
 
+/* Work-decomposition knobs of the column side, for callers that tune or test them; they
+ * apply to matrices whose CSC is built afterwards.  A value <= 0 keeps the current one.
+ *   seg              entries per work item of a long column                      (default 256)
+ *   panel            rows per panel of the L2-blocked traversal of heavy columns (default 16384)
+ *   heavy_per_panel  a column is heavy if it averages this many entries per panel (default 8)
+ *   vlong            columns with more items are summed by a whole workgroup      (default 512)
+ *   min_panels       matrices with fewer panels use plain segments only           (default 64)
+ * Results do not depend on these values beyond fp32 rounding. */
+int fm_set_tuning(int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t vlong, int32_t min_panels);
+
 int fm_destroy(fm_matrix* m);
 const char* fm_last_error(const fm_matrix* m); /* m may be NULL: last build error of this thread */
 

@@ -1,6 +1,7 @@
 // C-ABI entry points and the epoch drivers.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -241,6 +242,41 @@ static int check_params(fm_matrix* m, const fm_params* p)
     return FM_OK;
 }
 
+// Packed rows are the default whenever a row is a whole number of float4 (K % 4 == 0) and
+// a column group of 64 lanes can cover it; FM_AUX_PACKED=0 selects the planar layout.
+bool fm_aux_packed(int32_t K)
+{
+    static const bool allow = [] {
+        const char* e = getenv("FM_AUX_PACKED");
+        return !(e != nullptr && *e == '0');
+    }();
+    return allow && K % 4 == 0 && K <= 252;
+}
+
+static int64_t packed_stride(int32_t K) { return ((int64_t)K + 3 + 15) / 16 * 16; }
+
+int64_t fm_aux_floats(int64_t N, int32_t K) { return fm_aux_packed(K) ? N * packed_stride(K) : N * ((int64_t)K + 3); }
+
+FmAux fm_aux_layout(const fm_matrix* m, int32_t K)
+{
+    FmAux x;
+    if (fm_aux_packed(K)) {
+        x.gs = x.ss = packed_stride(K);
+        x.G = m->aux;
+        x.r = m->aux + K;
+        x.a = m->aux + K + 1;
+        x.q = m->aux + K + 2;
+    } else {
+        x.gs = K;
+        x.ss = 1;
+        x.G = m->aux;
+        x.r = m->aux + m->N * (int64_t)K;
+        x.a = x.r + m->N;
+        x.q = x.a + m->N;
+    }
+    return x;
+}
+
 void fm_drop_workspace(fm_matrix* m)
 {
     for (void* p : {(void*)m->aux, (void*)m->dV, (void*)m->dwn, (void*)m->part_acc, (void*)m->part_gs,
@@ -258,8 +294,8 @@ static int ensure_ws(fm_matrix* m, int32_t K)
 {
     if (m->wsK == K) return FM_OK;
     fm_drop_workspace(m);
-    const size_t N = (size_t)m->N, D = (size_t)m->D;
-    FM_TRY(fm_dev_alloc(m, (void**)&m->aux, N * (size_t)fm_aux_stride(K) * sizeof(float)));
+    const size_t D = (size_t)m->D;
+    FM_TRY(fm_dev_alloc(m, (void**)&m->aux, (size_t)std::max<int64_t>(fm_aux_floats(m->N, K), 1) * sizeof(float)));
     const int64_t items = std::max<int64_t>(m->lfull.nitems, m->lstrat.nitems);
     FM_TRY(fm_dev_alloc(m, (void**)&m->part_acc, (size_t)std::max<int64_t>(items, 1) * K * sizeof(float)));
     FM_TRY(fm_dev_alloc(m, (void**)&m->part_gs, (size_t)std::max<int64_t>(items, 1) * sizeof(float2)));
@@ -302,13 +338,13 @@ static void fill_long(ColArgs& A, const LongIndex& li, int32_t s, bool strat)
 // RowArgs outputs pointing into the handle's aggregate rows [G | r | a | q | pad]
 static void aux_outputs(fm_matrix* m, int32_t K, RowArgs& A, bool with_aq)
 {
-    const int64_t gs = fm_aux_stride(K);
-    A.G = m->aux;
-    A.gs = gs;
-    A.ss = gs;
-    A.r = m->aux + K;
-    A.a = with_aq ? m->aux + K + 1 : nullptr;
-    A.q = with_aq ? m->aux + K + 2 : nullptr;
+    const FmAux x = fm_aux_layout(m, K);
+    A.G = x.G;
+    A.gs = x.gs;
+    A.ss = x.ss;
+    A.r = x.r;
+    A.a = with_aq ? x.a : nullptr;
+    A.q = with_aq ? x.q : nullptr;
 }
 
 // ---------------------------------------------------------------- forward ----
@@ -443,9 +479,12 @@ extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, fl
     A.ptr = m->colptr;
     A.row = m->crow;
     A.val = m->cval;
-    A.r = m->aux + p->K;
-    A.G = m->aux;
-    A.gs = A.rs = fm_aux_stride(p->K);
+    const FmAux x = fm_aux_layout(m, p->K);
+    A.r = x.r;
+    A.G = x.G;
+    A.gs = x.gs;
+    A.rs = x.ss;
+    A.packed = fm_aux_packed(p->K) ? 1 : 0;
     A.w = w;
     A.V = V;
     A.col_part = objective != nullptr ? m->col_part : nullptr;
@@ -496,9 +535,12 @@ extern "C" int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, c
     A.ptr = m->s_colptr + (int64_t)s * m->D;
     A.row = m->s_row;
     A.val = m->s_cval;
-    A.r = m->aux + p->K;
-    A.G = m->aux;
-    A.gs = A.rs = fm_aux_stride(p->K);
+    const FmAux x = fm_aux_layout(m, p->K);
+    A.r = x.r;
+    A.G = x.G;
+    A.gs = x.gs;
+    A.rs = x.ss;
+    A.packed = fm_aux_packed(p->K) ? 1 : 0;
     A.w = w;
     A.V = V;
     A.dV = m->dV;
@@ -542,7 +584,8 @@ extern "C" int fm_stratified_end(fm_matrix* m, const fm_params* p, float* w0, vo
     if (w0 == nullptr) return fm_fail(m, FM_EINVAL, "w0 must not be NULL");
     hipStream_t st = (hipStream_t)hip_stream;
     if (p->update_w0) {
-        FM_TRY(fm_reduce_sum(m, m->aux + p->K, m->N, fm_aux_stride(p->K), false, m->scal + 1, st));
+        const FmAux x = fm_aux_layout(m, p->K);
+        FM_TRY(fm_reduce_sum(m, x.r, m->N, x.ss, false, m->scal + 1, st));
         FM_TRY(fm_bias_step(m, w0, m->scal + 1, p->eta, nullptr, st));
     }
     return FM_OK;

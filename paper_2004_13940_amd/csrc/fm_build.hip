@@ -527,11 +527,25 @@ static int env_int(const char* name, int dflt, int lo, int hi)
     return (int)(v < lo ? lo : v > hi ? hi : v);
 }
 
-const FmTune& fm_tune()
+static FmTune& tune_mut()
 {
-    static const FmTune t = {env_int("FM_SEG", 128, 16, 1 << 20), env_int("FM_PANEL", 8192, 64, 1 << 30),
-                             env_int("FM_HEAVY_PER_PANEL", 4, 1, 1 << 20), env_int("FM_VLONG", 512, 1, 1 << 30)};
+    static FmTune t = {env_int("FM_SEG", 256, 16, 1 << 20), env_int("FM_PANEL", 16384, 64, 1 << 30),
+                       env_int("FM_HEAVY_PER_PANEL", 8, 1, 1 << 20), env_int("FM_VLONG", 512, 1, 1 << 30),
+                       env_int("FM_MIN_PANELS", 8 * FM_XCDS, 1, 1 << 30)};
     return t;
+}
+
+const FmTune& fm_tune() { return tune_mut(); }
+
+extern "C" int fm_set_tuning(int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t vlong, int32_t min_panels)
+{
+    FmTune& t = tune_mut();
+    if (seg > 0) t.seg = seg < 16 ? 16 : seg;
+    if (panel > 0) t.panel = panel < 64 ? 64 : panel;
+    if (heavy_per_panel > 0) t.heavy_per_panel = heavy_per_panel;
+    if (vlong > 0) t.vlong = vlong;
+    if (min_panels > 0) t.min_panels = min_panels;
+    return FM_OK;
 }
 
 int fm_build_full_index(fm_matrix* m, hipStream_t st)
@@ -572,7 +586,7 @@ int fm_build_full_index(fm_matrix* m, hipStream_t st)
     // 2. items per long column, then their first ids
     const int64_t npanels = (m->N + T.panel - 1) / T.panel;
     // the panel order pays off only when there are many more panels than XCDs
-    const int64_t heavy_min = npanels >= 8 * FM_XCDS
+    const int64_t heavy_min = npanels >= T.min_panels
                                   ? std::max<int64_t>((int64_t)T.heavy_per_panel * npanels, (int64_t)T.seg + 1)
                                   : INT64_MAX;
     const int64_t maxpos = (npanels + FM_XCDS - 1) / FM_XCDS;

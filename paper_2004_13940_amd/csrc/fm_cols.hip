@@ -20,20 +20,27 @@ namespace {
 
 // Accumulate one run of entries [beg,end) of a column into acc/gw/s2 (per-lane
 // partials for gw, s2; complete sums for acc's latent slice).
-template <int VEC, int L>
+template <int VEC, int L, bool PACKED>
 __device__ __forceinline__ void accumulate_entries(const ColArgs& A, int64_t beg, int64_t end, int sub, int kbase,
                                                    bool kact, float (&acc)[VEC], float& gw, float& s2)
 {
-    const float* __restrict__ r = A.r;
-    const int64_t rs = A.rs;
-    float unused = 0.f;
-    fm_gather_accumulate<VEC, L, false>(A.row, A.val, beg, end, A.G, A.gs, sub, kact ? kbase : 0, acc, unused,
-                                        [&](int i, float x) {
-                                            const float xr = x * r[(int64_t)i * rs];
-                                            gw += xr;
-                                            s2 += x * xr;
-                                            return xr;
-                                        });
+    if constexpr (PACKED) {
+        // every lane reads inside the row: lanes past the scalars re-read its last VEC floats
+        const int last = (int)A.gs - VEC;
+        fm_col_accumulate_packed<VEC, L>(A.row, A.val, beg, end, A.G, A.gs, sub, kbase < last ? kbase : last,
+                                         A.K / VEC, acc, gw, s2);
+    } else {
+        const float* __restrict__ r = A.r;
+        const int64_t rs = A.rs;
+        float unused = 0.f;
+        fm_gather_accumulate<VEC, L, false>(A.row, A.val, beg, end, A.G, A.gs, sub, kact ? kbase : 0, acc, unused,
+                                            [&](int i, float x) {
+                                                const float xr = x * r[(int64_t)i * rs];
+                                                gw += xr;
+                                                s2 += x * xr;
+                                                return xr;
+                                            });
+    }
 }
 
 __device__ __forceinline__ float reg_share(const ColArgs& A, int64_t j)
@@ -90,7 +97,7 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
 }
 
 // All columns; those longer than `seg` entries are left to the kernels below.
-template <int VEC, int L, bool UPDATE>
+template <int VEC, int L, bool UPDATE, bool PACKED>
 __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
 {
     constexpr int R = FM_WAVE / L;
@@ -114,7 +121,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
 #pragma unroll
     for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
     float gw = 0.f, s2 = 0.f;
-    accumulate_entries<VEC, L>(A, beg, end, sub, kbase, kact, acc, gw, s2);
+    accumulate_entries<VEC, L, PACKED>(A, beg, end, sub, kbase, kact, acc, gw, s2);
     gw = fm_group_sum<L>(gw);
     s2 = fm_group_sum<L>(s2);
 
@@ -157,7 +164,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
 
 // One group per item of a long column: partial sums only.  With an order array,
 // workgroup b takes its items from list b % FM_XCDS (the XCD it runs on).
-template <int VEC, int L>
+template <int VEC, int L, bool PACKED>
 __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
 {
     constexpr int R = FM_WAVE / L;
@@ -187,7 +194,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
 #pragma unroll
     for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
     float gw = 0.f, s2 = 0.f;
-    accumulate_entries<VEC, L>(A, beg, end, sub, kbase, kact, acc, gw, s2);
+    accumulate_entries<VEC, L, PACKED>(A, beg, end, sub, kbase, kact, acc, gw, s2);
     gw = fm_group_sum<L>(gw);
     s2 = fm_group_sum<L>(s2);
     if (valid) {
@@ -196,18 +203,37 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
     }
 }
 
-// Sum of the partials first, first+step, ... < last of one column, in fp64.
+// Sum of the partials first, first+step, ... < last of one column, in fp64 and in that
+// order; eight loads are issued before the first add so that the loop is not one memory
+// round trip per item.
 template <int VEC>
 __device__ __forceinline__ void add_partials(const ColArgs& A, int64_t first, int64_t last, int64_t step, int kbase,
                                              bool kact, double (&acc)[VEC], double& gw, double& s2)
 {
-    for (int64_t it = first; it < last; it += step) {
-        if (kact) {
-            float p[VEC];
-            fm_load_vec<VEC>(A.part_acc + it * A.K + kbase, p);
+    constexpr int U = 8;
+    const int kb = kact ? kbase : 0;
+    int64_t it = first;
+    for (; it + (U - 1) * step < last; it += U * step) {
+        float p[U][VEC];
+        float2 gs[U];
 #pragma unroll
-            for (int z = 0; z < VEC; ++z) acc[z] += (double)p[z];
+        for (int u = 0; u < U; ++u) {
+            fm_load_vec<VEC>(A.part_acc + (it + u * step) * A.K + kb, p[u]);
+            gs[u] = A.part_gs[it + u * step];
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int z = 0; z < VEC; ++z) acc[z] += (double)p[u][z];
+            gw += (double)gs[u].x;
+            s2 += (double)gs[u].y;
+        }
+    }
+    for (; it < last; it += step) {
+        float p[VEC];
+        fm_load_vec<VEC>(A.part_acc + it * A.K + kb, p);
+#pragma unroll
+        for (int z = 0; z < VEC; ++z) acc[z] += (double)p[z];
         const float2 gs = A.part_gs[it];
         gw += (double)gs.x;
         s2 += (double)gs.y;
@@ -300,7 +326,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_finish_block(const ColArgs A)
     }
 }
 
-template <int VEC, int L>
+template <int VEC, int L, bool PACKED>
 int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
 {
     constexpr int R = FM_WAVE / L;
@@ -310,9 +336,9 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     if (grid > 0) {
         ProfScope ps(m, st, FMK_COLS);
         if (update)
-            hipLaunchKernelGGL((k_cols<VEC, L, true>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
+            hipLaunchKernelGGL((k_cols<VEC, L, true, PACKED>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
         else
-            hipLaunchKernelGGL((k_cols<VEC, L, false>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
+            hipLaunchKernelGGL((k_cols<VEC, L, false, PACKED>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
         FM_HIP(m, hipGetLastError());
     }
     if (A.nitems > 0) {
@@ -328,7 +354,7 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
         if (g2 > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "item grid too large");
         {
             ProfScope ps(m, st, FMK_COLS_LONG);
-            hipLaunchKernelGGL((k_cols_long<VEC, L>), dim3((unsigned)g2), dim3(FM_BLOCK), 0, st, A);
+            hipLaunchKernelGGL((k_cols_long<VEC, L, PACKED>), dim3((unsigned)g2), dim3(FM_BLOCK), 0, st, A);
             FM_HIP(m, hipGetLastError());
         }
         {
@@ -353,27 +379,39 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     return FM_OK;
 }
 
-template <int VEC>
+template <int VEC, bool PACKED>
 int launch_cols_v(fm_matrix* m, int lanes, const ColArgs& A, bool update, hipStream_t st)
 {
     switch (lanes) {
-        case 1: return launch_cols_t<VEC, 1>(m, A, update, st);
-        case 2: return launch_cols_t<VEC, 2>(m, A, update, st);
-        case 4: return launch_cols_t<VEC, 4>(m, A, update, st);
-        case 8: return launch_cols_t<VEC, 8>(m, A, update, st);
-        case 16: return launch_cols_t<VEC, 16>(m, A, update, st);
-        case 32: return launch_cols_t<VEC, 32>(m, A, update, st);
-        case 64: return launch_cols_t<VEC, 64>(m, A, update, st);
+        case 1: return launch_cols_t<VEC, 1, PACKED>(m, A, update, st);
+        case 2: return launch_cols_t<VEC, 2, PACKED>(m, A, update, st);
+        case 4: return launch_cols_t<VEC, 4, PACKED>(m, A, update, st);
+        case 8: return launch_cols_t<VEC, 8, PACKED>(m, A, update, st);
+        case 16: return launch_cols_t<VEC, 16, PACKED>(m, A, update, st);
+        case 32: return launch_cols_t<VEC, 32, PACKED>(m, A, update, st);
+        case 64: return launch_cols_t<VEC, 64, PACKED>(m, A, update, st);
     }
     return fm_fail(m, FM_EINVAL, "unsupported lane count %d", lanes);
 }
 
 }  // namespace
 
+// lanes per column group: K/VEC latent lanes, plus one lane for the scalars of a packed row
+static bool cols_shape(int32_t K, bool packed, int* vec, int* lanes)
+{
+    if (!fm_shape_for_K(K, vec, lanes)) return false;
+    if (packed) {
+        int need = K / 4 + 1, l = 1;
+        while (l < need) l <<= 1;
+        *lanes = l;
+    }
+    return true;
+}
+
 int64_t fm_cols_grid(int64_t D, int32_t K)
 {
     int vec, lanes;
-    if (!fm_shape_for_K(K, &vec, &lanes)) return 0;
+    if (!cols_shape(K, fm_aux_packed(K), &vec, &lanes)) return 0;
     const int64_t per = (int64_t)FM_WAVES * (FM_WAVE / lanes);
     return (D + per - 1) / per;
 }
@@ -381,10 +419,11 @@ int64_t fm_cols_grid(int64_t D, int32_t K)
 int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
 {
     int vec, lanes;
-    if (!fm_shape_for_K(A.K, &vec, &lanes)) return fm_fail(m, FM_EINVAL, "unsupported K=%d", A.K);
+    if (!cols_shape(A.K, A.packed != 0, &vec, &lanes)) return fm_fail(m, FM_EINVAL, "unsupported K=%d", A.K);
+    if (A.packed) return launch_cols_v<4, true>(m, lanes, A, update, st);
     switch (vec) {
-        case 4: return launch_cols_v<4>(m, lanes, A, update, st);
-        case 2: return launch_cols_v<2>(m, lanes, A, update, st);
-        default: return launch_cols_v<1>(m, lanes, A, update, st);
+        case 4: return launch_cols_v<4, false>(m, lanes, A, update, st);
+        case 2: return launch_cols_v<2, false>(m, lanes, A, update, st);
+        default: return launch_cols_v<1, false>(m, lanes, A, update, st);
     }
 }

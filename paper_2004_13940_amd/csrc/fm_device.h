@@ -169,3 +169,71 @@ __device__ __forceinline__ void fm_gather_accumulate(const int32_t* __restrict__
         fm_gather_slots<VEC, L, SQ, L>(ix, mu, src, stride, kb, acc, sq);
     }
 }
+
+// Column-side variant for packed aggregate rows [G_0..G_{K-1} | r | a | q | pad]: a group of
+// L lanes reads a whole row with one request per 128 bytes; the lane that holds the
+// scalars (lane rl = K/VEC of the group) supplies r to the others.  Per entry (row i, value x):
+//   acc[z] += x r_i G_i[kb+z]     on the latent lanes,
+//   gw += x r_i, s2 += x^2 r_i    on the scalar lane.
+template <int VEC, int L, int S, class IX, class XV>
+__device__ __forceinline__ void fm_gather_slots_packed(const IX& ix, const XV& xv, const float* __restrict__ src,
+                                                       int64_t stride, int kb, int rl, bool scalar_lane,
+                                                       float (&acc)[VEC], float& gw, float& s2)
+{
+    constexpr int B = S < 16 ? S : 16;
+    fm_static_for<0, S / B>([&](auto bc) {
+        constexpr int B0 = decltype(bc)::value * B;
+        float g[B][VEC];
+        float xt[B];
+        fm_static_for<0, B>([&](auto sc) {
+            constexpr int s = B0 + decltype(sc)::value;
+            constexpr int u = s / L, T = s % L;
+            const int it = fm_bcast_i<L, T>(ix[u]);
+            xt[s - B0] = fm_bcast_f<L, T>(xv[u]);
+            fm_load_vec<VEC>(src + (int64_t)it * stride + kb, g[s - B0]);
+        });
+#pragma unroll
+        for (int s = 0; s < B; ++s) {
+            const float r = __shfl(g[s][0], rl, L);
+            const float m = xt[s] * r;
+#pragma unroll
+            for (int z = 0; z < VEC; ++z) acc[z] += m * g[s][z];
+            if (scalar_lane) {
+                gw += m;
+                s2 += xt[s] * m;
+            }
+        }
+    });
+}
+
+template <int VEC, int L>
+__device__ __forceinline__ void fm_col_accumulate_packed(const int32_t* __restrict__ idx, const float* __restrict__ val,
+                                                         int64_t beg, int64_t end, const float* __restrict__ src,
+                                                         int64_t stride, int sub, int kb, int rl, float (&acc)[VEC],
+                                                         float& gw, float& s2)
+{
+    constexpr int CH = FmChunk<L>::CH;
+    const bool scalar_lane = sub == rl;
+    int64_t e = beg;
+    for (; e + L * CH <= end; e += L * CH) {
+        int ix[CH];
+        float xv[CH];
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int64_t my = e + u * L + sub;
+            ix[u] = idx[my];
+            xv[u] = val[my];
+        }
+        fm_gather_slots_packed<VEC, L, CH * L>(ix, xv, src, stride, kb, rl, scalar_lane, acc, gw, s2);
+    }
+    for (; e < end; e += L) {
+        const int64_t want = e + sub;
+        const bool has = want < end;
+        const int64_t my = has ? want : end - 1;
+        int ix[1];
+        float xv[1];
+        ix[0] = idx[my];
+        xv[0] = has ? val[my] : 0.f;
+        fm_gather_slots_packed<VEC, L, L>(ix, xv, src, stride, kb, rl, scalar_lane, acc, gw, s2);
+    }
+}

@@ -18,17 +18,27 @@ constexpr int FM_MAXP = 4096;
 constexpr int FM_XCDS = 8;                // L2 domains; workgroup b runs on XCD b % 8
 
 // Tunables of the column-side work decomposition (read once from the environment:
-// FM_SEG, FM_PANEL, FM_HEAVY_PER_PANEL, FM_VLONG).
+// FM_SEG, FM_PANEL, FM_HEAVY_PER_PANEL, FM_VLONG, FM_MIN_PANELS; or fm_set_tuning).
 struct FmTune {
     int seg;              // entries per work item of a long column
     int panel;            // rows per panel of the L2-blocked traversal of heavy columns
     int heavy_per_panel;  // a column is heavy if it averages at least this many entries per panel
     int vlong;            // columns with more items than this are finished by a whole workgroup
+    int min_panels;       // the panel order is used only for matrices with at least this many panels
 };
 const FmTune& fm_tune();
 
-// internal aggregate row: [G_0..G_{K-1}, r, a, q, pad] with a stride that is a multiple of 16 floats
-inline int64_t fm_aux_stride(int32_t K) { return ((int64_t)K + 3 + 15) / 16 * 16; }
+// Where the handle keeps the aggregates.  Packed: one row [G_0..G_{K-1}, r, a, q, pad] per
+// example with a stride that is a multiple of 16 floats.  Planar (default): G dense [N x K],
+// then r, a, q as dense vectors.
+struct FmAux {
+    float *G, *r, *a, *q;
+    int64_t gs, ss;
+};
+bool fm_aux_packed(int32_t K);
+int64_t fm_aux_floats(int64_t N, int32_t K);
+struct fm_matrix;
+FmAux fm_aux_layout(const fm_matrix* m, int32_t K);
 
 enum fm_kernel_id {
     FMK_ROWS_FORWARD = 0,
@@ -90,7 +100,7 @@ struct fm_matrix {
     LongIndex lstrat;
     // workspace, sized for wsK
     int32_t wsK = 0;
-    float* aux = nullptr;   // [N * fm_aux_stride(K)] rows [G | r | a | q | pad]
+    float* aux = nullptr;   // aggregates, see fm_aux_layout
     float* dV = nullptr;    // [D*K] last step's change of V
     float2* dwn = nullptr;  // [D] (change of w_j, change of |v_j|^2)
     float* part_acc = nullptr;  // [max items * K]
@@ -179,6 +189,7 @@ struct ColArgs {
     const float* r;
     const float* G;
     int64_t gs, rs;  // row strides of G and r in floats
+    int32_t packed;  // G rows are packed aggregate rows [G | r | a | q | pad] (r is read from the row)
     int32_t seg;     // columns longer than this are split into items
     float* w;        // updated in place when update
     float* V;

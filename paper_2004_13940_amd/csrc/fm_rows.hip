@@ -191,23 +191,21 @@ int launch_rows_v(fm_matrix* m, int lanes, const RowArgs& A, bool refresh, hipSt
 }  // namespace
 
 namespace {
-__global__ void k_unpack_aux(const float* __restrict__ aux, int64_t N, int32_t K, int64_t gs, float* a, float* G,
-                             float* q, float* r)
+__global__ void k_unpack_aux(const FmAux x, int64_t N, int32_t K, float* a, float* G, float* q, float* r)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t per = K + 3;
     if (t >= N * per) return;
     const int64_t i = t / per;
     const int c = (int)(t % per);
-    const float v = aux[i * gs + c];
     if (c < K) {
-        if (G != nullptr) G[i * K + c] = v;
+        if (G != nullptr) G[i * K + c] = x.G[i * x.gs + c];
     } else if (c == K) {
-        if (r != nullptr) r[i] = v;
+        if (r != nullptr) r[i] = x.r[i * x.ss];
     } else if (c == K + 1) {
-        if (a != nullptr) a[i] = v;
+        if (a != nullptr) a[i] = x.a[i * x.ss];
     } else {
-        if (q != nullptr) q[i] = v;
+        if (q != nullptr) q[i] = x.q[i * x.ss];
     }
 }
 }  // namespace
@@ -218,8 +216,8 @@ int fm_unpack_aux(fm_matrix* m, float* a, float* G, float* q, float* r, hipStrea
     if (total <= 0) return FM_OK;
     const int64_t grid = (total + 255) / 256;
     if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "aggregate copy too large");
-    hipLaunchKernelGGL(k_unpack_aux, dim3((unsigned)grid), dim3(256), 0, st, (const float*)m->aux, m->N, m->wsK,
-                       fm_aux_stride(m->wsK), a, G, q, r);
+    hipLaunchKernelGGL(k_unpack_aux, dim3((unsigned)grid), dim3(256), 0, st, fm_aux_layout(m, m->wsK), m->N, m->wsK, a, G,
+                       q, r);
     FM_HIP(m, hipGetLastError());
     return FM_OK;
 }

@@ -369,6 +369,36 @@ def test_results_are_bit_reproducible():
     m.close()
 
 
+def test_heavy_columns_through_the_panel_order_and_workgroup_finish():
+    """Small knobs force every code path of the column side at a size the oracle handles:
+    columns cut at row-panel boundaries and handed out per XCD list, plain segments,
+    short columns, and columns summed by a whole workgroup."""
+    import torch
+    B = _B()
+    B.fm_set_tuning(seg=16, panel=64, heavy_per_panel=2, vlong=8, min_panels=4)
+    try:
+        for K, loss in [(16, O.LOSS_LOGISTIC), (8, O.LOSS_SQUARED), (3, O.LOSS_LOGISTIC), (32, O.LOSS_SQUARED)]:
+            N, D = 5000, 300
+            rng = np.random.default_rng(40 + K)
+            dens = np.concatenate([[1.0, 1.0, 0.5, 0.2, 0.1, 0.05], rng.random(D - 6) ** 6 * 0.05])
+            mask = rng.random((N, D)) < dens[None, :]
+            rowptr = np.zeros(N + 1, np.int64)
+            np.cumsum(mask.sum(axis=1), out=rowptr[1:])
+            col = np.nonzero(mask)[1].astype(np.int32)
+            val = rng.standard_normal(len(col)).astype(np.float32)
+            y = (np.where(rng.random(N) < 0.5, 1.0, -1.0) if loss == O.LOSS_LOGISTIC else rng.standard_normal(N)).astype(np.float32)
+            w = (rng.standard_normal(D) * 0.1).astype(np.float32)
+            V = (rng.standard_normal((D, K)) * 0.1).astype(np.float32)
+            from paper_2004_13940_amd.workloads import Workload
+            wl = Workload("panels", N, D, K, rowptr, col, val, y, np.float32(0.05), w, V, loss, 1e-3, 2e-3, 0.3,
+                          1.0 / N, 3, 4, 1)
+            _say("panel path", K, loss, len(col))
+            m, p, X, dev, host = _run_full_epochs(B, wl, 3)
+            m.close()
+    finally:
+        B.fm_set_tuning(seg=256, panel=16384, heavy_per_panel=8, vlong=512, min_panels=64)
+
+
 # ------------------------------------------------------------ error paths ----
 
 def test_state_and_argument_errors_are_reported():
