@@ -164,8 +164,8 @@ int fm_profile_read(fm_matrix* m, int64_t* launches /*HOST nk*/, double* total_m
 /* Work-decomposition knobs of the column side, for callers that tune or test them; they
  * apply to matrices whose CSC is built afterwards.  A value <= 0 keeps the current one.
  *   seg              entries per work item of a long column                      (default 256)
- *   panel            rows per panel of the L2-blocked traversal of heavy columns (default 16384)
- *   heavy_per_panel  a column is heavy if it averages this many entries per panel (default 8)
+ *   panel            rows per panel of the L2-blocked traversal of heavy columns (default 32768)
+ *   heavy_per_panel  a column is heavy if it averages this many entries per panel (default 16)
  *   vlong            columns with more items are summed by a whole workgroup      (default 512)
  *   min_panels       matrices with fewer panels use plain segments only           (default 64)
  * Results do not depend on these values beyond fp32 rounding. */

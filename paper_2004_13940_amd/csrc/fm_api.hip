@@ -328,7 +328,10 @@ static void fill_long(ColArgs& A, const LongIndex& li, int32_t s, bool strat)
     A.item_beg = li.item_beg;
     A.item_len = li.item_len;
     A.order = strat ? nullptr : li.order;
+    A.ord_beg = li.ord_beg;
+    A.ord_len = li.ord_len;
     for (int x = 0; x <= FM_XCDS; ++x) A.list_off[x] = li.list_off[x];
+    for (int x = 0; x < FM_XCDS; ++x) A.list_mid[x] = li.list_mid[x];
     A.vlong = strat ? nullptr : li.vlong;
     A.nvlong = strat ? 0 : li.nvlong;
     A.vlong_items = fm_tune().vlong;

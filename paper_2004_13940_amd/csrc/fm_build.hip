@@ -376,6 +376,19 @@ __global__ __launch_bounds__(256) void k_full_items(const int64_t* __restrict__ 
     if (!pass && threadIdx.x == 0) nitems[lc] = running;
 }
 
+// item records copied into processing order, so that the column kernel streams them
+__global__ void k_order_items(const uint32_t* __restrict__ order, int64_t n, const int64_t* __restrict__ item_beg,
+                              const int32_t* __restrict__ item_len, int64_t* __restrict__ ord_beg,
+                              int32_t* __restrict__ ord_len)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        const uint32_t it = order[i];
+        ord_beg[i] = item_beg[it];
+        ord_len[i] = item_len[it];
+    }
+}
+
 __global__ void k_iota_u32(uint32_t* __restrict__ x, int64_t n)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -383,12 +396,14 @@ __global__ void k_iota_u32(uint32_t* __restrict__ x, int64_t n)
 }
 
 // list_off[x] = number of sorted keys smaller than x * (maxpos+1), x = 0..FM_XCDS
+// and list_off[FM_XCDS+1+x] = number of keys smaller than x*(maxpos+1)+maxpos (first non-panel item)
 __global__ void k_list_offsets(const uint32_t* __restrict__ keys, int64_t n, int64_t maxpos,
                                int64_t* __restrict__ list_off)
 {
     const int x = threadIdx.x;
-    if (x > FM_XCDS) return;
-    const int64_t bound = (int64_t)x * (maxpos + 1);
+    if (x > 2 * FM_XCDS) return;
+    const int64_t bound = x <= FM_XCDS ? (int64_t)x * (maxpos + 1)
+                                       : (int64_t)(x - FM_XCDS - 1) * (maxpos + 1) + maxpos;
     int64_t lo = 0, hi = n;
     while (lo < hi) {
         const int64_t mid = (lo + hi) >> 1;
@@ -529,8 +544,8 @@ static int env_int(const char* name, int dflt, int lo, int hi)
 
 static FmTune& tune_mut()
 {
-    static FmTune t = {env_int("FM_SEG", 256, 16, 1 << 20), env_int("FM_PANEL", 16384, 64, 1 << 30),
-                       env_int("FM_HEAVY_PER_PANEL", 8, 1, 1 << 20), env_int("FM_VLONG", 512, 1, 1 << 30),
+    static FmTune t = {env_int("FM_SEG", 256, 16, 1 << 20), env_int("FM_PANEL", 32768, 64, 1 << 30),
+                       env_int("FM_HEAVY_PER_PANEL", 16, 1, 1 << 20), env_int("FM_VLONG", 512, 1, 1 << 30),
                        env_int("FM_MIN_PANELS", 8 * FM_XCDS, 1, 1 << 30)};
     return t;
 }
@@ -622,13 +637,23 @@ int fm_build_full_index(fm_matrix* m, hipStream_t st)
     bool alt = false;
     FM_TRY(fm_sort_by_key_u32(m, k0, i0, k1, i1, nitems, bits_for((int64_t)FM_XCDS * (maxpos + 1)), st, &alt));
     int64_t* d_off = nullptr;
-    FM_TRY(fm_dev_alloc(m, (void**)&d_off, (FM_XCDS + 1) * sizeof(int64_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&d_off, (2 * FM_XCDS + 1) * sizeof(int64_t)));
     hipLaunchKernelGGL(k_list_offsets, dim3(1), dim3(64), 0, st, (const uint32_t*)(alt ? k1 : k0), nitems, maxpos, d_off);
     FM_HIP(m, hipGetLastError());
-    FM_HIP(m, hipMemcpyAsync(out->list_off, d_off, (FM_XCDS + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    int64_t h_off[2 * FM_XCDS + 1];
+    FM_HIP(m, hipMemcpyAsync(h_off, d_off, sizeof(h_off), hipMemcpyDeviceToHost, st));
     FM_HIP(m, hipStreamSynchronize(st));
+    for (int x = 0; x <= FM_XCDS; ++x) out->list_off[x] = h_off[x];
+    for (int x = 0; x < FM_XCDS; ++x) out->list_mid[x] = h_off[FM_XCDS + 1 + x];
     out->order = alt ? i1 : i0;
     fm_dev_free(m, alt ? i0 : i1);
+    FM_TRY(fm_dev_alloc(m, (void**)&out->ord_beg, (size_t)nitems * sizeof(int64_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&out->ord_len, (size_t)nitems * sizeof(int32_t)));
+    hipLaunchKernelGGL(k_order_items, dim3(blocks_for(nitems, 256)), dim3(256), 0, st, (const uint32_t*)out->order,
+                       nitems, (const int64_t*)out->item_beg, (const int32_t*)out->item_len, out->ord_beg,
+                       out->ord_len);
+    FM_HIP(m, hipGetLastError());
+    FM_HIP(m, hipStreamSynchronize(st));
     fm_dev_free(m, k0);
     fm_dev_free(m, k1);
     fm_dev_free(m, d_off);

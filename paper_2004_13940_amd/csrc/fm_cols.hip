@@ -20,14 +20,14 @@ namespace {
 
 // Accumulate one run of entries [beg,end) of a column into acc/gw/s2 (per-lane
 // partials for gw, s2; complete sums for acc's latent slice).
-template <int VEC, int L, bool PACKED>
+template <int VEC, int L, bool PACKED, bool NT>
 __device__ __forceinline__ void accumulate_entries(const ColArgs& A, int64_t beg, int64_t end, int sub, int kbase,
                                                    bool kact, float (&acc)[VEC], float& gw, float& s2)
 {
     if constexpr (PACKED) {
         // every lane reads inside the row: lanes past the scalars re-read its last VEC floats
         const int last = (int)A.gs - VEC;
-        fm_col_accumulate_packed<VEC, L>(A.row, A.val, beg, end, A.G, A.gs, sub, kbase < last ? kbase : last,
+        fm_col_accumulate_packed<VEC, L, NT>(A.row, A.val, beg, end, A.G, A.gs, sub, kbase < last ? kbase : last,
                                          A.K / VEC, acc, gw, s2);
     } else {
         const float* __restrict__ r = A.r;
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
 #pragma unroll
     for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
     float gw = 0.f, s2 = 0.f;
-    accumulate_entries<VEC, L, PACKED>(A, beg, end, sub, kbase, kact, acc, gw, s2);
+    accumulate_entries<VEC, L, PACKED, true>(A, beg, end, sub, kbase, kact, acc, gw, s2);  // short columns: no reuse
     gw = fm_group_sum<L>(gw);
     s2 = fm_group_sum<L>(s2);
 
@@ -174,27 +174,36 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
     const int grp = lane / L;
     const int slot_in_block = wave * R + grp;
     int64_t it = -1;
+    int64_t beg = 0, end = 0;
+    bool reused = false;  // item of a heavy column inside a panel: its rows are gathered again soon
     if (A.order != nullptr) {
         const int x = blockIdx.x % FM_XCDS;
         const int64_t pos = A.list_off[x] + (int64_t)(blockIdx.x / FM_XCDS) * (FM_WAVES * R) + slot_in_block;
-        if (pos < A.list_off[x + 1]) it = A.order[pos];
+        if (pos < A.list_off[x + 1]) {
+            it = A.order[pos];
+            beg = A.ord_beg[pos];
+            end = beg + A.ord_len[pos];
+        }
+        reused = pos < A.list_mid[x];
     } else {
         const int64_t pos = (int64_t)blockIdx.x * (FM_WAVES * R) + slot_in_block;
-        if (pos < A.nitems) it = A.item_base + pos;
+        if (pos < A.nitems) {
+            it = A.item_base + pos;
+            beg = A.item_beg[it];
+            end = beg + A.item_len[it];
+        }
     }
     const bool valid = it >= 0;
-    int64_t beg = 0, end = 0;
-    if (valid) {
-        beg = A.item_beg[it];
-        end = beg + A.item_len[it];
-    }
     const int kbase = sub * VEC;
     const bool kact = kbase < A.K;
     float acc[VEC];
 #pragma unroll
     for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
     float gw = 0.f, s2 = 0.f;
-    accumulate_entries<VEC, L, PACKED>(A, beg, end, sub, kbase, kact, acc, gw, s2);
+    if (reused)
+        accumulate_entries<VEC, L, PACKED, false>(A, beg, end, sub, kbase, kact, acc, gw, s2);
+    else
+        accumulate_entries<VEC, L, PACKED, true>(A, beg, end, sub, kbase, kact, acc, gw, s2);
     gw = fm_group_sum<L>(gw);
     s2 = fm_group_sum<L>(s2);
     if (valid) {

@@ -20,6 +20,25 @@ __device__ __forceinline__ void fm_load_vec(const float* __restrict__ p, float (
     }
 }
 
+// Same load with the non-temporal hint: the line is not kept in L2 ahead of lines that
+// were loaded normally.  Used on the column side for rows that will not be gathered again
+// soon, so that they do not push a panel's rows out of the 4 MB L2 of the XCD.
+typedef float fm_v4f __attribute__((ext_vector_type(4)));
+typedef float fm_v2f __attribute__((ext_vector_type(2)));
+template <int VEC>
+__device__ __forceinline__ void fm_load_vec_nt(const float* __restrict__ p, float (&v)[VEC])
+{
+    if constexpr (VEC == 4) {
+        const fm_v4f t = __builtin_nontemporal_load(reinterpret_cast<const fm_v4f*>(p));
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else if constexpr (VEC == 2) {
+        const fm_v2f t = __builtin_nontemporal_load(reinterpret_cast<const fm_v2f*>(p));
+        v[0] = t.x; v[1] = t.y;
+    } else {
+        v[0] = __builtin_nontemporal_load(p);
+    }
+}
+
 template <int VEC>
 __device__ __forceinline__ void fm_store_vec(float* __restrict__ p, const float (&v)[VEC])
 {
@@ -111,9 +130,9 @@ __device__ __forceinline__ void fm_gather_slots(const IX& ix, const MU& mu, cons
         fm_static_for<0, B>([&](auto sc) {
             constexpr int s = B0 + decltype(sc)::value;
             constexpr int u = s / L, T = s % L;
-            const int it = fm_bcast_i<L, T>(ix[u]);
+            const int raw = fm_bcast_i<L, T>(ix[u]);
             mt[s - B0] = fm_bcast_f<L, T>(mu[u]);
-            fm_load_vec<VEC>(src + (int64_t)it * stride + kb, g[s - B0]);
+            fm_load_vec<VEC>(src + (int64_t)raw * stride + kb, g[s - B0]);
         });
 #pragma unroll
         for (int s = 0; s < B; ++s) {
@@ -175,7 +194,7 @@ __device__ __forceinline__ void fm_gather_accumulate(const int32_t* __restrict__
 // scalars (lane rl = K/VEC of the group) supplies r to the others.  Per entry (row i, value x):
 //   acc[z] += x r_i G_i[kb+z]     on the latent lanes,
 //   gw += x r_i, s2 += x^2 r_i    on the scalar lane.
-template <int VEC, int L, int S, class IX, class XV>
+template <int VEC, int L, bool NT, int S, class IX, class XV>
 __device__ __forceinline__ void fm_gather_slots_packed(const IX& ix, const XV& xv, const float* __restrict__ src,
                                                        int64_t stride, int kb, int rl, bool scalar_lane,
                                                        float (&acc)[VEC], float& gw, float& s2)
@@ -190,7 +209,10 @@ __device__ __forceinline__ void fm_gather_slots_packed(const IX& ix, const XV& x
             constexpr int u = s / L, T = s % L;
             const int it = fm_bcast_i<L, T>(ix[u]);
             xt[s - B0] = fm_bcast_f<L, T>(xv[u]);
-            fm_load_vec<VEC>(src + (int64_t)it * stride + kb, g[s - B0]);
+            if constexpr (NT)
+                fm_load_vec_nt<VEC>(src + (int64_t)it * stride + kb, g[s - B0]);
+            else
+                fm_load_vec<VEC>(src + (int64_t)it * stride + kb, g[s - B0]);
         });
 #pragma unroll
         for (int s = 0; s < B; ++s) {
@@ -206,7 +228,7 @@ __device__ __forceinline__ void fm_gather_slots_packed(const IX& ix, const XV& x
     });
 }
 
-template <int VEC, int L>
+template <int VEC, int L, bool NT>
 __device__ __forceinline__ void fm_col_accumulate_packed(const int32_t* __restrict__ idx, const float* __restrict__ val,
                                                          int64_t beg, int64_t end, const float* __restrict__ src,
                                                          int64_t stride, int sub, int kb, int rl, float (&acc)[VEC],
@@ -224,7 +246,7 @@ __device__ __forceinline__ void fm_col_accumulate_packed(const int32_t* __restri
             ix[u] = idx[my];
             xv[u] = val[my];
         }
-        fm_gather_slots_packed<VEC, L, CH * L>(ix, xv, src, stride, kb, rl, scalar_lane, acc, gw, s2);
+        fm_gather_slots_packed<VEC, L, NT, CH * L>(ix, xv, src, stride, kb, rl, scalar_lane, acc, gw, s2);
     }
     for (; e < end; e += L) {
         const int64_t want = e + sub;
@@ -234,6 +256,6 @@ __device__ __forceinline__ void fm_col_accumulate_packed(const int32_t* __restri
         float xv[1];
         ix[0] = idx[my];
         xv[0] = has ? val[my] : 0.f;
-        fm_gather_slots_packed<VEC, L, L>(ix, xv, src, stride, kb, rl, scalar_lane, acc, gw, s2);
+        fm_gather_slots_packed<VEC, L, NT, L>(ix, xv, src, stride, kb, rl, scalar_lane, acc, gw, s2);
     }
 }

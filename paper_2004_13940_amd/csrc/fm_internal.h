@@ -65,7 +65,10 @@ struct LongIndex {
     // processing order of the full matrix: FM_XCDS lists of item ids, list x walked by the
     // workgroups that run on XCD x, heavy columns panel by panel (order == nullptr: id order)
     uint32_t* order = nullptr;      // [nitems]
+    int64_t* ord_beg = nullptr;     // [nitems] item_beg / item_len in processing order
+    int32_t* ord_len = nullptr;
     int64_t list_off[FM_XCDS + 1] = {0};
+    int64_t list_mid[FM_XCDS] = {0};  // in list x, positions from list_mid[x] on are not panel items
     int32_t* vlong = nullptr;       // [nvlong] indices into long_col of columns with > vlong items
     int64_t nvlong = 0;
 };
@@ -212,7 +215,10 @@ struct ColArgs {
     int64_t nlong, nitems;        // counts of this launch
     int64_t long_base, item_base;  // first long column / first item of this launch (absolute ids)
     const uint32_t* order;         // nullable: item ids in processing order, FM_XCDS lists
+    const int64_t* ord_beg;        // with order: item_beg / item_len in processing order
+    const int32_t* ord_len;
     int64_t list_off[FM_XCDS + 1];
+    int64_t list_mid[FM_XCDS];
     const int32_t* vlong;          // nullable: long columns finished by a whole workgroup
     int64_t nvlong;
     int32_t vlong_items;           // threshold that defines vlong

@@ -396,7 +396,7 @@ def test_heavy_columns_through_the_panel_order_and_workgroup_finish():
             m, p, X, dev, host = _run_full_epochs(B, wl, 3)
             m.close()
     finally:
-        B.fm_set_tuning(seg=256, panel=16384, heavy_per_panel=8, vlong=512, min_panels=64)
+        B.fm_set_tuning(seg=256, panel=32768, heavy_per_panel=16, vlong=512, min_panels=64)
 
 
 # ------------------------------------------------------------ error paths ----
