@@ -187,6 +187,24 @@ def stratum_cells(P, s):
     return [(p, (p + s) % P) for p in range(P)]
 
 
+def cell_update(X: Matrix, y, w0, w, V, a, G, q, r, rows, cols, *, loss, s, eta, rho, lambda_w, lambda_v,
+                dw, dV, dn):
+    """Phase A of one cell step, in place on (w, V, r) with the deltas recorded in (dw, dV, dn):
+    rows = (i_lo, i_hi), cols = (j_lo, j_hi).  All arrays fp64 and contiguous."""
+    K = V.shape[1]
+    _L().oracle_cell_update(_i32(K), _i32(loss), _f64(s), _f64(eta), _f64(rho), _f64(lambda_w), _f64(lambda_v),
+                            _i64(rows[0]), _i64(rows[1]), _i64(cols[0]), _i64(cols[1]), _p(X.colptr), _p(X.row),
+                            _p(X.cval), _p(y), _f64(w0), _p(a), _p(G), _p(q), _p(r), _p(w), _p(V), _p(dw), _p(dV),
+                            _p(dn))
+
+
+def refresh(X: Matrix, a, G, q, rows, cols, dw, dV, dn):
+    """Phase B of one cell step, in place on (a, G, q)."""
+    K = G.shape[1]
+    _L().oracle_refresh(_i32(K), _i64(rows[0]), _i64(rows[1]), _i64(cols[0]), _i64(cols[1]), _p(X.rowptr), _p(X.col),
+                        _p(X.val), _p(dw), _p(dV), _p(dn), _p(a), _p(G), _p(q))
+
+
 def stratified_epoch(X: Matrix, y, w0, w, V, *, P, loss, s, lambda_w, lambda_v, eta,
                      update_w0=True, reg_share=True, refresh_all_rows=False,
                      cell_order=None, on_stratum=None, final_objective=True):
