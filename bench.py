@@ -39,7 +39,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=4)
     ap.add_argument("--scale", type=float, default=1.0)
-    ap.add_argument("--cpu-rows", type=int, default=2_000_000, help="rows of the workload the oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=10_000_000, help="rows of the workload the oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stratified", action="store_true", help="also time fm_stratified_epoch (reported in extra)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -146,7 +146,7 @@ def main():
         kw = dict(loss=wl.loss, s=wl.loss_scale, lambda_w=wl.lambda_w, lambda_v=wl.lambda_v, eta=wl.eta,
                   update_w0=bool(wl.update_w0))
         ow0, ow, oV = float(wl.w0), wl.w, wl.V
-        reps = 2
+        reps = 3
         t0 = time.perf_counter()
         for _ in range(reps):
             ow0, ow, oV, _ = O.full_epoch(X, wl.y[:n], ow0, ow, oV, **kw)

@@ -599,15 +599,21 @@ int fm_build_full_index(fm_matrix* m, hipStream_t st)
                        (int32_t*)nullptr, (int64_t*)nullptr, (int32_t*)nullptr);
     FM_HIP(m, hipGetLastError());
     // 2. items per long column, then their first ids
-    const int64_t npanels = (m->N + T.panel - 1) / T.panel;
+    // Panels shrink (down to 1024 rows) so that a matrix of moderate height still has
+    // min_panels of them to spread over the XCD lists; the density that makes a column
+    // heavy (heavy_per_panel / panel) is kept.
+    int64_t panel = T.panel;
+    while (panel > 1024 && (m->N + panel - 1) / panel < T.min_panels) panel /= 2;
+    const int64_t npanels = (m->N + panel - 1) / panel;
+    const double heavy_density = (double)T.heavy_per_panel / (double)T.panel;
     // the panel order pays off only when there are many more panels than XCDs
     const int64_t heavy_min = npanels >= T.min_panels
-                                  ? std::max<int64_t>((int64_t)T.heavy_per_panel * npanels, (int64_t)T.seg + 1)
+                                  ? std::max<int64_t>((int64_t)(heavy_density * (double)m->N) + 1, (int64_t)T.seg + 1)
                                   : INT64_MAX;
     const int64_t maxpos = (npanels + FM_XCDS - 1) / FM_XCDS;
     FM_HIP(m, hipMemsetAsync(out->long_first, 0, (size_t)(nlong + 1) * sizeof(int64_t), st));
     hipLaunchKernelGGL(k_full_items, dim3((unsigned)nlong), dim3(256), 0, st, (const int64_t*)m->colptr,
-                       (const int32_t*)m->crow, (const int32_t*)out->long_col, m->N, T.seg, (int64_t)T.panel, heavy_min,
+                       (const int32_t*)m->crow, (const int32_t*)out->long_col, m->N, T.seg, panel, heavy_min,
                        maxpos, 0, out->long_first, (const int64_t*)nullptr, (int32_t*)nullptr, (int64_t*)nullptr,
                        (int32_t*)nullptr, (uint32_t*)nullptr);
     FM_HIP(m, hipGetLastError());
@@ -627,7 +633,7 @@ int fm_build_full_index(fm_matrix* m, hipStream_t st)
     FM_TRY(fm_dev_alloc(m, (void**)&k1, (size_t)nitems * 4));
     FM_TRY(fm_dev_alloc(m, (void**)&i1, (size_t)nitems * 4));
     hipLaunchKernelGGL(k_full_items, dim3((unsigned)nlong), dim3(256), 0, st, (const int64_t*)m->colptr,
-                       (const int32_t*)m->crow, (const int32_t*)out->long_col, m->N, T.seg, (int64_t)T.panel, heavy_min,
+                       (const int32_t*)m->crow, (const int32_t*)out->long_col, m->N, T.seg, panel, heavy_min,
                        maxpos, 1, (int64_t*)nullptr, (const int64_t*)out->long_first, out->item_col, out->item_beg,
                        out->item_len, k0);
     FM_HIP(m, hipGetLastError());
