@@ -28,7 +28,8 @@ def algorithmic_bytes(N, D, K, nnz, nnz_long, items, nlong):
     cols = 8 * short + 8 * (D + 1) + aux * (short / max(nnz, 1)) + 8 * (D - nlong) * (K + 1)
     cols_long = 8 * nnz_long + 16 * items + aux * (nnz_long / max(nnz, 1)) + 4 * items * (K + 2)
     cols_finish = 4 * items * (K + 2) + 12 * nlong + 8 * nlong * (K + 1)
-    return {"rows_forward": fwd, "cols": cols, "cols_long": cols_long, "cols_finish": cols_finish,
+    return {"rows_forward": fwd, "cols": cols, "cols_long": cols_long, "cols_tile": cols_long,
+            "cols_finish": cols_finish,
             "epoch": 16 * nnz + 8 * N * (K + 1) + 12 * D * (K + 1) + 12 * N + 8 * D}
 
 

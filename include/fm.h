@@ -170,6 +170,11 @@ int fm_profile_read(fm_matrix* m, int64_t* launches /*HOST nk*/, double* total_m
  *   min_panels       matrices with fewer panels use plain segments only           (default 64)
  * Results do not depend on these values beyond fp32 rounding. */
 int fm_set_tuning(int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t vlong, int32_t min_panels);
+/*   tile_rows     rows of aggregates staged in LDS by the kernel for dense-ish columns    (default 512)
+ *   min_per_tile  a column is dense-ish if it averages this many entries per tile; 0 = none (default 8)
+ *   tile_seg      entries per work item inside a tile                                     (default 256)
+ * min_per_tile < 0 keeps the current value. */
+int fm_set_tile_tuning(int32_t tile_rows, int32_t min_per_tile, int32_t tile_seg);
 
 int fm_destroy(fm_matrix* m);
 const char* fm_last_error(const fm_matrix* m); /* m may be NULL: last build error of this thread */

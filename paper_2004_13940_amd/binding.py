@@ -37,7 +37,7 @@ EXPORTS = ["fm_build_csr", "fm_build_csc", "fm_partition", "fm_get_csc", "fm_get
            "fm_get_stratum_nnz", "fm_get_stratum_csr", "fm_get_stratum_csc", "fm_forward", "fm_gradient",
            "fm_sgd_epoch", "fm_stratified_epoch", "fm_stratified_begin", "fm_stratified_step",
            "fm_stratified_end", "fm_get_aux", "fm_profile_enable", "fm_profile_kernels",
-           "fm_profile_kernel_name", "fm_profile_read", "fm_set_tuning", "fm_destroy", "fm_last_error"]
+           "fm_profile_kernel_name", "fm_profile_read", "fm_set_tuning", "fm_set_tile_tuning", "fm_destroy", "fm_last_error"]
 
 _lib = None
 
@@ -96,6 +96,10 @@ def make_params(K, loss, lambda_w, lambda_v, eta, loss_scale=1.0, update_w0=1, r
 
 def fm_set_tuning(seg=0, panel=0, heavy_per_panel=0, vlong=0, min_panels=0):
     load().fm_set_tuning(*(ctypes.c_int32(int(v)) for v in (seg, panel, heavy_per_panel, vlong, min_panels)))
+
+
+def fm_set_tile_tuning(tile_rows=0, min_per_tile=-1, tile_seg=0):
+    load().fm_set_tile_tuning(*(ctypes.c_int32(int(v)) for v in (tile_rows, min_per_tile, tile_seg)))
 
 
 class Matrix:

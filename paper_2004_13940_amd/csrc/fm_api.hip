@@ -64,7 +64,7 @@ ProfScope::~ProfScope()
 }
 
 static const char* const kKernelNames[FMK_COUNT] = {
-    "rows_forward", "rows_refresh", "cols", "cols_long", "cols_finish", "reduce", "bias"};
+    "rows_forward", "rows_refresh", "cols", "cols_long", "cols_tile", "cols_finish", "reduce", "bias"};
 
 extern "C" int fm_profile_enable(fm_matrix* m, int32_t on)
 {
@@ -332,6 +332,10 @@ static void fill_long(ColArgs& A, const LongIndex& li, int32_t s, bool strat)
     A.ord_len = li.ord_len;
     for (int x = 0; x <= FM_XCDS; ++x) A.list_off[x] = li.list_off[x];
     for (int x = 0; x < FM_XCDS; ++x) A.list_mid[x] = li.list_mid[x];
+    A.tile_rows = li.tile_rows;
+    A.ntiles = strat ? 0 : li.ntiles;
+    A.tile_ptr = li.tile_ptr;
+    A.lin_mode = 0;
     A.vlong = strat ? nullptr : li.vlong;
     A.nvlong = strat ? 0 : li.nvlong;
     A.vlong_items = fm_tune().vlong;

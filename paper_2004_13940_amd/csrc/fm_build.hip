@@ -322,10 +322,15 @@ __device__ __forceinline__ int64_t first_row_at_least(const int32_t* __restrict_
 // into segments of `seg`; its items carry the key (b % FM_XCDS, b / FM_XCDS) so that the
 // stable sort by key hands panel b to XCD b % FM_XCDS in ascending panel order.  Other
 // items get the last position of the list (slot % FM_XCDS) and run after the panels.
+// A column with at least tile_min entries ("dense-ish") is instead cut at the boundaries of
+// row tiles of `tile` rows and into segments of `tseg`; its items get the key
+// FM_XCDS*(maxpos+1) + tile id, i.e. they sort behind the eight lists, tile by tile, and are
+// processed by the kernel that stages a tile of aggregate rows in LDS.
 // One workgroup per long column; pass 0 counts, pass 1 fills.
 __global__ __launch_bounds__(256) void k_full_items(const int64_t* __restrict__ colptr, const int32_t* __restrict__ crow,
                                                     const int32_t* __restrict__ long_col, int64_t N, int seg,
-                                                    int64_t panel, int64_t heavy_min, int64_t maxpos, int pass,
+                                                    int64_t panel, int64_t heavy_min, int64_t maxpos, int64_t tile,
+                                                    int64_t tile_min, int tseg, int pass,
                                                     int64_t* __restrict__ nitems, const int64_t* __restrict__ long_first,
                                                     int32_t* __restrict__ item_col, int64_t* __restrict__ item_beg,
                                                     int32_t* __restrict__ item_len, uint32_t* __restrict__ item_key)
@@ -335,7 +340,8 @@ __global__ __launch_bounds__(256) void k_full_items(const int64_t* __restrict__ 
     const int32_t j = long_col[lc];
     const int64_t beg = colptr[j], end = colptr[j + 1], cnt = end - beg;
     const int64_t first = pass ? long_first[lc] : 0;
-    if (cnt < heavy_min) {
+    const bool tiled = cnt >= tile_min;
+    if (!tiled && cnt < heavy_min) {
         const int64_t nit = (cnt + seg - 1) / seg;
         if (!pass) {
             if (threadIdx.x == 0) nitems[lc] = nit;
@@ -350,30 +356,49 @@ __global__ __launch_bounds__(256) void k_full_items(const int64_t* __restrict__ 
         }
         return;
     }
-    const int64_t npanels = (N + panel - 1) / panel;
+    const int64_t piece = tiled ? tile : panel;  // rows per piece
+    const int64_t sg = tiled ? tseg : seg;       // entries per item inside a piece
+    const int64_t npieces = (N + piece - 1) / piece;
     int64_t running = 0;
-    for (int64_t b0 = 0; b0 < npanels; b0 += blockDim.x) {
+    for (int64_t b0 = 0; b0 < npieces; b0 += blockDim.x) {
         const int64_t b = b0 + threadIdx.x;
         int64_t lo = 0, hi = 0;
-        if (b < npanels) {
-            lo = first_row_at_least(crow, beg, end, b * panel);
-            hi = first_row_at_least(crow, lo, end, (b + 1) * panel);
+        if (b < npieces) {
+            lo = first_row_at_least(crow, beg, end, b * piece);
+            hi = first_row_at_least(crow, lo, end, (b + 1) * piece);
         }
-        const int64_t nb = (hi - lo + seg - 1) / seg;
+        const int64_t nb = (hi - lo + sg - 1) / sg;
         int64_t total;
         const int64_t off = block_exclusive_256(nb, sh, &total);
         if (pass) {
+            const uint32_t key = tiled ? (uint32_t)(FM_XCDS * (maxpos + 1) + b)
+                                       : (uint32_t)((b % FM_XCDS) * (maxpos + 1) + b / FM_XCDS);
             for (int64_t k = 0; k < nb; ++k) {
                 const int64_t slot = first + running + off + k;
                 item_col[slot] = j;
-                item_beg[slot] = lo + k * seg;
-                item_len[slot] = (int32_t)((hi - lo - k * seg) < seg ? (hi - lo - k * seg) : seg);
-                item_key[slot] = (uint32_t)((b % FM_XCDS) * (maxpos + 1) + b / FM_XCDS);
+                item_beg[slot] = lo + k * sg;
+                item_len[slot] = (int32_t)((hi - lo - k * sg) < sg ? (hi - lo - k * sg) : sg);
+                item_key[slot] = key;
             }
         }
         running += total;
     }
     if (!pass && threadIdx.x == 0) nitems[lc] = running;
+}
+
+// tile_ptr[t] = number of sorted keys smaller than base + t, t = 0..ntiles
+__global__ void k_tile_ptr(const uint32_t* __restrict__ keys, int64_t n, int64_t base, int64_t ntiles,
+                           int64_t* __restrict__ tile_ptr)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t > ntiles) return;
+    const int64_t bound = base + t;
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)keys[mid] < bound) lo = mid + 1; else hi = mid;
+    }
+    tile_ptr[t] = lo;
 }
 
 // item records copied into processing order, so that the column kernel streams them
@@ -546,11 +571,21 @@ static FmTune& tune_mut()
 {
     static FmTune t = {env_int("FM_SEG", 256, 16, 1 << 20), env_int("FM_PANEL", 32768, 64, 1 << 30),
                        env_int("FM_HEAVY_PER_PANEL", 16, 1, 1 << 20), env_int("FM_VLONG", 512, 1, 1 << 30),
-                       env_int("FM_MIN_PANELS", 8 * FM_XCDS, 1, 1 << 30)};
+                       env_int("FM_MIN_PANELS", 8 * FM_XCDS, 1, 1 << 30), env_int("FM_TILE", 512, 64, 1 << 20),
+                       env_int("FM_TILE_MIN", 8, 0, 1 << 20), env_int("FM_TILE_SEG", 256, 16, 1 << 20)};
     return t;
 }
 
 const FmTune& fm_tune() { return tune_mut(); }
+
+extern "C" int fm_set_tile_tuning(int32_t tile_rows, int32_t min_per_tile, int32_t tile_seg)
+{
+    FmTune& t = tune_mut();
+    if (tile_rows > 0) t.tile = tile_rows < 64 ? 64 : tile_rows;
+    if (min_per_tile >= 0) t.tile_min = min_per_tile;
+    if (tile_seg > 0) t.tile_seg = tile_seg < 16 ? 16 : tile_seg;
+    return FM_OK;
+}
 
 extern "C" int fm_set_tuning(int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t vlong, int32_t min_panels)
 {
@@ -611,10 +646,18 @@ int fm_build_full_index(fm_matrix* m, hipStream_t st)
                                   ? std::max<int64_t>((int64_t)(heavy_density * (double)m->N) + 1, (int64_t)T.seg + 1)
                                   : INT64_MAX;
     const int64_t maxpos = (npanels + FM_XCDS - 1) / FM_XCDS;
+    // dense-ish columns (at least tile_min entries per row tile on average) go to the LDS-staged kernel
+    const int64_t tile = T.tile;
+    const int64_t nrtiles = (m->N + tile - 1) / tile;
+    const int64_t tile_min = (T.tile_min > 0 && nrtiles >= 2)
+                                 ? std::max<int64_t>((int64_t)T.tile_min * nrtiles, (int64_t)T.seg + 1)
+                                 : INT64_MAX;
+    const int64_t key_tiles = (int64_t)FM_XCDS * (maxpos + 1);
+    if (key_tiles + nrtiles >= (1LL << 32)) return fm_fail(m, FM_ERANGE, "too many row tiles");
     FM_HIP(m, hipMemsetAsync(out->long_first, 0, (size_t)(nlong + 1) * sizeof(int64_t), st));
     hipLaunchKernelGGL(k_full_items, dim3((unsigned)nlong), dim3(256), 0, st, (const int64_t*)m->colptr,
                        (const int32_t*)m->crow, (const int32_t*)out->long_col, m->N, T.seg, panel, heavy_min,
-                       maxpos, 0, out->long_first, (const int64_t*)nullptr, (int32_t*)nullptr, (int64_t*)nullptr,
+                       maxpos, tile, tile_min, T.tile_seg, 0, out->long_first, (const int64_t*)nullptr, (int32_t*)nullptr, (int64_t*)nullptr,
                        (int32_t*)nullptr, (uint32_t*)nullptr);
     FM_HIP(m, hipGetLastError());
     FM_TRY(fm_scan_exclusive_i64(m, out->long_first, nlong + 1, st));
@@ -634,14 +677,14 @@ int fm_build_full_index(fm_matrix* m, hipStream_t st)
     FM_TRY(fm_dev_alloc(m, (void**)&i1, (size_t)nitems * 4));
     hipLaunchKernelGGL(k_full_items, dim3((unsigned)nlong), dim3(256), 0, st, (const int64_t*)m->colptr,
                        (const int32_t*)m->crow, (const int32_t*)out->long_col, m->N, T.seg, panel, heavy_min,
-                       maxpos, 1, (int64_t*)nullptr, (const int64_t*)out->long_first, out->item_col, out->item_beg,
+                       maxpos, tile, tile_min, T.tile_seg, 1, (int64_t*)nullptr, (const int64_t*)out->long_first, out->item_col, out->item_beg,
                        out->item_len, k0);
     FM_HIP(m, hipGetLastError());
     // 3. processing order: stable sort of the item ids by (XCD list, panel position)
     hipLaunchKernelGGL(k_iota_u32, dim3(blocks_for(nitems, 256)), dim3(256), 0, st, i0, nitems);
     FM_HIP(m, hipGetLastError());
     bool alt = false;
-    FM_TRY(fm_sort_by_key_u32(m, k0, i0, k1, i1, nitems, bits_for((int64_t)FM_XCDS * (maxpos + 1)), st, &alt));
+    FM_TRY(fm_sort_by_key_u32(m, k0, i0, k1, i1, nitems, bits_for(key_tiles + nrtiles), st, &alt));
     int64_t* d_off = nullptr;
     FM_TRY(fm_dev_alloc(m, (void**)&d_off, (2 * FM_XCDS + 1) * sizeof(int64_t)));
     hipLaunchKernelGGL(k_list_offsets, dim3(1), dim3(64), 0, st, (const uint32_t*)(alt ? k1 : k0), nitems, maxpos, d_off);
@@ -651,6 +694,16 @@ int fm_build_full_index(fm_matrix* m, hipStream_t st)
     FM_HIP(m, hipStreamSynchronize(st));
     for (int x = 0; x <= FM_XCDS; ++x) out->list_off[x] = h_off[x];
     for (int x = 0; x < FM_XCDS; ++x) out->list_mid[x] = h_off[FM_XCDS + 1 + x];
+    out->tile_rows = tile;
+    out->ntiles = 0;
+    if (out->list_off[FM_XCDS] < nitems) {  // there are tile items
+        out->ntiles = nrtiles;
+        FM_TRY(fm_dev_alloc(m, (void**)&out->tile_ptr, (size_t)(nrtiles + 1) * sizeof(int64_t)));
+        hipLaunchKernelGGL(k_tile_ptr, dim3(blocks_for(nrtiles + 1, 256)), dim3(256), 0, st,
+                           (const uint32_t*)(alt ? k1 : k0), nitems, key_tiles, nrtiles, out->tile_ptr);
+        FM_HIP(m, hipGetLastError());
+        FM_HIP(m, hipStreamSynchronize(st));
+    }
     out->order = alt ? i1 : i0;
     fm_dev_free(m, alt ? i0 : i1);
     FM_TRY(fm_dev_alloc(m, (void**)&out->ord_beg, (size_t)nitems * sizeof(int64_t)));

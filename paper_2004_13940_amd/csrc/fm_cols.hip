@@ -176,7 +176,16 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
     int64_t it = -1;
     int64_t beg = 0, end = 0;
     bool reused = false;  // item of a heavy column inside a panel: its rows are gathered again soon
-    if (A.order != nullptr) {
+    if (A.order != nullptr && A.lin_mode) {
+        const int64_t rel = (int64_t)blockIdx.x * (FM_WAVES * R) + slot_in_block;
+        if (rel < A.lin_count) {
+            const int64_t pos = A.lin_base + rel;
+            it = A.order[pos];
+            beg = A.ord_beg[pos];
+            end = beg + A.ord_len[pos];
+        }
+        reused = true;
+    } else if (A.order != nullptr) {
         const int x = blockIdx.x % FM_XCDS;
         const int64_t pos = A.list_off[x] + (int64_t)(blockIdx.x / FM_XCDS) * (FM_WAVES * R) + slot_in_block;
         if (pos < A.list_off[x + 1]) {
@@ -208,6 +217,103 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
     s2 = fm_group_sum<L>(s2);
     if (valid) {
         if (kact) fm_store_vec<VEC>(A.part_acc + it * A.K + kbase, acc);
+        if (sub == 0) A.part_gs[it] = make_float2(gw, s2);
+    }
+}
+
+// Dense-ish columns, LDS-staged: workgroup t copies the aggregate rows [G | r] of row tile t
+// (tile_rows rows of packed aggregate rows) into LDS once, then its groups walk the tile's items
+// (pieces of dense-ish columns whose rows lie inside the tile) and gather G and r from LDS.
+// One partial sum per item, as in k_cols_long.  L lanes of VEC=4 latent dimensions per group.
+template <int L>
+__global__ __launch_bounds__(FM_BLOCK) void k_cols_tile(const ColArgs A)
+{
+    constexpr int VEC = 4;
+    constexpr int NG = FM_BLOCK / L;
+    extern __shared__ float tile[];  // G part: tile_rows x K floats, then r: tile_rows floats
+    const int K = A.K;
+    const int S = K;
+    float* __restrict__ tile_r = tile + A.tile_rows * K;
+    const int chunks = K / VEC + 1;  // float4 chunks read per row (the last one holds r, a, q)
+    const int64_t t = blockIdx.x;
+    const int64_t row0 = t * A.tile_rows;
+    const int64_t nrows = (A.N - row0) < A.tile_rows ? (A.N - row0) : A.tile_rows;
+    {   // copy in batches of eight float4 per thread: all loads of a batch are issued before the first store
+        const int total = (int)nrows * chunks;
+        const float* __restrict__ src = A.G + row0 * A.gs;
+        constexpr int U = 8;
+        for (int c0 = threadIdx.x; c0 < total; c0 += U * FM_BLOCK) {
+            float4 v[U];
+            int dst[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = c0 + u * FM_BLOCK;
+                const int cc = c < total ? c : total - 1;
+                const int rr = cc / chunks, ch = cc - rr * chunks;
+                dst[u] = c < total ? (rr << 8) | ch : -1;  // chunks <= 64 for every K of this path
+                v[u] = *reinterpret_cast<const float4*>(src + (int64_t)rr * A.gs + ch * VEC);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (dst[u] < 0) continue;
+                const int rr = dst[u] >> 8, ch = dst[u] & 255;
+                if (ch < chunks - 1)
+                    *reinterpret_cast<float4*>(tile + rr * S + ch * VEC) = v[u];
+                else
+                    tile_r[rr] = v[u].x;
+            }
+        }
+    }
+    __syncthreads();
+
+    const int sub = threadIdx.x & (L - 1);
+    const int grp = threadIdx.x / L;
+    const int kbase = sub * VEC;
+    const bool kact = kbase < K;
+    const int kb = kact ? kbase : 0;
+    const int64_t pend = A.tile_ptr[t + 1];
+    for (int64_t pos = A.tile_ptr[t] + grp; pos < pend; pos += NG) {
+        const int64_t it = A.order[pos];
+        const int64_t beg = A.ord_beg[pos];
+        const int64_t end = beg + A.ord_len[pos];
+        float acc[VEC] = {0.f, 0.f, 0.f, 0.f};
+        float gw = 0.f, s2 = 0.f;
+        constexpr int CH = FmChunk<L>::CH;
+        for (int64_t e = beg; e < end; e += L * CH) {
+            int il[CH];
+            float xr[CH];
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {  // own entries: index and value from global memory
+                const int64_t my = e + u * L + sub;
+                const bool has = my < end;
+                const int64_t mc = has ? my : end - 1;
+                il[u] = (int)((int64_t)A.row[mc] - row0);
+                xr[u] = has ? A.val[mc] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {  // r of the own entry from LDS
+                const float x = xr[u];
+                xr[u] = x * tile_r[il[u]];
+                gw += xr[u];
+                s2 += x * xr[u];
+            }
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                fm_static_for<0, L>([&](auto tc) {
+                    constexpr int T = decltype(tc)::value;
+                    const int ir = fm_bcast_i<L, T>(il[u]);
+                    const float mt = fm_bcast_f<L, T>(xr[u]);
+                    const float4 g = *reinterpret_cast<const float4*>(tile + ir * S + kb);
+                    acc[0] += mt * g.x;
+                    acc[1] += mt * g.y;
+                    acc[2] += mt * g.z;
+                    acc[3] += mt * g.w;
+                });
+            }
+        }
+        gw = fm_group_sum<L>(gw);
+        s2 = fm_group_sum<L>(s2);
+        if (kact) fm_store_vec<VEC>(A.part_acc + it * K + kbase, acc);
         if (sub == 0) A.part_gs[it] = make_float2(gw, s2);
     }
 }
@@ -335,6 +441,44 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_finish_block(const ColArgs A)
     }
 }
 
+// LDS-staged kernel for the tile items; false if the tile does not fit in LDS for this K
+// (the caller then runs the items through k_cols_long).
+template <int L>
+bool launch_tile_l(const ColArgs& A, size_t lds, hipStream_t st)
+{
+    static bool attr_set = false;  // opt in once to more than the default 64 KB of dynamic LDS
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_cols_tile<L>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) != hipSuccess) {
+            (void)hipGetLastError();
+            if (lds > 64 * 1024) return false;
+        }
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_cols_tile<L>), dim3((unsigned)A.ntiles), dim3(FM_BLOCK), lds, st, A);
+    return true;
+}
+
+inline bool launch_tile(fm_matrix* m, const ColArgs& A, hipStream_t st)
+{
+    (void)m;
+    if (A.ntiles <= 0 || A.ntiles > 0x7fffffffLL || A.K % 4 != 0) return false;
+    const size_t lds = (size_t)A.tile_rows * (size_t)(A.K + 1) * sizeof(float);
+    if (lds > 150 * 1024) return false;
+    int need = A.K / 4, l = 1;
+    while (l < need) l <<= 1;
+    switch (l) {
+        case 1: return launch_tile_l<1>(A, lds, st);
+        case 2: return launch_tile_l<2>(A, lds, st);
+        case 4: return launch_tile_l<4>(A, lds, st);
+        case 8: return launch_tile_l<8>(A, lds, st);
+        case 16: return launch_tile_l<16>(A, lds, st);
+        case 32: return launch_tile_l<32>(A, lds, st);
+        case 64: return launch_tile_l<64>(A, lds, st);
+    }
+    return false;
+}
+
 template <int VEC, int L, bool PACKED>
 int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
 {
@@ -361,9 +505,26 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
             g2 = (A.nitems + per - 1) / per;
         }
         if (g2 > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "item grid too large");
-        {
+        if (g2 > 0) {
             ProfScope ps(m, st, FMK_COLS_LONG);
             hipLaunchKernelGGL((k_cols_long<VEC, L, PACKED>), dim3((unsigned)g2), dim3(FM_BLOCK), 0, st, A);
+            FM_HIP(m, hipGetLastError());
+        }
+        // items of dense-ish columns, sorted by row tile
+        const int64_t ntile_items = A.order != nullptr ? A.nitems - A.list_off[FM_XCDS] : 0;
+        if (ntile_items > 0) {
+            ProfScope ps(m, st, FMK_COLS_TILE);
+            bool staged = false;
+            if constexpr (PACKED) staged = launch_tile(m, A, st);
+            if (!staged) {  // same items through global memory
+                ColArgs B = A;
+                B.lin_mode = 1;
+                B.lin_base = A.list_off[FM_XCDS];
+                B.lin_count = ntile_items;
+                const int64_t g4 = (ntile_items + per - 1) / per;
+                if (g4 > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "item grid too large");
+                hipLaunchKernelGGL((k_cols_long<VEC, L, PACKED>), dim3((unsigned)g4), dim3(FM_BLOCK), 0, st, B);
+            }
             FM_HIP(m, hipGetLastError());
         }
         {

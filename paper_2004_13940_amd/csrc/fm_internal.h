@@ -25,6 +25,9 @@ struct FmTune {
     int heavy_per_panel;  // a column is heavy if it averages at least this many entries per panel
     int vlong;            // columns with more items than this are finished by a whole workgroup
     int min_panels;       // the panel order is used only for matrices with at least this many panels
+    int tile;             // rows per LDS tile of the kernel for dense-ish columns
+    int tile_min;         // a column is dense-ish if it averages this many entries per tile (0: none)
+    int tile_seg;         // entries per item inside a tile
 };
 const FmTune& fm_tune();
 
@@ -45,6 +48,7 @@ enum fm_kernel_id {
     FMK_ROWS_REFRESH,
     FMK_COLS,
     FMK_COLS_LONG,
+    FMK_COLS_TILE,
     FMK_COLS_FINISH,
     FMK_REDUCE,
     FMK_BIAS,
@@ -69,6 +73,9 @@ struct LongIndex {
     int32_t* ord_len = nullptr;
     int64_t list_off[FM_XCDS + 1] = {0};
     int64_t list_mid[FM_XCDS] = {0};  // in list x, positions from list_mid[x] on are not panel items
+    // items of dense-ish columns: positions list_off[FM_XCDS]..nitems of `order`, sorted by row tile
+    int64_t tile_rows = 0, ntiles = 0;
+    int64_t* tile_ptr = nullptr;    // [ntiles+1] positions in `order`
     int32_t* vlong = nullptr;       // [nvlong] indices into long_col of columns with > vlong items
     int64_t nvlong = 0;
 };
@@ -219,6 +226,10 @@ struct ColArgs {
     const int32_t* ord_len;
     int64_t list_off[FM_XCDS + 1];
     int64_t list_mid[FM_XCDS];
+    int64_t tile_rows, ntiles;     // dense-ish columns: items sorted by row tile, after the lists
+    const int64_t* tile_ptr;
+    int32_t lin_mode;              // k_cols_long: take positions lin_base.. of `order` in sequence
+    int64_t lin_base, lin_count;
     const int32_t* vlong;          // nullable: long columns finished by a whole workgroup
     int64_t nvlong;
     int32_t vlong_items;           // threshold that defines vlong

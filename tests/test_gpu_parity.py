@@ -376,6 +376,7 @@ def test_heavy_columns_through_the_panel_order_and_workgroup_finish():
     import torch
     B = _B()
     B.fm_set_tuning(seg=16, panel=64, heavy_per_panel=2, vlong=8, min_panels=4)
+    B.fm_set_tile_tuning(tile_rows=64, min_per_tile=12, tile_seg=16)
     try:
         for K, loss in [(16, O.LOSS_LOGISTIC), (8, O.LOSS_SQUARED), (3, O.LOSS_LOGISTIC), (32, O.LOSS_SQUARED)]:
             N, D = 5000, 300
@@ -397,6 +398,7 @@ def test_heavy_columns_through_the_panel_order_and_workgroup_finish():
             m.close()
     finally:
         B.fm_set_tuning(seg=256, panel=32768, heavy_per_panel=16, vlong=512, min_panels=64)
+        B.fm_set_tile_tuning(tile_rows=512, min_per_tile=8, tile_seg=256)
 
 
 # ------------------------------------------------------------ error paths ----
