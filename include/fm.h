@@ -153,7 +153,8 @@ int fm_get_aux(const fm_matrix* m, float* a /*N*/, float* G /*N*K*/, float* q /*
                void* hip_stream);
 
 /* Per-kernel timing with HIP events on the launch stream.  While enabled, every kernel
- * launch of this handle is bracketed by two events.  fm_profile_read waits for the
+ * launch of this handle is bracketed by two events, and kernels that normally overlap on
+ * internal side streams run back to back on the launch stream, so that each is timed alone.  fm_profile_read waits for the
  * stream, then reports for kernel id k (0 <= k < fm_profile_kernels()) the number of
  * launches and their total time in milliseconds since the last reset, and resets. */
 int fm_profile_enable(fm_matrix* m, int32_t on);

@@ -106,6 +106,10 @@ extern "C" int fm_destroy(fm_matrix* m)
     (void)hipDeviceSynchronize();
     for (void* p : m->allocs) (void)hipFree(p);
     if (m->h_scal != nullptr) (void)hipHostFree(m->h_scal);
+    if (m->side1 != nullptr) (void)hipStreamDestroy(m->side1);
+    if (m->side2 != nullptr) (void)hipStreamDestroy(m->side2);
+    for (hipEvent_t e : {m->ev_fork, m->ev_join1, m->ev_join2})
+        if (e != nullptr) (void)hipEventDestroy(e);
     for (const ProfRec& r : m->prof_recs) {
         (void)hipEventDestroy(r.a);
         (void)hipEventDestroy(r.b);
@@ -275,6 +279,24 @@ FmAux fm_aux_layout(const fm_matrix* m, int32_t K)
         x.q = x.a + m->N;
     }
     return x;
+}
+
+bool fm_side_streams(fm_matrix* m)
+{
+    if (m->side_state == 0) {
+        const char* e = getenv("FM_SIDE_STREAMS");
+        m->side_state = -1;
+        if (!(e != nullptr && *e == '0') &&
+            hipStreamCreateWithFlags(&m->side1, hipStreamNonBlocking) == hipSuccess &&
+            hipStreamCreateWithFlags(&m->side2, hipStreamNonBlocking) == hipSuccess &&
+            hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&m->ev_join1, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&m->ev_join2, hipEventDisableTiming) == hipSuccess)
+            m->side_state = 1;
+        else
+            (void)hipGetLastError();
+    }
+    return m->side_state == 1;
 }
 
 void fm_drop_workspace(fm_matrix* m)

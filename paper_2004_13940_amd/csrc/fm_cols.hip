@@ -486,12 +486,33 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     const int64_t per = FM_WAVES * R;
     const int64_t grid = (A.D + per - 1) / per;
     if (grid > 0x7fffffffLL || A.nlong > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
-    if (grid > 0) {
-        ProfScope ps(m, st, FMK_COLS);
-        if (update)
-            hipLaunchKernelGGL((k_cols<VEC, L, true, PACKED>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
-        else
-            hipLaunchKernelGGL((k_cols<VEC, L, false, PACKED>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
+    // The three accumulation kernels touch disjoint columns.  When there are LDS-staged items,
+    // k_cols and k_cols_tile go to two side streams so that the LDS-bound kernel overlaps the
+    // memory-bound ones; the finish kernels wait for all three.
+    const int64_t ntile_items = A.order != nullptr ? A.nitems - A.list_off[FM_XCDS] : 0;
+    // (not while per-kernel timing is on: each kernel is then timed alone on the launch stream)
+    const bool side = ntile_items > 0 && !m->prof && fm_side_streams(m);
+    hipStream_t s_cols = st, s_tile = st;
+    if (side) {
+        FM_HIP(m, hipEventRecord(m->ev_fork, st));
+        FM_HIP(m, hipStreamWaitEvent(m->side1, m->ev_fork, 0));
+        FM_HIP(m, hipStreamWaitEvent(m->side2, m->ev_fork, 0));
+        s_tile = m->side1;
+        s_cols = m->side2;
+    }
+    if (ntile_items > 0) {  // items of dense-ish columns, sorted by row tile
+        ProfScope ps(m, s_tile, FMK_COLS_TILE);
+        bool staged = false;
+        if constexpr (PACKED) staged = launch_tile(m, A, s_tile);
+        if (!staged) {  // same items through global memory
+            ColArgs B = A;
+            B.lin_mode = 1;
+            B.lin_base = A.list_off[FM_XCDS];
+            B.lin_count = ntile_items;
+            const int64_t g4 = (ntile_items + per - 1) / per;
+            if (g4 > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "item grid too large");
+            hipLaunchKernelGGL((k_cols_long<VEC, L, PACKED>), dim3((unsigned)g4), dim3(FM_BLOCK), 0, s_tile, B);
+        }
         FM_HIP(m, hipGetLastError());
     }
     if (A.nitems > 0) {
@@ -510,23 +531,22 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
             hipLaunchKernelGGL((k_cols_long<VEC, L, PACKED>), dim3((unsigned)g2), dim3(FM_BLOCK), 0, st, A);
             FM_HIP(m, hipGetLastError());
         }
-        // items of dense-ish columns, sorted by row tile
-        const int64_t ntile_items = A.order != nullptr ? A.nitems - A.list_off[FM_XCDS] : 0;
-        if (ntile_items > 0) {
-            ProfScope ps(m, st, FMK_COLS_TILE);
-            bool staged = false;
-            if constexpr (PACKED) staged = launch_tile(m, A, st);
-            if (!staged) {  // same items through global memory
-                ColArgs B = A;
-                B.lin_mode = 1;
-                B.lin_base = A.list_off[FM_XCDS];
-                B.lin_count = ntile_items;
-                const int64_t g4 = (ntile_items + per - 1) / per;
-                if (g4 > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "item grid too large");
-                hipLaunchKernelGGL((k_cols_long<VEC, L, PACKED>), dim3((unsigned)g4), dim3(FM_BLOCK), 0, st, B);
-            }
-            FM_HIP(m, hipGetLastError());
-        }
+    }
+    if (grid > 0) {
+        ProfScope ps(m, s_cols, FMK_COLS);
+        if (update)
+            hipLaunchKernelGGL((k_cols<VEC, L, true, PACKED>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, s_cols, A);
+        else
+            hipLaunchKernelGGL((k_cols<VEC, L, false, PACKED>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, s_cols, A);
+        FM_HIP(m, hipGetLastError());
+    }
+    if (side) {
+        FM_HIP(m, hipEventRecord(m->ev_join1, m->side1));
+        FM_HIP(m, hipEventRecord(m->ev_join2, m->side2));
+        FM_HIP(m, hipStreamWaitEvent(st, m->ev_join1, 0));
+        FM_HIP(m, hipStreamWaitEvent(st, m->ev_join2, 0));
+    }
+    if (A.nitems > 0) {
         {
             ProfScope ps(m, st, FMK_COLS_FINISH);
             const int64_t g3 = (A.nlong + FM_WAVES - 1) / FM_WAVES;

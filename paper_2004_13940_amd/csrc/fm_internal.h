@@ -120,6 +120,10 @@ struct fm_matrix {
     double* scal = nullptr;     // device scalars: 0 loss, 1 sum r, 2 |w|^2, 3 |V|^2
     double* h_scal = nullptr;   // pinned mirror
     bool aux_full = false;      // a, q valid (not only G, r)
+    // side streams so that the LDS-bound and the memory-bound column kernels overlap
+    hipStream_t side1 = nullptr, side2 = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join1 = nullptr, ev_join2 = nullptr;
+    int side_state = 0;  // 0 not tried, 1 ready, -1 unavailable or disabled
     // profiling
     bool prof = false;
     std::vector<ProfRec> prof_recs;
@@ -135,7 +139,8 @@ struct fm_matrix {
 int fm_fail(fm_matrix* m, int code, const char* fmt, ...);
 int fm_dev_alloc(fm_matrix* m, void** p, size_t bytes);
 void fm_dev_free(fm_matrix* m, void* p);
-void fm_drop_workspace(fm_matrix* m);  // forces reallocation after the structures changed
+void fm_drop_workspace(fm_matrix* m);
+bool fm_side_streams(fm_matrix* m);  // creates them on first use; false if disabled (FM_SIDE_STREAMS=0)  // forces reallocation after the structures changed
 
 #define FM_HIP(m, expr)                                                                  \
     do {                                                                                 \
