@@ -302,9 +302,9 @@ bool fm_side_streams(fm_matrix* m)
 void fm_drop_workspace(fm_matrix* m)
 {
     for (void* p : {(void*)m->aux, (void*)m->dV, (void*)m->dwn, (void*)m->part_acc, (void*)m->part_gs,
-                    (void*)m->row_part, (void*)m->col_part})
+                    (void*)m->row_part})
         fm_dev_free(m, p);
-    m->aux = m->dV = m->part_acc = m->row_part = m->col_part = nullptr;
+    m->aux = m->dV = m->part_acc = m->row_part = nullptr;
     m->dwn = nullptr;
     m->part_gs = nullptr;
     m->wsK = 0;
@@ -322,7 +322,6 @@ static int ensure_ws(fm_matrix* m, int32_t K)
     FM_TRY(fm_dev_alloc(m, (void**)&m->part_acc, (size_t)std::max<int64_t>(items, 1) * K * sizeof(float)));
     FM_TRY(fm_dev_alloc(m, (void**)&m->part_gs, (size_t)std::max<int64_t>(items, 1) * sizeof(float2)));
     FM_TRY(fm_dev_alloc(m, (void**)&m->row_part, (size_t)std::max<int64_t>(fm_rows_grid(m->N, K), 1) * 2 * sizeof(float)));
-    FM_TRY(fm_dev_alloc(m, (void**)&m->col_part, (size_t)std::max<int64_t>(fm_cols_grid(m->D, K), 1) * 2 * sizeof(float)));
     if (m->P > 0) {
         FM_TRY(fm_dev_alloc(m, (void**)&m->dV, D * K * sizeof(float)));
         FM_TRY(fm_dev_alloc(m, (void**)&m->dwn, D * sizeof(float2)));
@@ -362,6 +361,9 @@ static void fill_long(ColArgs& A, const LongIndex& li, int32_t s, bool strat)
     A.nvlong = strat ? 0 : li.nvlong;
     A.vlong_items = fm_tune().vlong;
     A.seg = fm_tune().seg;
+    const int64_t s0 = strat ? li.h_short_off[s] : 0, s1 = strat ? li.h_short_off[s + 1] : li.nshort;
+    A.short_col = li.short_col != nullptr ? li.short_col + s0 : nullptr;
+    A.nshort = s1 - s0;
 }
 
 // RowArgs outputs pointing into the handle's aggregate rows [G | r | a | q | pad]
@@ -502,6 +504,10 @@ extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, fl
     // steps 1-3: G, r, loss and sum r
     FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, nullptr, nullptr, nullptr, 1, true, st));
     m->aux_full = false;
+    if (objective != nullptr) {  // regulariser at the parameters the epoch starts from
+        FM_TRY(fm_reduce_sum(m, w, m->D, 1, true, m->scal + 2, st));
+        FM_TRY(fm_reduce_sum(m, V, m->D * (int64_t)p->K, 1, true, m->scal + 3, st));
+    }
     // steps 4-5 fused: gradient of every column and the step on w, V
     ColArgs A;
     base_col_args(m, p, A);
@@ -516,10 +522,8 @@ extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, fl
     A.packed = fm_aux_packed(p->K) ? 1 : 0;
     A.w = w;
     A.V = V;
-    A.col_part = objective != nullptr ? m->col_part : nullptr;
     fill_long(A, m->lfull, 0, false);
     FM_TRY(fm_launch_cols(m, A, true, st));
-    if (objective != nullptr) FM_TRY(fm_reduce_pairs(m, m->col_part, fm_cols_grid(m->D, p->K), m->scal + 2, st));
     if (p->update_w0) FM_TRY(fm_bias_step(m, w0, m->scal + 1, p->eta, nullptr, st));
     if (objective != nullptr) {
         FM_HIP(m, hipMemcpyAsync(m->h_scal, m->scal, 4 * sizeof(double), hipMemcpyDeviceToHost, st));

@@ -303,6 +303,58 @@ __global__ __launch_bounds__(LI_T) void k_long_fill(const int64_t* __restrict__ 
 }
 
 
+// -------------------------------------------- short non-empty columns ----
+// Columns with 1..seg entries, in (virtual) column order: k_cols works through this list;
+// empty columns only feel the regulariser and are handled by an elementwise kernel.
+__global__ __launch_bounds__(LI_T) void k_short_list(const int64_t* __restrict__ ptr, int64_t ncols, int64_t D, int seg,
+                                                     int pass, int64_t* __restrict__ tile_cnt,
+                                                     int32_t* __restrict__ short_col, int64_t* __restrict__ short_vcol)
+{
+    __shared__ int64_t sh[2][SCAN_T];
+    const int64_t base = (int64_t)blockIdx.x * LI_TILE + (int64_t)threadIdx.x * LI_E;
+    int64_t ns = 0;
+    for (int u = 0; u < LI_E; ++u) {
+        const int64_t c = base + u;
+        if (c < ncols) {
+            const int64_t len = ptr[c + 1] - ptr[c];
+            if (len > 0 && len <= seg) ns += 1;
+        }
+    }
+    int64_t total;
+    int64_t pos = block_exclusive_256(ns, sh, &total);
+    if (!pass) {
+        if (threadIdx.x == 0) tile_cnt[blockIdx.x] = total;
+        return;
+    }
+    pos += tile_cnt[blockIdx.x];
+    for (int u = 0; u < LI_E; ++u) {
+        const int64_t c = base + u;
+        if (c >= ncols) break;
+        const int64_t len = ptr[c + 1] - ptr[c];
+        if (len > 0 && len <= seg) {
+            short_col[pos] = (int32_t)(c % D);
+            short_vcol[pos] = c;
+            ++pos;
+        }
+    }
+}
+
+// off[s] = number of list entries with virtual column < s*D, s = 0..nstrata
+__global__ void k_stratum_offsets(const int64_t* __restrict__ vcol, int64_t n, int64_t D, int32_t nstrata,
+                                  int64_t* __restrict__ off)
+{
+    const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s > nstrata) return;
+    const int64_t bound = s * D;
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (vcol[mid] < bound) lo = mid + 1; else hi = mid;
+    }
+    off[s] = lo;
+}
+
+
 // ---------------------------------------------------- full-matrix items ----
 // first position in rows[beg,end) (ascending) whose row is >= bound
 __device__ __forceinline__ int64_t first_row_at_least(const int32_t* __restrict__ rows, int64_t beg, int64_t end,
@@ -501,9 +553,52 @@ int fm_sort_by_key_u32(fm_matrix* m, uint32_t* keys, uint32_t* idx, uint32_t* ke
     return rc;
 }
 
+
+// List of the non-empty columns with at most `seg` entries (per stratum when nstrata > 1).
+static int build_short_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
+                            LongIndex* out, hipStream_t st)
+{
+    out->nshort = 0;
+    out->h_short_off.assign(nstrata + 1, 0);
+    if (ncols_total <= 0) return FM_OK;
+    const int seg = fm_tune().seg;
+    const int64_t ntiles = (ncols_total + LI_TILE - 1) / LI_TILE;
+    int64_t* tc = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&tc, (size_t)(ntiles + 1) * sizeof(int64_t)));
+    FM_HIP(m, hipMemsetAsync(tc, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
+    hipLaunchKernelGGL(k_short_list, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, D, seg, 0, tc,
+                       (int32_t*)nullptr, (int64_t*)nullptr);
+    FM_HIP(m, hipGetLastError());
+    FM_TRY(fm_scan_exclusive_i64(m, tc, ntiles + 1, st));
+    int64_t n = 0;
+    FM_HIP(m, hipMemcpyAsync(&n, tc + ntiles, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    FM_HIP(m, hipStreamSynchronize(st));
+    if (n > 0) {
+        int64_t *vcol = nullptr, *d_off = nullptr;
+        FM_TRY(fm_dev_alloc(m, (void**)&out->short_col, (size_t)n * sizeof(int32_t)));
+        FM_TRY(fm_dev_alloc(m, (void**)&vcol, (size_t)n * sizeof(int64_t)));
+        FM_TRY(fm_dev_alloc(m, (void**)&d_off, (size_t)(nstrata + 1) * sizeof(int64_t)));
+        hipLaunchKernelGGL(k_short_list, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, D, seg, 1, tc,
+                           out->short_col, vcol);
+        FM_HIP(m, hipGetLastError());
+        hipLaunchKernelGGL(k_stratum_offsets, dim3(blocks_for(nstrata + 1, 256)), dim3(256), 0, st, (const int64_t*)vcol,
+                           n, D, nstrata, d_off);
+        FM_HIP(m, hipGetLastError());
+        FM_HIP(m, hipMemcpyAsync(out->h_short_off.data(), d_off, (size_t)(nstrata + 1) * sizeof(int64_t),
+                                 hipMemcpyDeviceToHost, st));
+        FM_HIP(m, hipStreamSynchronize(st));
+        fm_dev_free(m, vcol);
+        fm_dev_free(m, d_off);
+    }
+    out->nshort = n;
+    fm_dev_free(m, tc);
+    return FM_OK;
+}
+
 int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
                         LongIndex* out, hipStream_t st)
 {
+    FM_TRY(build_short_list(m, ptr, ncols_total, D, nstrata, out, st));
     out->nlong = out->nitems = 0;
     out->h_long_off.assign(nstrata + 1, 0);
     out->h_item_off.assign(nstrata + 1, 0);
@@ -602,6 +697,7 @@ int fm_build_full_index(fm_matrix* m, hipStream_t st)
 {
     LongIndex* out = &m->lfull;
     const FmTune& T = fm_tune();
+    FM_TRY(build_short_list(m, m->colptr, m->D, m->D, 1, out, st));
     out->nlong = out->nitems = 0;
     out->h_long_off.assign(2, 0);
     out->h_item_off.assign(2, 0);

@@ -96,7 +96,7 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
     }
 }
 
-// All columns; those longer than `seg` entries are left to the kernels below.
+// Short non-empty columns (1..seg entries), taken from a list: one group per column.
 template <int VEC, int L, bool UPDATE, bool PACKED>
 __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
 {
@@ -105,18 +105,16 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
     const int wave = threadIdx.x / FM_WAVE;
     const int sub = lane & (L - 1);
     const int grp = lane / L;
-    const int64_t j = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
-    const bool valid = j < A.D;
-    int64_t beg = 0, end = 0;
+    const int64_t pos = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
+    const bool valid = pos < A.nshort;
+    int64_t j = 0, beg = 0, end = 0;
     if (valid) {
+        j = A.short_col[pos];
         beg = A.ptr[j];
         end = A.ptr[j + 1];
     }
-    const bool is_long = (end - beg) > A.seg;
-    if (is_long) end = beg;
     const int kbase = sub * VEC;
     const bool kact = kbase < A.K;
-
     float acc[VEC];
 #pragma unroll
     for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
@@ -124,42 +122,28 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
     accumulate_entries<VEC, L, PACKED, true>(A, beg, end, sub, kbase, kact, acc, gw, s2);  // short columns: no reuse
     gw = fm_group_sum<L>(gw);
     s2 = fm_group_sum<L>(s2);
+    if (valid) finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, acc, gw, s2);
+}
 
-    float wsq = 0.f, vsq = 0.f;
-    if (A.col_part != nullptr && valid) {  // |w|^2, |V|^2 at the parameters before the step
-        if (kact) {
-            float v[VEC];
-            fm_load_vec<VEC>(A.V + j * A.K + kbase, v);
+// Columns with nothing stored (in this matrix or stratum) only feel the regulariser:
+// finish_column with zero data sums, one group of LE = K/VEC lanes per column over all D
+// columns, consecutive groups on consecutive columns so that V is streamed.
+template <int VEC, int LE, bool UPDATE>
+__global__ __launch_bounds__(FM_BLOCK) void k_cols_empty(const ColArgs A)
+{
+    constexpr int R = FM_WAVE / LE;
+    const int lane = threadIdx.x & (FM_WAVE - 1);
+    const int wave = threadIdx.x / FM_WAVE;
+    const int sub = lane & (LE - 1);
+    const int grp = lane / LE;
+    const int64_t j = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
+    if (j >= A.D) return;              // whole groups leave together
+    if (A.ptr[j + 1] != A.ptr[j]) return;
+    const int kbase = sub * VEC;
+    float acc[VEC];
 #pragma unroll
-            for (int z = 0; z < VEC; ++z) vsq += v[z] * v[z];
-        }
-        if (sub == 0) {
-            const float wj = A.w[j];
-            wsq = wj * wj;
-        }
-    }
-    if (valid && !is_long) finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, acc, gw, s2);
-
-    if (A.col_part != nullptr) {
-        __shared__ float sh[2 * FM_WAVES];
-        const float t0 = fm_wave_sum(wsq);
-        const float t1 = fm_wave_sum(vsq);
-        if (lane == 0) {
-            sh[wave] = t0;
-            sh[FM_WAVES + wave] = t1;
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            float u0 = 0.f, u1 = 0.f;
-#pragma unroll
-            for (int wv = 0; wv < FM_WAVES; ++wv) {
-                u0 += sh[wv];
-                u1 += sh[FM_WAVES + wv];
-            }
-            A.col_part[2 * (int64_t)blockIdx.x] = u0;
-            A.col_part[2 * (int64_t)blockIdx.x + 1] = u1;
-        }
-    }
+    for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
+    finish_column<VEC, LE, UPDATE>(A, j, sub, kbase, kbase < A.K, acc, 0.f, 0.f);
 }
 
 // One group per item of a long column: partial sums only.  With an order array,
@@ -479,13 +463,44 @@ inline bool launch_tile(fm_matrix* m, const ColArgs& A, hipStream_t st)
     return false;
 }
 
+// k_cols_empty with LE = smallest power of two >= K/VEC lanes per column
+template <int VEC, int LE>
+int launch_empty_l(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
+{
+    const int64_t per = (int64_t)FM_WAVES * (FM_WAVE / LE);
+    const int64_t grid = (A.D + per - 1) / per;
+    if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
+    if (update)
+        hipLaunchKernelGGL((k_cols_empty<VEC, LE, true>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
+    else
+        hipLaunchKernelGGL((k_cols_empty<VEC, LE, false>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
+    FM_HIP(m, hipGetLastError());
+    return FM_OK;
+}
+
+template <int VEC>
+int launch_empty(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
+{
+    int need = A.K / VEC, l = 1;
+    while (l < need) l <<= 1;
+    switch (l) {
+        case 1: return launch_empty_l<VEC, 1>(m, A, update, st);
+        case 2: return launch_empty_l<VEC, 2>(m, A, update, st);
+        case 4: return launch_empty_l<VEC, 4>(m, A, update, st);
+        case 8: return launch_empty_l<VEC, 8>(m, A, update, st);
+        case 16: return launch_empty_l<VEC, 16>(m, A, update, st);
+        case 32: return launch_empty_l<VEC, 32>(m, A, update, st);
+        case 64: return launch_empty_l<VEC, 64>(m, A, update, st);
+    }
+    return fm_fail(m, FM_EINVAL, "unsupported K=%d", A.K);
+}
+
 template <int VEC, int L, bool PACKED>
 int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
 {
     constexpr int R = FM_WAVE / L;
     const int64_t per = FM_WAVES * R;
-    const int64_t grid = (A.D + per - 1) / per;
-    if (grid > 0x7fffffffLL || A.nlong > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
+    if (A.nlong > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
     // The three accumulation kernels touch disjoint columns.  When there are LDS-staged items,
     // k_cols and k_cols_tile go to two side streams so that the LDS-bound kernel overlaps the
     // memory-bound ones; the finish kernels wait for all three.
@@ -532,13 +547,20 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
             FM_HIP(m, hipGetLastError());
         }
     }
-    if (grid > 0) {
+    {
         ProfScope ps(m, s_cols, FMK_COLS);
-        if (update)
-            hipLaunchKernelGGL((k_cols<VEC, L, true, PACKED>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, s_cols, A);
-        else
-            hipLaunchKernelGGL((k_cols<VEC, L, false, PACKED>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, s_cols, A);
-        FM_HIP(m, hipGetLastError());
+        const int64_t g1 = (A.nshort + per - 1) / per;
+        if (g1 > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
+        if (g1 > 0) {
+            if (update)
+                hipLaunchKernelGGL((k_cols<VEC, L, true, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK), 0, s_cols, A);
+            else
+                hipLaunchKernelGGL((k_cols<VEC, L, false, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK), 0, s_cols, A);
+            FM_HIP(m, hipGetLastError());
+        }
+        // empty columns: regulariser only (skipped when there is none and nothing records the change)
+        const bool need_empty = A.lambda_w != 0.f || A.lambda_v != 0.f || !update || A.dV != nullptr;
+        if (need_empty && A.D > 0) FM_TRY((launch_empty<VEC>(m, A, update, s_cols)));
     }
     if (side) {
         FM_HIP(m, hipEventRecord(m->ev_join1, m->side1));
@@ -596,14 +618,6 @@ static bool cols_shape(int32_t K, bool packed, int* vec, int* lanes)
         *lanes = l;
     }
     return true;
-}
-
-int64_t fm_cols_grid(int64_t D, int32_t K)
-{
-    int vec, lanes;
-    if (!cols_shape(K, fm_aux_packed(K), &vec, &lanes)) return 0;
-    const int64_t per = (int64_t)FM_WAVES * (FM_WAVE / lanes);
-    return (D + per - 1) / per;
 }
 
 int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)

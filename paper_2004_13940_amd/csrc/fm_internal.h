@@ -66,6 +66,10 @@ struct LongIndex {
     int64_t* item_beg = nullptr;    // [nitems]
     int32_t* item_len = nullptr;    // [nitems]
     std::vector<int64_t> h_long_off, h_item_off;  // per-stratum ranges (size P+1), or {0,nlong}
+    // non-empty columns with at most `seg` entries, in column order (per stratum: h_short_off)
+    int64_t nshort = 0;
+    int32_t* short_col = nullptr;
+    std::vector<int64_t> h_short_off;
     // processing order of the full matrix: FM_XCDS lists of item ids, list x walked by the
     // workgroups that run on XCD x, heavy columns panel by panel (order == nullptr: id order)
     uint32_t* order = nullptr;      // [nitems]
@@ -116,7 +120,6 @@ struct fm_matrix {
     float* part_acc = nullptr;  // [max items * K]
     float2* part_gs = nullptr;  // [max items]
     float* row_part = nullptr;  // [2 * row blocks]: loss, sum r
-    float* col_part = nullptr;  // [2 * col blocks]: sum w^2, sum V^2
     double* scal = nullptr;     // device scalars: 0 loss, 1 sum r, 2 |w|^2, 3 |V|^2
     double* h_scal = nullptr;   // pinned mirror
     bool aux_full = false;      // a, q valid (not only G, r)
@@ -212,7 +215,8 @@ struct ColArgs {
     float* grad_V;
     float* dV;       // delta outputs (nullable)
     float2* dwn;
-    float* col_part;  // nullable: [2*gridDim] sum w^2, sum V^2 per block (kernel over all columns only)
+    const int32_t* short_col;  // list of the short non-empty columns of this launch
+    int64_t nshort;
     float lambda_w, lambda_v, eta;
     // regulariser share: rho = 1 when rb == nullptr, else |I_p|/N with p = (colblock(j) - s) mod P
     const int64_t* rb;
@@ -242,7 +246,6 @@ struct ColArgs {
     float2* part_gs;
 };
 int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st);
-int64_t fm_cols_grid(int64_t D, int32_t K);
 
 int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st);
 int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, int64_t stride, bool square, double* out1, hipStream_t st);
