@@ -19,18 +19,36 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(N, D, K, nnz, nnz_long, items, nlong):
-    """Bytes each kernel must move if every array is streamed once and every gather is
-    served from cache (fp32 values, int32 indices, int64 pointers)."""
-    fwd = 8 * nnz + 8 * (N + 1) + 4 * N + 4 * D * (K + 1) + 4 * N * (K + 1)
-    aux = 4 * N * (K + 1)                       # compulsory read of r and G by the column side
-    short = nnz - nnz_long
-    cols = 8 * short + 8 * (D + 1) + aux * (short / max(nnz, 1)) + 8 * (D - nlong) * (K + 1)
-    cols_long = 8 * nnz_long + 16 * items + aux * (nnz_long / max(nnz, 1)) + 4 * items * (K + 2)
-    cols_finish = 4 * items * (K + 2) + 12 * nlong + 8 * nlong * (K + 1)
-    return {"rows_forward": fwd, "cols": cols, "cols_long": cols_long, "cols_tile": cols_long,
+def algorithmic_bytes(N, D, K, counts, seg=256, tile_rows=512, tile_min=8, tile_seg=256):
+    """Bytes each kernel must move if every array is streamed once and every gather is served
+    from cache (fp32 values, int32 indices, int64 pointers).  Columns are classed as the library
+    classes them: empty / short (<= seg entries) -> cols; dense-ish (>= tile_min entries per row
+    tile on average) -> cols_tile; the other long columns -> cols_long; partial sums of the long
+    columns are added by cols_finish.  The compulsory read of r and G (4N(K+1) bytes) is shared
+    between the three accumulation kernels in proportion to the entries they process."""
+    import numpy as np
+    nnz = int(counts.sum())
+    ntiles = (N + tile_rows - 1) // tile_rows
+    tile_thr = max(tile_min * ntiles, seg + 1) if ntiles >= 2 and tile_min > 0 else np.iinfo(np.int64).max
+    short = counts <= seg
+    tiled = counts >= tile_thr
+    longc = ~short & ~tiled
+    nnz_s, nnz_t, nnz_l = int(counts[short].sum()), int(counts[tiled].sum()), int(counts[longc].sum())
+    items_l = int(((counts[longc] + seg - 1) // seg).sum())
+    items_t = int(np.maximum(ntiles, (counts[tiled] + tile_seg - 1) // tile_seg).sum())
+    nlong = int((~short).sum())
+    aux = 4 * N * (K + 1)
+    fwd = 8 * nnz + 8 * (N + 1) + 4 * N + 4 * D * (K + 1) + aux
+    share = lambda e: aux * (e / max(nnz, 1))
+    cols = 8 * nnz_s + 8 * (D + 1) + 4 * int((short & (counts > 0)).sum()) + share(nnz_s) + 8 * int(short.sum()) * (K + 1)
+    cols_long = 8 * nnz_l + 16 * items_l + share(nnz_l) + 4 * items_l * (K + 2)
+    cols_tile = 8 * nnz_t + 16 * items_t + share(nnz_t) + 4 * items_t * (K + 2)
+    cols_finish = 4 * (items_l + items_t) * (K + 2) + 12 * nlong + 8 * nlong * (K + 1)
+    return {"rows_forward": fwd, "cols": cols, "cols_long": cols_long, "cols_tile": cols_tile,
             "cols_finish": cols_finish,
-            "epoch": 16 * nnz + 8 * N * (K + 1) + 12 * D * (K + 1) + 12 * N + 8 * D}
+            "epoch": 16 * nnz + 8 * N * (K + 1) + 12 * D * (K + 1) + 12 * N + 8 * D,
+            "classes": {"nnz_short": nnz_s, "nnz_long": nnz_l, "nnz_tile": nnz_t, "items_long": items_l,
+                        "items_tile": items_t, "long_columns": nlong}}
 
 
 def main():
@@ -102,13 +120,8 @@ def main():
         m.fm_sgd_epoch(p, y, w0, w, V)
     prof = m.fm_profile_read()
     m.fm_profile_enable(False)
-    counts = np.bincount(wl.col, minlength=wl.D)
-    seg = int(os.environ.get("FM_SEG", "256"))  # the library's default item length
-    long_mask = counts > seg
-    nnz_long = int(counts[long_mask].sum())
-    nlong = int(long_mask.sum())
-    items = int(((counts[long_mask] + seg - 1) // seg).sum())  # lower bound: panel cuts add a few
-    ab = algorithmic_bytes(wl.N, wl.D, wl.K, wl.nnz, nnz_long, items, nlong)
+    counts = np.bincount(wl.col, minlength=wl.D).astype(np.int64)
+    ab = algorithmic_bytes(wl.N, wl.D, wl.K, counts)
     kern = {k: {"launches": n, "avg_ms": ms / n} for k, (n, ms) in prof.items() if n > 0}
     dominant = max(kern, key=lambda k: kern[k]["avg_ms"] * kern[k]["launches"])
     dom_ms = kern[dominant]["avg_ms"]
@@ -125,7 +138,7 @@ def main():
                 "kernels": {k: {"avg_ms": v["avg_ms"], "algorithmic_GBs": ab[k] / (v["avg_ms"] * 1e-3) / 1e9}
                             for k, v in kern.items() if k in ab}}
 
-    extra = {"gen_s": t_gen, "upload_s": t_up, "csc_build_s": t_csc, "sha256": wl.sha256()[:16]}
+    extra = {"column_classes": ab["classes"], "gen_s": t_gen, "upload_s": t_up, "csc_build_s": t_csc, "sha256": wl.sha256()[:16]}
     if args.stratified:
         m.fm_partition(wl.P)
         m.fm_stratified_epoch(p, y, w0, w, V)
