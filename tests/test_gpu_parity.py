@@ -328,6 +328,23 @@ def test_stratified_variants_with_per_stratum_checks(P, flags):
     m.close()
 
 
+@pytest.mark.parametrize("K", [5, 12, 20, 60, 252, 256])
+def test_odd_and_large_latent_sizes_through_whole_epochs(K):
+    """K that is odd (one float per lane), not a power of two, at the limit of the packed
+    aggregate rows (252) and beyond it (256: planar rows, 64 lanes per group)."""
+    B = _B()
+    N, D = 700, 90
+    rowptr, col, val, y, w0, w, V = _problem(300 + K, N, D, K, 0.1, O.LOSS_LOGISTIC, dense_cols=(11,))
+    V *= np.float32(0.3)
+    from paper_2004_13940_amd.workloads import Workload
+    wl = Workload("ksize", N, D, K, rowptr, col, val, y, w0, w, V, O.LOSS_LOGISTIC, 1e-3, 1e-3, 0.2, 1.0 / N, 2, 3, 1)
+    _say("latent size", K, len(col))
+    m, p, X, dev, host = _run_full_epochs(B, wl, 2)
+    m.fm_partition(3)
+    _run_stratified_epochs(B, wl, m, p, X, dev, host, 1)
+    m.close()
+
+
 def test_single_block_stratified_epoch_equals_full_gradient_epoch_on_gpu():
     import torch
     B = _B()
