@@ -185,7 +185,32 @@ __device__ __forceinline__ void fm_gather_accumulate(const int32_t* __restrict__
         float mu[1];
         ix[0] = idx[my];
         mu[0] = own(ix[0], has ? val[my] : 0.f);
-        fm_gather_slots<VEC, L, SQ, L>(ix, mu, src, stride, kb, acc, sq);
+        if constexpr (L <= 4) {
+            fm_gather_slots<VEC, L, SQ, L>(ix, mu, src, stride, kb, acc, sq);
+        } else {
+            // wide groups: only the entries that exist, four gathers at a time
+            const int nv = (int)((end - e) < L ? (end - e) : L);
+            for (int t0 = 0; t0 < nv; t0 += 4) {
+                float g[4][VEC];
+                float mt[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int t = t0 + u < nv ? t0 + u : nv - 1;
+                    const int it = __shfl(ix[0], t, L);
+                    const float mm = __shfl(mu[0], t, L);
+                    mt[u] = t0 + u < nv ? mm : 0.f;
+                    fm_load_vec<VEC>(src + (int64_t)it * stride + kb, g[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                    for (int z = 0; z < VEC; ++z) {
+                        acc[z] += mt[u] * g[u][z];
+                        if constexpr (SQ) sq += (mt[u] * mt[u]) * (g[u][z] * g[u][z]);
+                    }
+                }
+            }
+        }
     }
 }
 
@@ -256,6 +281,37 @@ __device__ __forceinline__ void fm_col_accumulate_packed(const int32_t* __restri
         float xv[1];
         ix[0] = idx[my];
         xv[0] = has ? val[my] : 0.f;
-        fm_gather_slots_packed<VEC, L, NT, L>(ix, xv, src, stride, kb, rl, scalar_lane, acc, gw, s2);
+        if constexpr (L <= 4) {
+            fm_gather_slots_packed<VEC, L, NT, L>(ix, xv, src, stride, kb, rl, scalar_lane, acc, gw, s2);
+        } else {
+            // wide groups: only the entries that exist, four gathers at a time
+            const int nv = (int)((end - e) < L ? (end - e) : L);
+            for (int t0 = 0; t0 < nv; t0 += 4) {
+                float g[4][VEC];
+                float xt[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int t = t0 + u < nv ? t0 + u : nv - 1;
+                    const int it = __shfl(ix[0], t, L);
+                    const float x = __shfl(xv[0], t, L);
+                    xt[u] = t0 + u < nv ? x : 0.f;
+                    if constexpr (NT)
+                        fm_load_vec_nt<VEC>(src + (int64_t)it * stride + kb, g[u]);
+                    else
+                        fm_load_vec<VEC>(src + (int64_t)it * stride + kb, g[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float r = __shfl(g[u][0], rl, L);
+                    const float m = xt[u] * r;
+#pragma unroll
+                    for (int z = 0; z < VEC; ++z) acc[z] += m * g[u][z];
+                    if (scalar_lane) {
+                        gw += m;
+                        s2 += xt[u] * m;
+                    }
+                }
+            }
+        }
     }
 }
