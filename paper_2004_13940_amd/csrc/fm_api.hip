@@ -536,6 +536,16 @@ extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, fl
 
 // ------------------------------------------------------- stratified epoch ----
 
+// FM_LAZY_REG=0 makes fm_stratified_epoch take every column's step in every stratum.
+static bool fm_lazy_enabled()
+{
+    static const bool on = [] {
+        const char* e = getenv("FM_LAZY_REG");
+        return !(e != nullptr && e[0] == '0');
+    }();
+    return on;
+}
+
 extern "C" int fm_stratified_begin(fm_matrix* m, const fm_params* p, const float* y, const float* w0,
                                    const float* w, const float* V, void* hip_stream)
 {
@@ -551,20 +561,26 @@ extern "C" int fm_stratified_begin(fm_matrix* m, const fm_params* p, const float
     return FM_OK;
 }
 
-extern "C" int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const float* y, const float* w0,
-                                  float* w, float* V, void* hip_stream)
+// Column-side arguments of stratum s (s == P: the flush after the last stratum).
+static void strat_col_args(fm_matrix* m, const fm_params* p, int32_t s, float* w, float* V, bool lazy, ColArgs& A)
 {
-    if (m == nullptr) return FM_EINVAL;
-    FM_TRY(check_params(m, p));
-    if (m->P == 0) return fm_fail(m, FM_ESTATE, "stratified calls need fm_partition first");
-    if (s < 0 || s >= m->P) return fm_fail(m, FM_EINVAL, "stratum %d outside [0,%d)", s, m->P);
-    if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
-        return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
-    if (m->wsK != p->K || !m->aux_full) return fm_fail(m, FM_ESTATE, "call fm_stratified_begin first");
-    hipStream_t st = (hipStream_t)hip_stream;
+    base_col_args(m, p, A);
+    A.w = w;
+    A.V = V;
+    A.P = m->P;
+    A.s = s;
+    if (!p->reg_full_per_cell) A.rho = m->d_rho;
+    if (lazy) A.lazy_last = m->lazy_last;
+}
+
+// One stratum.  lazy: columns that are empty in their cell postpone their regulariser-only step
+// (the caller starts the epoch with lazy_last = 0 and flushes after the last stratum).
+static int stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const float* y, const float* w0, float* w,
+                           float* V, bool lazy, hipStream_t st)
+{
     // phase A: block gradients of the stratum's P cells and the step on every column block
     ColArgs A;
-    base_col_args(m, p, A);
+    strat_col_args(m, p, s, w, V, lazy, A);
     A.ptr = m->s_colptr + (int64_t)s * m->D;
     A.row = m->s_row;
     A.val = m->s_cval;
@@ -574,15 +590,8 @@ extern "C" int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, c
     A.gs = x.gs;
     A.rs = x.ss;
     A.packed = fm_aux_packed(p->K) ? 1 : 0;
-    A.w = w;
-    A.V = V;
     A.dV = m->dV;
     A.dwn = m->dwn;
-    if (!p->reg_full_per_cell) {
-        A.rb = m->d_rb;
-        A.P = m->P;
-        A.s = s;
-    }
     fill_long(A, m->lstrat, s, true);
     FM_TRY(fm_launch_cols(m, A, true, st));
     // phase B: incremental refresh of the aggregates and multipliers
@@ -598,6 +607,12 @@ extern "C" int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, c
         R.rowptr = m->s_rowptr + (int64_t)s * m->N;
         R.col = m->s_col;
         R.val = m->s_val;
+        if (m->s_touched != nullptr) {  // only the rows that have an entry in this stratum
+            R.rows = m->s_touched + m->h_touch_off[s];
+            R.N = m->h_touch_off[s + 1] - m->h_touch_off[s];
+        } else {
+            R.N = 0;
+        }
     }
     R.w0 = w0;
     R.V = m->dV;
@@ -607,6 +622,19 @@ extern "C" int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, c
     R.loss = p->loss;
     R.s = p->loss_scale;
     return fm_launch_rows(m, R, true, st);
+}
+
+extern "C" int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const float* y, const float* w0,
+                                  float* w, float* V, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    FM_TRY(check_params(m, p));
+    if (m->P == 0) return fm_fail(m, FM_ESTATE, "stratified calls need fm_partition first");
+    if (s < 0 || s >= m->P) return fm_fail(m, FM_EINVAL, "stratum %d outside [0,%d)", s, m->P);
+    if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
+        return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
+    if (m->wsK != p->K || !m->aux_full) return fm_fail(m, FM_ESTATE, "call fm_stratified_begin first");
+    return stratified_step(m, p, s, y, w0, w, V, false, (hipStream_t)hip_stream);
 }
 
 extern "C" int fm_stratified_end(fm_matrix* m, const fm_params* p, float* w0, void* hip_stream)
@@ -628,10 +656,20 @@ extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float
                                    double* objective, void* hip_stream)
 {
     FM_TRY(fm_stratified_begin(m, p, y, w0, w, V, hip_stream));
-    for (int32_t s = 0; s < m->P; ++s) FM_TRY(fm_stratified_step(m, p, s, y, w0, w, V, hip_stream));
+    hipStream_t st = (hipStream_t)hip_stream;
+    // The refresh of a stratum reads the change of a column only where the column has entries in
+    // its cell, so the regulariser-only steps of the other columns can wait (not when every row
+    // is refreshed from every column's change).
+    const bool lazy = !p->refresh_all_rows && m->lazy_last != nullptr && fm_lazy_enabled();
+    if (lazy) FM_HIP(m, hipMemsetAsync(m->lazy_last, 0, (size_t)m->D * sizeof(int32_t), st));
+    for (int32_t s = 0; s < m->P; ++s) FM_TRY(stratified_step(m, p, s, y, w0, w, V, lazy, st));
+    if (lazy) {
+        ColArgs F;
+        strat_col_args(m, p, m->P, w, V, true, F);
+        FM_TRY(fm_launch_cols_flush(m, F, st));
+    }
     FM_TRY(fm_stratified_end(m, p, w0, hip_stream));
     if (objective != nullptr) {
-        hipStream_t st = (hipStream_t)hip_stream;
         FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, nullptr, nullptr, nullptr, 2, true, st));
         FM_TRY(fm_reduce_sum(m, w, m->D, 1, true, m->scal + 2, st));
         FM_TRY(fm_reduce_sum(m, V, m->D * (int64_t)p->K, 1, true, m->scal + 3, st));

@@ -554,14 +554,15 @@ int fm_sort_by_key_u32(fm_matrix* m, uint32_t* keys, uint32_t* idx, uint32_t* ke
 }
 
 
-// List of the non-empty columns with at most `seg` entries (per stratum when nstrata > 1).
-static int build_short_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
-                            LongIndex* out, hipStream_t st)
+// List of the non-empty columns (or rows) with at most `seg` entries, per stratum when
+// nstrata > 1: h_off[s] is where stratum s starts in the list.
+static int build_nonempty_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
+                               int seg, int32_t** list_out, int64_t* count_out, std::vector<int64_t>* h_off,
+                               hipStream_t st)
 {
-    out->nshort = 0;
-    out->h_short_off.assign(nstrata + 1, 0);
+    *count_out = 0;
+    h_off->assign(nstrata + 1, 0);
     if (ncols_total <= 0) return FM_OK;
-    const int seg = fm_tune().seg;
     const int64_t ntiles = (ncols_total + LI_TILE - 1) / LI_TILE;
     int64_t* tc = nullptr;
     FM_TRY(fm_dev_alloc(m, (void**)&tc, (size_t)(ntiles + 1) * sizeof(int64_t)));
@@ -575,24 +576,31 @@ static int build_short_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_tota
     FM_HIP(m, hipStreamSynchronize(st));
     if (n > 0) {
         int64_t *vcol = nullptr, *d_off = nullptr;
-        FM_TRY(fm_dev_alloc(m, (void**)&out->short_col, (size_t)n * sizeof(int32_t)));
+        FM_TRY(fm_dev_alloc(m, (void**)list_out, (size_t)n * sizeof(int32_t)));
         FM_TRY(fm_dev_alloc(m, (void**)&vcol, (size_t)n * sizeof(int64_t)));
         FM_TRY(fm_dev_alloc(m, (void**)&d_off, (size_t)(nstrata + 1) * sizeof(int64_t)));
         hipLaunchKernelGGL(k_short_list, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, D, seg, 1, tc,
-                           out->short_col, vcol);
+                           *list_out, vcol);
         FM_HIP(m, hipGetLastError());
         hipLaunchKernelGGL(k_stratum_offsets, dim3(blocks_for(nstrata + 1, 256)), dim3(256), 0, st, (const int64_t*)vcol,
                            n, D, nstrata, d_off);
         FM_HIP(m, hipGetLastError());
-        FM_HIP(m, hipMemcpyAsync(out->h_short_off.data(), d_off, (size_t)(nstrata + 1) * sizeof(int64_t),
+        FM_HIP(m, hipMemcpyAsync(h_off->data(), d_off, (size_t)(nstrata + 1) * sizeof(int64_t),
                                  hipMemcpyDeviceToHost, st));
         FM_HIP(m, hipStreamSynchronize(st));
         fm_dev_free(m, vcol);
         fm_dev_free(m, d_off);
     }
-    out->nshort = n;
+    *count_out = n;
     fm_dev_free(m, tc);
     return FM_OK;
+}
+
+static int build_short_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
+                            LongIndex* out, hipStream_t st)
+{
+    return build_nonempty_list(m, ptr, ncols_total, D, nstrata, fm_tune().seg, &out->short_col, &out->nshort,
+                               &out->h_short_off, st);
 }
 
 int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
@@ -931,6 +939,11 @@ extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
     FM_TRY(fm_dev_alloc(m, (void**)&m->d_rb, (size_t)(P + 1) * sizeof(int64_t)));
     FM_TRY(fm_dev_alloc(m, (void**)&d_cb, (size_t)(P + 1) * sizeof(int64_t)));
     FM_HIP(m, hipMemcpy(m->d_rb, m->h_rb.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
+    std::vector<float> h_rho((size_t)P);
+    for (int32_t b = 0; b < P; ++b) h_rho[b] = (float)((double)(m->h_rb[b + 1] - m->h_rb[b]) / (double)m->N);
+    FM_TRY(fm_dev_alloc(m, (void**)&m->d_rho, (size_t)P * sizeof(float)));
+    FM_HIP(m, hipMemcpy(m->d_rho, h_rho.data(), (size_t)P * sizeof(float), hipMemcpyHostToDevice));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->lazy_last, (size_t)m->D * sizeof(int32_t)));
     FM_HIP(m, hipMemcpy(d_cb, m->h_cb.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
 
     FM_TRY(build_strata_side(m, true, st, &m->s_rowptr, &m->s_col, &m->s_val));
@@ -959,6 +972,9 @@ extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
     fm_dev_free(m, d_starts);
     fm_dev_free(m, d_cb);
     FM_TRY(fm_build_long_index(m, m->s_colptr, (int64_t)P * m->D, m->D, P, &m->lstrat, st));
+    // rows that have an entry in stratum s: the refresh of that stratum visits only these
+    FM_TRY(build_nonempty_list(m, m->s_rowptr, (int64_t)P * m->N, m->N, P, 0x7fffffff, &m->s_touched, &m->ntouched,
+                               &m->h_touch_off, st));
     FM_HIP(m, hipStreamSynchronize(st));
     fm_drop_workspace(m);
     return FM_OK;

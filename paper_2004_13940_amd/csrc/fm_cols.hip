@@ -43,13 +43,42 @@ __device__ __forceinline__ void accumulate_entries(const ColArgs& A, int64_t beg
     }
 }
 
-__device__ __forceinline__ float reg_share(const ColArgs& A, int64_t j)
+// Share of the regulariser that the step of stratum t applies to column block qb.
+__device__ __forceinline__ float reg_share(const ColArgs& A, int32_t qb, int32_t t)
 {
-    if (A.rb == nullptr) return 1.f;
-    const int32_t qb = fm_block_of(j, A.D, A.P);
-    int32_t p = (qb - A.s) % A.P;
+    if (A.rho == nullptr) return 1.f;
+    int32_t p = (qb - t) % A.P;
     if (p < 0) p += A.P;
-    return (float)((double)(A.rb[p + 1] - A.rb[p]) / (double)A.N);
+    return A.rho[p];
+}
+
+// Walks the shares of consecutive strata for one column block: start at stratum t, then
+// next() returns the share of the current stratum and moves on to the following one.
+struct ShareWalk {
+    const float* rho;
+    int32_t p, P;
+    __device__ __forceinline__ ShareWalk(const ColArgs& A, int32_t qb, int32_t t) : rho(A.rho), p(0), P(A.P)
+    {
+        if (rho != nullptr) {
+            p = (qb - t) % P;
+            if (p < 0) p += P;
+        }
+    }
+    __device__ __forceinline__ float next()
+    {
+        if (rho == nullptr) return 1.f;
+        const float x = rho[p];
+        p = p == 0 ? P - 1 : p - 1;
+        return x;
+    }
+};
+
+// The step of a column that has no entries in its cell: only the regulariser acts.  Written
+// with explicitly rounded operations, and finish_column with fused ones whose data part is
+// exactly zero for such a column, so that a postponed step gives the bits of an immediate one.
+__device__ __forceinline__ float reg_only_step(float x, float rl, float eta)
+{
+    return __fadd_rn(x, __fmul_rn(-eta, __fmul_rn(rl, x)));
 }
 
 // Turn the data sums of column j into the gradient, and either store it or take the
@@ -59,19 +88,31 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
                                               const float (&acc)[VEC], float gw, float s2)
 {
     const int K = A.K;
-    const float rho = reg_share(A, j);
+    const int32_t qb = A.rho != nullptr ? fm_block_of(j, A.D, A.P) : 0;
+    const float rho = reg_share(A, qb, A.s);
+    int32_t t0 = A.s;  // first stratum whose step this column has not taken yet
+    if constexpr (UPDATE) {
+        if (A.lazy_last != nullptr) t0 = A.lazy_last[j];
+    }
     float dn = 0.f;
     if (kact) {
         float v[VEC], g[VEC];
         fm_load_vec<VEC>(A.V + j * K + kbase, v);
+        ShareWalk sw(A, qb, t0);
+        for (int32_t t = t0; t < A.s; ++t) {
+            const float rl = __fmul_rn(sw.next(), A.lambda_v);
 #pragma unroll
-        for (int z = 0; z < VEC; ++z) g[z] = acc[z] - s2 * v[z] + rho * A.lambda_v * v[z];
+            for (int z = 0; z < VEC; ++z) v[z] = reg_only_step(v[z], rl, A.eta);
+        }
+        const float rl = __fmul_rn(rho, A.lambda_v);
+#pragma unroll
+        for (int z = 0; z < VEC; ++z) g[z] = __fmaf_rn(rl, v[z], __fmaf_rn(-s2, v[z], acc[z]));
         if constexpr (UPDATE) {
             float d[VEC], vn[VEC];
 #pragma unroll
             for (int z = 0; z < VEC; ++z) {
-                d[z] = -A.eta * g[z];
-                vn[z] = v[z] + d[z];
+                d[z] = __fmul_rn(-A.eta, g[z]);
+                vn[z] = __fadd_rn(v[z], d[z]);
                 dn += d[z] * (2.f * v[z] + d[z]);  // |v+d|^2 - |v|^2 without cancellation
             }
             fm_store_vec<VEC>(A.V + j * K + kbase, vn);
@@ -84,12 +125,15 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
         if (A.dwn != nullptr) dn = fm_group_sum<L>(dn);
     }
     if (sub == 0) {
-        const float wj = A.w[j];
-        const float g = gw + rho * A.lambda_w * wj;
+        float wj = A.w[j];
+        ShareWalk sw(A, qb, t0);
+        for (int32_t t = t0; t < A.s; ++t) wj = reg_only_step(wj, __fmul_rn(sw.next(), A.lambda_w), A.eta);
+        const float g = __fmaf_rn(__fmul_rn(rho, A.lambda_w), wj, gw);
         if constexpr (UPDATE) {
-            const float d = -A.eta * g;
-            A.w[j] = wj + d;
+            const float d = __fmul_rn(-A.eta, g);
+            A.w[j] = __fadd_rn(wj, d);
             if (A.dwn != nullptr) A.dwn[j] = make_float2(d, dn);
+            if (A.lazy_last != nullptr) A.lazy_last[j] = A.s + 1;
         } else {
             if (A.grad_w != nullptr) A.grad_w[j] = g;
         }
@@ -144,6 +188,41 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_empty(const ColArgs A)
 #pragma unroll
     for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
     finish_column<VEC, LE, UPDATE>(A, j, sub, kbase, kbase < A.K, acc, 0.f, 0.f);
+}
+
+// The postponed regulariser steps of every column, strata lazy_last[j] .. A.s-1 in order;
+// one group of LE lanes per column, consecutive columns in consecutive groups.
+template <int VEC, int LE>
+__global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
+{
+    constexpr int R = FM_WAVE / LE;
+    const int lane = threadIdx.x & (FM_WAVE - 1);
+    const int wave = threadIdx.x / FM_WAVE;
+    const int sub = lane & (LE - 1);
+    const int grp = lane / LE;
+    const int64_t j = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
+    if (j >= A.D) return;  // whole groups leave together
+    const int32_t t0 = A.lazy_last[j];
+    if (t0 >= A.s) return;
+    const int32_t qb = A.rho != nullptr ? fm_block_of(j, A.D, A.P) : 0;
+    const int kbase = sub * VEC;
+    if (kbase < A.K) {
+        float v[VEC];
+        fm_load_vec<VEC>(A.V + j * A.K + kbase, v);
+        ShareWalk sw(A, qb, t0);
+        for (int32_t t = t0; t < A.s; ++t) {
+            const float rl = __fmul_rn(sw.next(), A.lambda_v);
+#pragma unroll
+            for (int z = 0; z < VEC; ++z) v[z] = reg_only_step(v[z], rl, A.eta);
+        }
+        fm_store_vec<VEC>(A.V + j * A.K + kbase, v);
+    }
+    if (sub == 0) {
+        float wj = A.w[j];
+        ShareWalk sw(A, qb, t0);
+        for (int32_t t = t0; t < A.s; ++t) wj = reg_only_step(wj, __fmul_rn(sw.next(), A.lambda_w), A.eta);
+        A.w[j] = wj;
+    }
 }
 
 // One group per item of a long column: partial sums only.  With an order array,
@@ -495,6 +574,35 @@ int launch_empty(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     return fm_fail(m, FM_EINVAL, "unsupported K=%d", A.K);
 }
 
+template <int VEC, int LE>
+int launch_flush_l(fm_matrix* m, const ColArgs& A, hipStream_t st)
+{
+    const int64_t per = (int64_t)FM_WAVES * (FM_WAVE / LE);
+    const int64_t grid = (A.D + per - 1) / per;
+    if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
+    ProfScope ps(m, st, FMK_COLS);
+    hipLaunchKernelGGL((k_cols_flush<VEC, LE>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
+    FM_HIP(m, hipGetLastError());
+    return FM_OK;
+}
+
+template <int VEC>
+int launch_flush(fm_matrix* m, const ColArgs& A, hipStream_t st)
+{
+    int need = A.K / VEC, l = 1;
+    while (l < need) l <<= 1;
+    switch (l) {
+        case 1: return launch_flush_l<VEC, 1>(m, A, st);
+        case 2: return launch_flush_l<VEC, 2>(m, A, st);
+        case 4: return launch_flush_l<VEC, 4>(m, A, st);
+        case 8: return launch_flush_l<VEC, 8>(m, A, st);
+        case 16: return launch_flush_l<VEC, 16>(m, A, st);
+        case 32: return launch_flush_l<VEC, 32>(m, A, st);
+        case 64: return launch_flush_l<VEC, 64>(m, A, st);
+    }
+    return fm_fail(m, FM_EINVAL, "unsupported K=%d", A.K);
+}
+
 template <int VEC, int L, bool PACKED>
 int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
 {
@@ -559,7 +667,8 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
             FM_HIP(m, hipGetLastError());
         }
         // empty columns: regulariser only (skipped when there is none and nothing records the change)
-        const bool need_empty = A.lambda_w != 0.f || A.lambda_v != 0.f || !update || A.dV != nullptr;
+        const bool need_empty =
+            (A.lambda_w != 0.f || A.lambda_v != 0.f || !update || A.dV != nullptr) && A.lazy_last == nullptr;
         if (need_empty && A.D > 0) FM_TRY((launch_empty<VEC>(m, A, update, s_cols)));
     }
     if (side) {
@@ -629,5 +738,17 @@ int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
         case 4: return launch_cols_v<4, false>(m, lanes, A, update, st);
         case 2: return launch_cols_v<2, false>(m, lanes, A, update, st);
         default: return launch_cols_v<1, false>(m, lanes, A, update, st);
+    }
+}
+
+int fm_launch_cols_flush(fm_matrix* m, const ColArgs& A, hipStream_t st)
+{
+    int vec, lanes;
+    if (!fm_shape_for_K(A.K, &vec, &lanes)) return fm_fail(m, FM_EINVAL, "unsupported K=%d", A.K);
+    if (A.lazy_last == nullptr || A.D <= 0) return FM_OK;
+    switch (vec) {
+        case 4: return launch_flush<4>(m, A, st);
+        case 2: return launch_flush<2>(m, A, st);
+        default: return launch_flush<1>(m, A, st);
     }
 }

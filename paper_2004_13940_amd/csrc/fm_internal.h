@@ -105,6 +105,8 @@ struct fm_matrix {
     int32_t P = 0;
     std::vector<int64_t> h_rb, h_cb, h_cell_nnz, h_strat_nnz_off;  // bounds, P*P table, P+1 offsets
     int64_t* d_rb = nullptr;
+    float* d_rho = nullptr;        // [P] share |I_p|/N of the regulariser that a step on row block p applies
+    int32_t* lazy_last = nullptr;  // [D] see ColArgs::lazy_last
     int64_t* s_rowptr = nullptr;  // [P*N+1] global offsets into s_col/s_val
     int32_t* s_col = nullptr;
     float* s_val = nullptr;
@@ -112,6 +114,9 @@ struct fm_matrix {
     int32_t* s_row = nullptr;
     float* s_cval = nullptr;
     LongIndex lstrat;
+    int32_t* s_touched = nullptr;  // per stratum: the rows with at least one entry there, ascending
+    int64_t ntouched = 0;
+    std::vector<int64_t> h_touch_off;  // [P+1] offsets into s_touched
     // workspace, sized for wsK
     int32_t wsK = 0;
     float* aux = nullptr;   // aggregates, see fm_aux_layout
@@ -191,6 +196,7 @@ struct RowArgs {
     int64_t gs;         // floats between consecutive rows of G
     int64_t ss;         // floats between consecutive rows of r, a, q (1, or the aggregate row stride)
     float* row_part;    // nullable: [2*gridDim] loss and sum r per block
+    const int32_t* rows;  // nullable: the launch covers rows[0..N) instead of rows 0..N-1
     int32_t loss;
     float s;
 };
@@ -218,10 +224,15 @@ struct ColArgs {
     const int32_t* short_col;  // list of the short non-empty columns of this launch
     int64_t nshort;
     float lambda_w, lambda_v, eta;
-    // regulariser share: rho = 1 when rb == nullptr, else |I_p|/N with p = (colblock(j) - s) mod P
-    const int64_t* rb;
+    // regulariser share: rho = 1 when rho == nullptr, else rho[p] = |I_p|/N with p = (colblock(j) - s) mod P
+    const float* rho;
     int64_t N;
     int32_t P, s;
+    // nullable, update only: lazy_last[j] = number of strata of this epoch whose step column j has
+    // taken.  A column that is empty in a cell only feels the regulariser there; with this array
+    // those steps are postponed until the column next has entries (or the epoch ends) and then
+    // taken in order, so no pass over the columns that are empty in a stratum is needed.
+    int32_t* lazy_last;
     // long-column items
     const int32_t* long_col;
     const int64_t* long_first;
@@ -246,6 +257,8 @@ struct ColArgs {
     float2* part_gs;
 };
 int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st);
+// takes the postponed regulariser steps of every column up to stratum A.s (exclusive)
+int fm_launch_cols_flush(fm_matrix* m, const ColArgs& A, hipStream_t st);
 
 int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st);
 int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, int64_t stride, bool square, double* out1, hipStream_t st);

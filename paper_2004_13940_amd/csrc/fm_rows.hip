@@ -44,8 +44,12 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
     const int wave = threadIdx.x / FM_WAVE;
     const int sub = lane & (L - 1);
     const int grp = lane / L;
-    const int64_t row = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
-    const bool valid = row < A.N;
+    const int64_t slot = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
+    const bool valid = slot < A.N;
+    int64_t row = slot;
+    if constexpr (MODE == MODE_REFRESH) {
+        if (A.rows != nullptr && valid) row = A.rows[slot];
+    }
     int64_t beg = 0, end = 0;
     if (valid) {
         beg = A.rowptr[row];
@@ -60,6 +64,9 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
     for (int u = 0; u < VEC; ++u) acc[u] = 0.f;
     float a_acc = 0.f, q_acc = 0.f;
     const int kb = kact ? kbase : 0;
+    [[maybe_unused]] bool touched = false;
+    [[maybe_unused]] float g_old[VEC] = {};
+    [[maybe_unused]] float a_old = 0.f, q_old = 0.f;
     if constexpr (MODE == MODE_FORWARD) {
         const float* __restrict__ w = A.w;
         fm_gather_accumulate<VEC, L, true>(A.col, A.val, beg, end, A.V, K, sub, kb, acc, q_acc,
@@ -68,6 +75,15 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
                                                return x;
                                            });
     } else {
+        // rows that have no entry in this stratum keep their aggregates untouched
+        touched = valid && beg < end;  // uniform inside a group
+        if (touched) {  // issued before the gathers so that it overlaps them
+            if (kact) fm_load_vec<VEC>(A.G + row * A.gs + kbase, g_old);
+            if (sub == 0) {
+                a_old = A.a[row * A.ss];
+                q_old = A.q[row * A.ss];
+            }
+        }
         const float2* __restrict__ dwn = A.dwn;
         float unused = 0.f;
         fm_gather_accumulate<VEC, L, false>(A.col, A.val, beg, end, A.V, K, sub, kb, acc, unused,
@@ -106,25 +122,22 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
             }
         }
     } else {
-        // rows that have no entry in this stratum keep their aggregates untouched
-        const bool touched = valid && beg < end;  // uniform inside a group
         const float da = fm_group_sum<L>(a_acc);
         const float dq = fm_group_sum<L>(q_acc);
         float pair = 0.f;
         if (touched && kact) {
             float g[VEC];
-            fm_load_vec<VEC>(A.G + row * A.gs + kbase, g);
 #pragma unroll
             for (int z = 0; z < VEC; ++z) {
-                g[z] += acc[z];
+                g[z] = g_old[z] + acc[z];
                 pair += g[z] * g[z];
             }
             fm_store_vec<VEC>(A.G + row * A.gs + kbase, g);
         }
         pair = fm_group_sum<L>(pair);
         if (touched && sub == 0) {
-            const float a_i = A.a[row * A.ss] + da;
-            const float q_i = A.q[row * A.ss] + dq;
+            const float a_i = a_old + da;
+            const float q_i = q_old + dq;
             A.a[row * A.ss] = a_i;
             A.q[row * A.ss] = q_i;
             const float yh = A.w0[0] + a_i + 0.5f * (pair - q_i);

@@ -365,6 +365,33 @@ def test_single_block_stratified_epoch_equals_full_gradient_epoch_on_gpu():
     m.close()
 
 
+@pytest.mark.parametrize("idx,scale,P,full_reg", [(3, 0.05, 8, False), (5, 0.002, 16, False), (5, 0.002, 5, True)])
+def test_postponed_regulariser_steps_give_the_bits_of_immediate_ones(idx, scale, P, full_reg):
+    """fm_stratified_epoch lets a column that is empty in its cell take its regulariser-only steps
+    later, in order; fm_stratified_step takes every step at once.  Same arithmetic, same bits."""
+    import torch
+    B = _B()
+    wl = make_config(idx, scale=scale)
+    m = B.Matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
+    m.fm_build_csc()
+    m.fm_partition(P)
+    p = B.make_params(wl.K, wl.loss, 1e-2, 2e-2, wl.eta, wl.loss_scale, 1)
+    p.reg_full_per_cell = int(full_reg)
+    y = to_dev(wl.y)
+    a0, aw, aV = dev_params(wl.w0, wl.w, wl.V)
+    b0, bw, bV = dev_params(wl.w0, wl.w, wl.V)
+    for _ in range(2):
+        m.fm_stratified_epoch(p, y, a0, aw, aV)
+        m.fm_stratified_begin(p, y, b0, bw, bV)
+        for s in range(P):
+            m.fm_stratified_step(p, s, y, b0, bw, bV)
+        m.fm_stratified_end(p, b0)
+        torch.cuda.synchronize()
+        assert torch.equal(aw, bw) and torch.equal(aV, bV) and torch.equal(a0, b0)
+    assert not torch.equal(aw, to_dev(wl.w))
+    m.close()
+
+
 def test_results_are_bit_reproducible():
     import torch
     B = _B()
