@@ -259,6 +259,12 @@ bool fm_aux_packed(int32_t K)
 
 static int64_t packed_stride(int32_t K) { return ((int64_t)K + 3 + 15) / 16 * 16; }
 
+int fm_cols_packed_mode(int32_t K)
+{
+    if (!fm_aux_packed(K)) return FM_PLANAR;
+    return K + 1 <= 32 ? FM_PACKED_LANE : FM_PACKED_LOAD;
+}
+
 int64_t fm_aux_floats(int64_t N, int32_t K) { return fm_aux_packed(K) ? N * packed_stride(K) : N * ((int64_t)K + 3); }
 
 FmAux fm_aux_layout(const fm_matrix* m, int32_t K)
@@ -519,7 +525,7 @@ extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, fl
     A.G = x.G;
     A.gs = x.gs;
     A.rs = x.ss;
-    A.packed = fm_aux_packed(p->K) ? 1 : 0;
+    A.packed = fm_cols_packed_mode(p->K);
     A.w = w;
     A.V = V;
     fill_long(A, m->lfull, 0, false);
@@ -589,7 +595,7 @@ static int stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const fl
     A.G = x.G;
     A.gs = x.gs;
     A.rs = x.ss;
-    A.packed = fm_aux_packed(p->K) ? 1 : 0;
+    A.packed = fm_cols_packed_mode(p->K);
     A.dV = m->dV;
     A.dwn = m->dwn;
     fill_long(A, m->lstrat, s, true);

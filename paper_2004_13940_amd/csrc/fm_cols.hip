@@ -20,15 +20,19 @@ namespace {
 
 // Accumulate one run of entries [beg,end) of a column into acc/gw/s2 (per-lane
 // partials for gw, s2; complete sums for acc's latent slice).
-template <int VEC, int L, bool PACKED, bool NT>
+template <int VEC, int L, int PACKED, bool NT>
 __device__ __forceinline__ void accumulate_entries(const ColArgs& A, int64_t beg, int64_t end, int sub, int kbase,
                                                    bool kact, float (&acc)[VEC], float& gw, float& s2)
 {
-    if constexpr (PACKED) {
+    if constexpr (PACKED == FM_PACKED_LANE) {
         // every lane reads inside the row: lanes past the scalars re-read its last VEC floats
         const int last = (int)A.gs - VEC;
-        fm_col_accumulate_packed<VEC, L, NT>(A.row, A.val, beg, end, A.G, A.gs, sub, kbase < last ? kbase : last,
-                                         A.K / VEC, acc, gw, s2);
+        fm_col_accumulate_packed<VEC, L, NT, true>(A.row, A.val, beg, end, A.G, A.gs, sub, kbase < last ? kbase : last,
+                                                   A.K, acc, gw, s2);
+    } else if constexpr (PACKED == FM_PACKED_LOAD) {
+        // idle lanes of a group wider than K/VEC read a valid slice and discard it
+        fm_col_accumulate_packed<VEC, L, NT, false>(A.row, A.val, beg, end, A.G, A.gs, sub, kact ? kbase : 0, A.K, acc,
+                                                    gw, s2);
     } else {
         const float* __restrict__ r = A.r;
         const int64_t rs = A.rs;
@@ -55,9 +59,10 @@ __device__ __forceinline__ float reg_share(const ColArgs& A, int32_t qb, int32_t
 // Walks the shares of consecutive strata for one column block: start at stratum t, then
 // next() returns the share of the current stratum and moves on to the following one.
 struct ShareWalk {
-    const float* rho;
+    const float* rho;  // the table of shares, in global memory or staged in LDS
     int32_t p, P;
-    __device__ __forceinline__ ShareWalk(const ColArgs& A, int32_t qb, int32_t t) : rho(A.rho), p(0), P(A.P)
+    __device__ __forceinline__ ShareWalk(const ColArgs& A, const float* tab, int32_t qb, int32_t t)
+        : rho(tab), p(0), P(A.P)
     {
         if (rho != nullptr) {
             p = (qb - t) % P;
@@ -73,6 +78,16 @@ struct ShareWalk {
     }
 };
 
+// Kernels whose every thread gets here copy the table of shares to LDS when postponed steps
+// may have to be taken: the walk then costs an LDS read per stratum instead of a trip to L2.
+__device__ __forceinline__ const float* stage_shares(const ColArgs& A, float* sh)
+{
+    if (A.lazy_last == nullptr || A.rho == nullptr) return A.rho;  // uniform over the launch
+    for (int i = threadIdx.x; i < A.P; i += FM_BLOCK) sh[i] = A.rho[i];
+    __syncthreads();
+    return sh;
+}
+
 // The step of a column that has no entries in its cell: only the regulariser acts.  Written
 // with explicitly rounded operations, and finish_column with fused ones whose data part is
 // exactly zero for such a column, so that a postponed step gives the bits of an immediate one.
@@ -85,7 +100,7 @@ __device__ __forceinline__ float reg_only_step(float x, float rl, float eta)
 // step (optionally recording the change for the incremental refresh).
 template <int VEC, int L, bool UPDATE>
 __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int sub, int kbase, bool kact,
-                                              const float (&acc)[VEC], float gw, float s2)
+                                              const float (&acc)[VEC], float gw, float s2, const float* shares)
 {
     const int K = A.K;
     const int32_t qb = A.rho != nullptr ? fm_block_of(j, A.D, A.P) : 0;
@@ -98,7 +113,8 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
     if (kact) {
         float v[VEC], g[VEC];
         fm_load_vec<VEC>(A.V + j * K + kbase, v);
-        ShareWalk sw(A, qb, t0);
+        ShareWalk sw(A, shares, qb, t0);
+#pragma unroll 4
         for (int32_t t = t0; t < A.s; ++t) {
             const float rl = __fmul_rn(sw.next(), A.lambda_v);
 #pragma unroll
@@ -126,7 +142,8 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
     }
     if (sub == 0) {
         float wj = A.w[j];
-        ShareWalk sw(A, qb, t0);
+        ShareWalk sw(A, shares, qb, t0);
+#pragma unroll 4
         for (int32_t t = t0; t < A.s; ++t) wj = reg_only_step(wj, __fmul_rn(sw.next(), A.lambda_w), A.eta);
         const float g = __fmaf_rn(__fmul_rn(rho, A.lambda_w), wj, gw);
         if constexpr (UPDATE) {
@@ -141,7 +158,7 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
 }
 
 // Short non-empty columns (1..seg entries), taken from a list: one group per column.
-template <int VEC, int L, bool UPDATE, bool PACKED>
+template <int VEC, int L, bool UPDATE, int PACKED>
 __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
 {
     constexpr int R = FM_WAVE / L;
@@ -149,6 +166,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
     const int wave = threadIdx.x / FM_WAVE;
     const int sub = lane & (L - 1);
     const int grp = lane / L;
+    extern __shared__ float sh_rho[];  // A.P floats when postponed steps may be pending, else none
+    const float* shares = UPDATE ? stage_shares(A, sh_rho) : A.rho;
     const int64_t pos = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
     const bool valid = pos < A.nshort;
     int64_t j = 0, beg = 0, end = 0;
@@ -166,7 +185,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
     accumulate_entries<VEC, L, PACKED, true>(A, beg, end, sub, kbase, kact, acc, gw, s2);  // short columns: no reuse
     gw = fm_group_sum<L>(gw);
     s2 = fm_group_sum<L>(s2);
-    if (valid) finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, acc, gw, s2);
+    if (valid) finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, acc, gw, s2, shares);
 }
 
 // Columns with nothing stored (in this matrix or stratum) only feel the regulariser:
@@ -187,7 +206,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_empty(const ColArgs A)
     float acc[VEC];
 #pragma unroll
     for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
-    finish_column<VEC, LE, UPDATE>(A, j, sub, kbase, kbase < A.K, acc, 0.f, 0.f);
+    finish_column<VEC, LE, UPDATE>(A, j, sub, kbase, kbase < A.K, acc, 0.f, 0.f, A.rho);
 }
 
 // The postponed regulariser steps of every column, strata lazy_last[j] .. A.s-1 in order;
@@ -200,6 +219,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
     const int wave = threadIdx.x / FM_WAVE;
     const int sub = lane & (LE - 1);
     const int grp = lane / LE;
+    extern __shared__ float sh_rho[];  // A.P floats
+    const float* shares = stage_shares(A, sh_rho);
     const int64_t j = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
     if (j >= A.D) return;  // whole groups leave together
     const int32_t t0 = A.lazy_last[j];
@@ -209,7 +230,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
     if (kbase < A.K) {
         float v[VEC];
         fm_load_vec<VEC>(A.V + j * A.K + kbase, v);
-        ShareWalk sw(A, qb, t0);
+        ShareWalk sw(A, shares, qb, t0);
+#pragma unroll 4
         for (int32_t t = t0; t < A.s; ++t) {
             const float rl = __fmul_rn(sw.next(), A.lambda_v);
 #pragma unroll
@@ -219,7 +241,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
     }
     if (sub == 0) {
         float wj = A.w[j];
-        ShareWalk sw(A, qb, t0);
+        ShareWalk sw(A, shares, qb, t0);
+#pragma unroll 4
         for (int32_t t = t0; t < A.s; ++t) wj = reg_only_step(wj, __fmul_rn(sw.next(), A.lambda_w), A.eta);
         A.w[j] = wj;
     }
@@ -227,7 +250,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
 
 // One group per item of a long column: partial sums only.  With an order array,
 // workgroup b takes its items from list b % FM_XCDS (the XCD it runs on).
-template <int VEC, int L, bool PACKED>
+template <int VEC, int L, int PACKED>
 __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
 {
     constexpr int R = FM_WAVE / L;
@@ -455,7 +478,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_finish_wave(const ColArgs A)
         float accf[VEC];
 #pragma unroll
         for (int z = 0; z < VEC; ++z) accf[z] = (float)acc[z];
-        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)gw, (float)s2);
+        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)gw, (float)s2, A.rho);
     }
 }
 
@@ -500,7 +523,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_finish_block(const ColArgs A)
         float accf[VEC];
 #pragma unroll
         for (int z = 0; z < VEC; ++z) accf[z] = (float)tot[z];
-        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)tg, (float)ts);
+        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)tg, (float)ts, A.rho);
     }
 }
 
@@ -542,6 +565,12 @@ inline bool launch_tile(fm_matrix* m, const ColArgs& A, hipStream_t st)
     return false;
 }
 
+// dynamic LDS of the kernels that stage the table of shares (see stage_shares)
+static size_t share_table_bytes(const ColArgs& A)
+{
+    return (A.lazy_last != nullptr && A.rho != nullptr) ? (size_t)A.P * sizeof(float) : 0;
+}
+
 // k_cols_empty with LE = smallest power of two >= K/VEC lanes per column
 template <int VEC, int LE>
 int launch_empty_l(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
@@ -581,7 +610,7 @@ int launch_flush_l(fm_matrix* m, const ColArgs& A, hipStream_t st)
     const int64_t grid = (A.D + per - 1) / per;
     if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
     ProfScope ps(m, st, FMK_COLS);
-    hipLaunchKernelGGL((k_cols_flush<VEC, LE>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
+    hipLaunchKernelGGL((k_cols_flush<VEC, LE>), dim3((unsigned)grid), dim3(FM_BLOCK), share_table_bytes(A), st, A);
     FM_HIP(m, hipGetLastError());
     return FM_OK;
 }
@@ -603,7 +632,7 @@ int launch_flush(fm_matrix* m, const ColArgs& A, hipStream_t st)
     return fm_fail(m, FM_EINVAL, "unsupported K=%d", A.K);
 }
 
-template <int VEC, int L, bool PACKED>
+template <int VEC, int L, int PACKED>
 int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
 {
     constexpr int R = FM_WAVE / L;
@@ -626,7 +655,7 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     if (ntile_items > 0) {  // items of dense-ish columns, sorted by row tile
         ProfScope ps(m, s_tile, FMK_COLS_TILE);
         bool staged = false;
-        if constexpr (PACKED) staged = launch_tile(m, A, s_tile);
+        if constexpr (PACKED != FM_PLANAR) staged = launch_tile(m, A, s_tile);
         if (!staged) {  // same items through global memory
             ColArgs B = A;
             B.lin_mode = 1;
@@ -661,7 +690,8 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
         if (g1 > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
         if (g1 > 0) {
             if (update)
-                hipLaunchKernelGGL((k_cols<VEC, L, true, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK), 0, s_cols, A);
+                hipLaunchKernelGGL((k_cols<VEC, L, true, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK),
+                                   share_table_bytes(A), s_cols, A);
             else
                 hipLaunchKernelGGL((k_cols<VEC, L, false, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK), 0, s_cols, A);
             FM_HIP(m, hipGetLastError());
@@ -700,7 +730,7 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     return FM_OK;
 }
 
-template <int VEC, bool PACKED>
+template <int VEC, int PACKED>
 int launch_cols_v(fm_matrix* m, int lanes, const ColArgs& A, bool update, hipStream_t st)
 {
     switch (lanes) {
@@ -718,10 +748,11 @@ int launch_cols_v(fm_matrix* m, int lanes, const ColArgs& A, bool update, hipStr
 }  // namespace
 
 // lanes per column group: K/VEC latent lanes, plus one lane for the scalars of a packed row
-static bool cols_shape(int32_t K, bool packed, int* vec, int* lanes)
+// when the row [G | r] lies inside one 128-byte line
+static bool cols_shape(int32_t K, int packed, int* vec, int* lanes)
 {
     if (!fm_shape_for_K(K, vec, lanes)) return false;
-    if (packed) {
+    if (packed == FM_PACKED_LANE) {
         int need = K / 4 + 1, l = 1;
         while (l < need) l <<= 1;
         *lanes = l;
@@ -732,12 +763,13 @@ static bool cols_shape(int32_t K, bool packed, int* vec, int* lanes)
 int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
 {
     int vec, lanes;
-    if (!cols_shape(A.K, A.packed != 0, &vec, &lanes)) return fm_fail(m, FM_EINVAL, "unsupported K=%d", A.K);
-    if (A.packed) return launch_cols_v<4, true>(m, lanes, A, update, st);
+    if (!cols_shape(A.K, A.packed, &vec, &lanes)) return fm_fail(m, FM_EINVAL, "unsupported K=%d", A.K);
+    if (A.packed == FM_PACKED_LANE) return launch_cols_v<4, FM_PACKED_LANE>(m, lanes, A, update, st);
+    if (A.packed == FM_PACKED_LOAD) return launch_cols_v<4, FM_PACKED_LOAD>(m, lanes, A, update, st);
     switch (vec) {
-        case 4: return launch_cols_v<4, false>(m, lanes, A, update, st);
-        case 2: return launch_cols_v<2, false>(m, lanes, A, update, st);
-        default: return launch_cols_v<1, false>(m, lanes, A, update, st);
+        case 4: return launch_cols_v<4, FM_PLANAR>(m, lanes, A, update, st);
+        case 2: return launch_cols_v<2, FM_PLANAR>(m, lanes, A, update, st);
+        default: return launch_cols_v<1, FM_PLANAR>(m, lanes, A, update, st);
     }
 }
 

@@ -39,6 +39,10 @@ struct FmAux {
     int64_t gs, ss;
 };
 bool fm_aux_packed(int32_t K);
+// How the column kernels read the aggregate rows (ColArgs::packed).
+enum { FM_PLANAR = 0, FM_PACKED_LANE = 1, FM_PACKED_LOAD = 2 };
+// FM_PACKED_LANE when [G | r] of a packed row lies inside one 128-byte line, else FM_PACKED_LOAD
+int fm_cols_packed_mode(int32_t K);
 int64_t fm_aux_floats(int64_t N, int32_t K);
 struct fm_matrix;
 FmAux fm_aux_layout(const fm_matrix* m, int32_t K);
@@ -213,7 +217,7 @@ struct ColArgs {
     const float* r;
     const float* G;
     int64_t gs, rs;  // row strides of G and r in floats
-    int32_t packed;  // G rows are packed aggregate rows [G | r | a | q | pad] (r is read from the row)
+    int32_t packed;  // FM_PLANAR, or G rows are packed aggregate rows [G | r | a | q | pad]: FM_PACKED_*
     int32_t seg;     // columns longer than this are split into items
     float* w;        // updated in place when update
     float* V;
