@@ -615,6 +615,7 @@ static int stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const fl
         R.val = m->s_val;
         if (m->s_touched != nullptr) {  // only the rows that have an entry in this stratum
             R.rows = m->s_touched + m->h_touch_off[s];
+            R.rowptr = m->s_touched_beg + m->h_touch_off[s];
             R.N = m->h_touch_off[s + 1] - m->h_touch_off[s];
         } else {
             R.N = 0;

@@ -308,7 +308,8 @@ __global__ __launch_bounds__(LI_T) void k_long_fill(const int64_t* __restrict__ 
 // empty columns only feel the regulariser and are handled by an elementwise kernel.
 __global__ __launch_bounds__(LI_T) void k_short_list(const int64_t* __restrict__ ptr, int64_t ncols, int64_t D, int seg,
                                                      int pass, int64_t* __restrict__ tile_cnt,
-                                                     int32_t* __restrict__ short_col, int64_t* __restrict__ short_vcol)
+                                                     int32_t* __restrict__ short_col, int64_t* __restrict__ short_vcol,
+                                                     int64_t* __restrict__ short_beg)
 {
     __shared__ int64_t sh[2][SCAN_T];
     const int64_t base = (int64_t)blockIdx.x * LI_TILE + (int64_t)threadIdx.x * LI_E;
@@ -334,6 +335,7 @@ __global__ __launch_bounds__(LI_T) void k_short_list(const int64_t* __restrict__
         if (len > 0 && len <= seg) {
             short_col[pos] = (int32_t)(c % D);
             short_vcol[pos] = c;
+            if (short_beg != nullptr) short_beg[pos] = ptr[c];
             ++pos;
         }
     }
@@ -558,7 +560,7 @@ int fm_sort_by_key_u32(fm_matrix* m, uint32_t* keys, uint32_t* idx, uint32_t* ke
 // nstrata > 1: h_off[s] is where stratum s starts in the list.
 static int build_nonempty_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
                                int seg, int32_t** list_out, int64_t* count_out, std::vector<int64_t>* h_off,
-                               hipStream_t st)
+                               hipStream_t st, int64_t** beg_out = nullptr)
 {
     *count_out = 0;
     h_off->assign(nstrata + 1, 0);
@@ -568,7 +570,7 @@ static int build_nonempty_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_t
     FM_TRY(fm_dev_alloc(m, (void**)&tc, (size_t)(ntiles + 1) * sizeof(int64_t)));
     FM_HIP(m, hipMemsetAsync(tc, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
     hipLaunchKernelGGL(k_short_list, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, D, seg, 0, tc,
-                       (int32_t*)nullptr, (int64_t*)nullptr);
+                       (int32_t*)nullptr, (int64_t*)nullptr, (int64_t*)nullptr);
     FM_HIP(m, hipGetLastError());
     FM_TRY(fm_scan_exclusive_i64(m, tc, ntiles + 1, st));
     int64_t n = 0;
@@ -579,8 +581,14 @@ static int build_nonempty_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_t
         FM_TRY(fm_dev_alloc(m, (void**)list_out, (size_t)n * sizeof(int32_t)));
         FM_TRY(fm_dev_alloc(m, (void**)&vcol, (size_t)n * sizeof(int64_t)));
         FM_TRY(fm_dev_alloc(m, (void**)&d_off, (size_t)(nstrata + 1) * sizeof(int64_t)));
+        int64_t* beg = nullptr;
+        if (beg_out != nullptr) {  // start of every listed column; one more element: the end of all entries
+            FM_TRY(fm_dev_alloc(m, (void**)beg_out, (size_t)(n + 1) * sizeof(int64_t)));
+            beg = *beg_out;
+            FM_HIP(m, hipMemcpyAsync(beg + n, ptr + ncols_total, sizeof(int64_t), hipMemcpyDeviceToDevice, st));
+        }
         hipLaunchKernelGGL(k_short_list, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, D, seg, 1, tc,
-                           *list_out, vcol);
+                           *list_out, vcol, beg);
         FM_HIP(m, hipGetLastError());
         hipLaunchKernelGGL(k_stratum_offsets, dim3(blocks_for(nstrata + 1, 256)), dim3(256), 0, st, (const int64_t*)vcol,
                            n, D, nstrata, d_off);
@@ -973,8 +981,10 @@ extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
     fm_dev_free(m, d_cb);
     FM_TRY(fm_build_long_index(m, m->s_colptr, (int64_t)P * m->D, m->D, P, &m->lstrat, st));
     // rows that have an entry in stratum s: the refresh of that stratum visits only these
+    // (every entry of the per-stratum matrices belongs to a listed row, so a row's entries end where
+    // those of the next listed row begin)
     FM_TRY(build_nonempty_list(m, m->s_rowptr, (int64_t)P * m->N, m->N, P, 0x7fffffff, &m->s_touched, &m->ntouched,
-                               &m->h_touch_off, st));
+                               &m->h_touch_off, st, &m->s_touched_beg));
     FM_HIP(m, hipStreamSynchronize(st));
     fm_drop_workspace(m);
     return FM_OK;

@@ -156,13 +156,12 @@ __device__ __forceinline__ void fm_gather_slots(const IX& ix, const MU& mu, cons
 // Full chunks of L*CH entries run without masking; the tail runs in L-entry slots whose
 // missing entries repeat the last entry with value 0.  `kb` must be a valid offset for
 // every lane (idle lanes pass 0 and discard acc).
-template <int VEC, int L, bool SQ, class Own>
+template <int VEC, int L, bool SQ, int CH = FmChunk<L>::CH, class Own>
 __device__ __forceinline__ void fm_gather_accumulate(const int32_t* __restrict__ idx, const float* __restrict__ val,
                                                      int64_t beg, int64_t end, const float* __restrict__ src,
                                                      int64_t stride, int sub, int kb, float (&acc)[VEC], float& sq,
                                                      Own&& own)
 {
-    constexpr int CH = FmChunk<L>::CH;
     int64_t e = beg;
     for (; e + L * CH <= end; e += L * CH) {
         int ix[CH];

@@ -119,6 +119,7 @@ struct fm_matrix {
     float* s_cval = nullptr;
     LongIndex lstrat;
     int32_t* s_touched = nullptr;  // per stratum: the rows with at least one entry there, ascending
+    int64_t* s_touched_beg = nullptr;  // [ntouched+1] where the entries of each listed row begin
     int64_t ntouched = 0;
     std::vector<int64_t> h_touch_off;  // [P+1] offsets into s_touched
     // workspace, sized for wsK
@@ -200,7 +201,8 @@ struct RowArgs {
     int64_t gs;         // floats between consecutive rows of G
     int64_t ss;         // floats between consecutive rows of r, a, q (1, or the aggregate row stride)
     float* row_part;    // nullable: [2*gridDim] loss and sum r per block
-    const int32_t* rows;  // nullable: the launch covers rows[0..N) instead of rows 0..N-1
+    const int32_t* rows;  // nullable: the launch covers rows[0..N) instead of rows 0..N-1, and
+                          // rowptr[k], rowptr[k+1] bound the entries of rows[k]
     int32_t loss;
     float s;
 };

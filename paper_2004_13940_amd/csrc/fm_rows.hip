@@ -47,13 +47,17 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
     const int64_t slot = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
     const bool valid = slot < A.N;
     int64_t row = slot;
-    if constexpr (MODE == MODE_REFRESH) {
-        if (A.rows != nullptr && valid) row = A.rows[slot];
-    }
     int64_t beg = 0, end = 0;
     if (valid) {
-        beg = A.rowptr[row];
-        end = A.rowptr[row + 1];
+        int64_t at = slot;
+        if constexpr (MODE == MODE_REFRESH) {
+            if (A.rows != nullptr)
+                row = A.rows[slot];  // pointers are indexed by list position
+            else
+                at = row;
+        }
+        beg = A.rowptr[at];
+        end = A.rowptr[at + 1];
     }
     const int K = A.K;
     const int kbase = sub * VEC;
@@ -86,7 +90,9 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
         }
         const float2* __restrict__ dwn = A.dwn;
         float unused = 0.f;
-        fm_gather_accumulate<VEC, L, false>(A.col, A.val, beg, end, A.V, K, sub, kb, acc, unused,
+        // a row has few entries inside one stratum: one slot of L entries at a time keeps the
+        // register count low, so that more rows are in flight
+        fm_gather_accumulate<VEC, L, false, 1>(A.col, A.val, beg, end, A.V, K, sub, kb, acc, unused,
                                             [&](int c, float x) {
                                                 const float2 d = dwn[c];
                                                 a_acc += d.x * x;
