@@ -56,80 +56,116 @@ __device__ __forceinline__ float reg_share(const ColArgs& A, int32_t qb, int32_t
     return A.rho[p];
 }
 
-// Walks the shares of consecutive strata for one column block: start at stratum t, then
-// next() returns the share of the current stratum and moves on to the following one.
-struct ShareWalk {
-    const float* rho;  // the table of shares, in global memory or staged in LDS
-    int32_t p, P;
-    __device__ __forceinline__ ShareWalk(const ColArgs& A, const float* tab, int32_t qb, int32_t t)
-        : rho(tab), p(0), P(A.P)
-    {
-        if (rho != nullptr) {
-            p = (qb - t) % P;
-            if (p < 0) p += P;
-        }
-    }
-    __device__ __forceinline__ float next()
-    {
-        if (rho == nullptr) return 1.f;
-        const float x = rho[p];
-        p = p == 0 ? P - 1 : p - 1;
-        return x;
-    }
-};
-
-// Kernels whose every thread gets here copy the table of shares to LDS when postponed steps
-// may have to be taken: the walk then costs an LDS read per stratum instead of a trip to L2.
-__device__ __forceinline__ const float* stage_shares(const ColArgs& A, float* sh)
+// A column with no entries in its cell only feels the regulariser: x <- x - eta rho lambda x.
+// That step is taken as one rounded multiplication by c = 1 - eta (rho lambda), so that a run
+// of postponed steps costs one multiplication each and gives the bits of immediate ones.
+__device__ __forceinline__ float step_factor(float rho, float lambda, float eta)
 {
-    if (A.lazy_last == nullptr || A.rho == nullptr) return A.rho;  // uniform over the launch
-    for (int i = threadIdx.x; i < A.P; i += FM_BLOCK) sh[i] = A.rho[i];
-    __syncthreads();
-    return sh;
+    return __fsub_rn(1.f, __fmul_rn(eta, __fmul_rn(rho, lambda)));
 }
 
-// The step of a column that has no entries in its cell: only the regulariser acts.  Written
-// with explicitly rounded operations, and finish_column with fused ones whose data part is
-// exactly zero for such a column, so that a postponed step gives the bits of an immediate one.
-__device__ __forceinline__ float reg_only_step(float x, float rl, float eta)
+// Factors of the regulariser-only step per row block: from a table staged in LDS ([P] for V,
+// then [P] for w), or computed from the table of shares.
+struct StepFactors {
+    const float* tab;
+    const float* rho;
+    float lv, lw, eta;
+    int32_t P;
+    __device__ __forceinline__ float v(int32_t p) const
+    {
+        return tab != nullptr ? tab[p] : step_factor(rho != nullptr ? rho[p] : 1.f, lv, eta);
+    }
+    __device__ __forceinline__ float w(int32_t p) const
+    {
+        return tab != nullptr ? tab[P + p] : step_factor(rho != nullptr ? rho[p] : 1.f, lw, eta);
+    }
+    // row block that column block qb meets in stratum t, and the one it meets next
+    __device__ __forceinline__ int32_t block_at(int32_t qb, int32_t t) const
+    {
+        if (P <= 0) return 0;
+        int32_t p = (qb - t) % P;
+        return p < 0 ? p + P : p;
+    }
+    __device__ __forceinline__ int32_t next(int32_t p) const { return p == 0 ? (P > 0 ? P - 1 : 0) : p - 1; }
+};
+
+__device__ __forceinline__ StepFactors plain_factors(const ColArgs& A)
 {
-    return __fadd_rn(x, __fmul_rn(-eta, __fmul_rn(rl, x)));
+    return StepFactors{nullptr, A.rho, A.lambda_v, A.lambda_w, A.eta, A.rho != nullptr ? A.P : 0};
+}
+
+// Kernels whose every thread gets here fill the table in LDS (2 P floats) when postponed steps
+// may have to be taken: a walk over strata then costs an LDS read per stratum.
+__device__ __forceinline__ StepFactors stage_factors(const ColArgs& A, float* sh)
+{
+    StepFactors F = plain_factors(A);
+    if (A.lazy_last == nullptr || A.rho == nullptr) return F;  // uniform over the launch
+    for (int i = threadIdx.x; i < A.P; i += FM_BLOCK) {
+        const float rho = A.rho[i];
+        sh[i] = step_factor(rho, A.lambda_v, A.eta);
+        sh[A.P + i] = step_factor(rho, A.lambda_w, A.eta);
+    }
+    __syncthreads();
+    F.tab = sh;
+    return F;
+}
+
+// What the step of column j needs from memory besides the data sums; loaded early by the
+// kernels that can, so that it overlaps the gathers.
+template <int VEC>
+struct ColState {
+    float v[VEC];
+    float w;
+    int32_t t0;  // first stratum whose step the column has not taken yet
+};
+
+template <int VEC, bool UPDATE>
+__device__ __forceinline__ ColState<VEC> load_column(const ColArgs& A, int64_t j, int sub, int kbase, bool kact)
+{
+    ColState<VEC> c;
+#pragma unroll
+    for (int z = 0; z < VEC; ++z) c.v[z] = 0.f;
+    c.w = 0.f;
+    c.t0 = A.s;
+    if (kact) fm_load_vec<VEC>(A.V + j * A.K + kbase, c.v);
+    if (sub == 0) c.w = A.w[j];
+    if constexpr (UPDATE) {
+        if (A.lazy_last != nullptr) c.t0 = A.lazy_last[j];
+    }
+    return c;
 }
 
 // Turn the data sums of column j into the gradient, and either store it or take the
 // step (optionally recording the change for the incremental refresh).
 template <int VEC, int L, bool UPDATE>
 __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int sub, int kbase, bool kact,
-                                              const float (&acc)[VEC], float gw, float s2, const float* shares)
+                                              const float (&acc)[VEC], float gw, float s2, const StepFactors& F,
+                                              ColState<VEC> c)
 {
     const int K = A.K;
     const int32_t qb = A.rho != nullptr ? fm_block_of(j, A.D, A.P) : 0;
     const float rho = reg_share(A, qb, A.s);
-    int32_t t0 = A.s;  // first stratum whose step this column has not taken yet
-    if constexpr (UPDATE) {
-        if (A.lazy_last != nullptr) t0 = A.lazy_last[j];
-    }
     float dn = 0.f;
     if (kact) {
-        float v[VEC], g[VEC];
-        fm_load_vec<VEC>(A.V + j * K + kbase, v);
-        ShareWalk sw(A, shares, qb, t0);
+        float g[VEC];
+        int32_t p = F.block_at(qb, c.t0);
 #pragma unroll 4
-        for (int32_t t = t0; t < A.s; ++t) {
-            const float rl = __fmul_rn(sw.next(), A.lambda_v);
+        for (int32_t t = c.t0; t < A.s; ++t) {  // postponed regulariser-only steps
+            const float f = F.v(p);
+            p = F.next(p);
 #pragma unroll
-            for (int z = 0; z < VEC; ++z) v[z] = reg_only_step(v[z], rl, A.eta);
+            for (int z = 0; z < VEC; ++z) c.v[z] = __fmul_rn(c.v[z], f);
         }
         const float rl = __fmul_rn(rho, A.lambda_v);
 #pragma unroll
-        for (int z = 0; z < VEC; ++z) g[z] = __fmaf_rn(rl, v[z], __fmaf_rn(-s2, v[z], acc[z]));
+        for (int z = 0; z < VEC; ++z) g[z] = __fmaf_rn(rl, c.v[z], __fmaf_rn(-s2, c.v[z], acc[z]));
         if constexpr (UPDATE) {
             float d[VEC], vn[VEC];
 #pragma unroll
             for (int z = 0; z < VEC; ++z) {
                 d[z] = __fmul_rn(-A.eta, g[z]);
-                vn[z] = __fadd_rn(v[z], d[z]);
-                dn += d[z] * (2.f * v[z] + d[z]);  // |v+d|^2 - |v|^2 without cancellation
+                vn[z] = __fadd_rn(c.v[z], d[z]);
+                dn += d[z] * (2.f * c.v[z] + d[z]);  // |v+d|^2 - |v|^2 without cancellation
             }
             fm_store_vec<VEC>(A.V + j * K + kbase, vn);
             if (A.dV != nullptr) fm_store_vec<VEC>(A.dV + j * K + kbase, d);
@@ -141,10 +177,13 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
         if (A.dwn != nullptr) dn = fm_group_sum<L>(dn);
     }
     if (sub == 0) {
-        float wj = A.w[j];
-        ShareWalk sw(A, shares, qb, t0);
+        float wj = c.w;
+        int32_t p = F.block_at(qb, c.t0);
 #pragma unroll 4
-        for (int32_t t = t0; t < A.s; ++t) wj = reg_only_step(wj, __fmul_rn(sw.next(), A.lambda_w), A.eta);
+        for (int32_t t = c.t0; t < A.s; ++t) {
+            wj = __fmul_rn(wj, F.w(p));
+            p = F.next(p);
+        }
         const float g = __fmaf_rn(__fmul_rn(rho, A.lambda_w), wj, gw);
         if constexpr (UPDATE) {
             const float d = __fmul_rn(-A.eta, g);
@@ -166,8 +205,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
     const int wave = threadIdx.x / FM_WAVE;
     const int sub = lane & (L - 1);
     const int grp = lane / L;
-    extern __shared__ float sh_rho[];  // A.P floats when postponed steps may be pending, else none
-    const float* shares = UPDATE ? stage_shares(A, sh_rho) : A.rho;
+    extern __shared__ float sh_fac[];  // 2 A.P floats when postponed steps may be pending, else none
+    const StepFactors F = UPDATE ? stage_factors(A, sh_fac) : plain_factors(A);
     const int64_t pos = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
     const bool valid = pos < A.nshort;
     int64_t j = 0, beg = 0, end = 0;
@@ -178,6 +217,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
     }
     const int kbase = sub * VEC;
     const bool kact = kbase < A.K;
+    // the column's own values do not depend on the gathers: fetch them first
+    const ColState<VEC> c = load_column<VEC, UPDATE>(A, j, sub, kbase, kact && valid);
     float acc[VEC];
 #pragma unroll
     for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
@@ -185,12 +226,13 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
     accumulate_entries<VEC, L, PACKED, true>(A, beg, end, sub, kbase, kact, acc, gw, s2);  // short columns: no reuse
     gw = fm_group_sum<L>(gw);
     s2 = fm_group_sum<L>(s2);
-    if (valid) finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, acc, gw, s2, shares);
+    if (valid) finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, acc, gw, s2, F, c);
 }
 
-// Columns with nothing stored (in this matrix or stratum) only feel the regulariser:
-// finish_column with zero data sums, one group of LE = K/VEC lanes per column over all D
-// columns, consecutive groups on consecutive columns so that V is streamed.
+// Columns with nothing stored (in this matrix or stratum) only feel the regulariser; one group
+// of LE = K/VEC lanes per column over all D columns, consecutive groups on consecutive columns
+// so that V is streamed.  The gradient is finish_column with zero data sums; the step is the
+// multiplication by the step factor.
 template <int VEC, int LE, bool UPDATE>
 __global__ __launch_bounds__(FM_BLOCK) void k_cols_empty(const ColArgs A)
 {
@@ -203,10 +245,38 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_empty(const ColArgs A)
     if (j >= A.D) return;              // whole groups leave together
     if (A.ptr[j + 1] != A.ptr[j]) return;
     const int kbase = sub * VEC;
-    float acc[VEC];
+    const bool kact = kbase < A.K;
+    if constexpr (!UPDATE) {
+        float acc[VEC];
 #pragma unroll
-    for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
-    finish_column<VEC, LE, UPDATE>(A, j, sub, kbase, kbase < A.K, acc, 0.f, 0.f, A.rho);
+        for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
+        finish_column<VEC, LE, false>(A, j, sub, kbase, kact, acc, 0.f, 0.f, plain_factors(A),
+                                      load_column<VEC, false>(A, j, sub, kbase, kact));
+    } else {
+        const int32_t qb = A.rho != nullptr ? fm_block_of(j, A.D, A.P) : 0;
+        const float rho = reg_share(A, qb, A.s);
+        float dn = 0.f;
+        if (kact) {
+            const float f = step_factor(rho, A.lambda_v, A.eta);
+            float v[VEC], vn[VEC], d[VEC];
+            fm_load_vec<VEC>(A.V + j * A.K + kbase, v);
+#pragma unroll
+            for (int z = 0; z < VEC; ++z) {
+                vn[z] = __fmul_rn(v[z], f);
+                d[z] = vn[z] - v[z];
+                dn += d[z] * (2.f * v[z] + d[z]);
+            }
+            fm_store_vec<VEC>(A.V + j * A.K + kbase, vn);
+            if (A.dV != nullptr) fm_store_vec<VEC>(A.dV + j * A.K + kbase, d);
+        }
+        if (A.dwn != nullptr) dn = fm_group_sum<LE>(dn);
+        if (sub == 0) {
+            const float wj = A.w[j];
+            const float wn = __fmul_rn(wj, step_factor(rho, A.lambda_w, A.eta));
+            A.w[j] = wn;
+            if (A.dwn != nullptr) A.dwn[j] = make_float2(wn - wj, dn);
+        }
+    }
 }
 
 // The postponed regulariser steps of every column, strata lazy_last[j] .. A.s-1 in order;
@@ -219,8 +289,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
     const int wave = threadIdx.x / FM_WAVE;
     const int sub = lane & (LE - 1);
     const int grp = lane / LE;
-    extern __shared__ float sh_rho[];  // A.P floats
-    const float* shares = stage_shares(A, sh_rho);
+    extern __shared__ float sh_fac[];  // 2 A.P floats
+    const StepFactors F = stage_factors(A, sh_fac);
     const int64_t j = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
     if (j >= A.D) return;  // whole groups leave together
     const int32_t t0 = A.lazy_last[j];
@@ -230,20 +300,24 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
     if (kbase < A.K) {
         float v[VEC];
         fm_load_vec<VEC>(A.V + j * A.K + kbase, v);
-        ShareWalk sw(A, shares, qb, t0);
+        int32_t p = F.block_at(qb, t0);
 #pragma unroll 4
         for (int32_t t = t0; t < A.s; ++t) {
-            const float rl = __fmul_rn(sw.next(), A.lambda_v);
+            const float f = F.v(p);
+            p = F.next(p);
 #pragma unroll
-            for (int z = 0; z < VEC; ++z) v[z] = reg_only_step(v[z], rl, A.eta);
+            for (int z = 0; z < VEC; ++z) v[z] = __fmul_rn(v[z], f);
         }
         fm_store_vec<VEC>(A.V + j * A.K + kbase, v);
     }
     if (sub == 0) {
         float wj = A.w[j];
-        ShareWalk sw(A, shares, qb, t0);
+        int32_t p = F.block_at(qb, t0);
 #pragma unroll 4
-        for (int32_t t = t0; t < A.s; ++t) wj = reg_only_step(wj, __fmul_rn(sw.next(), A.lambda_w), A.eta);
+        for (int32_t t = t0; t < A.s; ++t) {
+            wj = __fmul_rn(wj, F.w(p));
+            p = F.next(p);
+        }
         A.w[j] = wj;
     }
 }
@@ -478,7 +552,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_finish_wave(const ColArgs A)
         float accf[VEC];
 #pragma unroll
         for (int z = 0; z < VEC; ++z) accf[z] = (float)acc[z];
-        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)gw, (float)s2, A.rho);
+        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)gw, (float)s2, plain_factors(A),
+                                      load_column<VEC, UPDATE>(A, j, sub, kbase, kact));
     }
 }
 
@@ -523,7 +598,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_finish_block(const ColArgs A)
         float accf[VEC];
 #pragma unroll
         for (int z = 0; z < VEC; ++z) accf[z] = (float)tot[z];
-        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)tg, (float)ts, A.rho);
+        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)tg, (float)ts, plain_factors(A),
+                                      load_column<VEC, UPDATE>(A, j, sub, kbase, kact));
     }
 }
 
@@ -568,7 +644,7 @@ inline bool launch_tile(fm_matrix* m, const ColArgs& A, hipStream_t st)
 // dynamic LDS of the kernels that stage the table of shares (see stage_shares)
 static size_t share_table_bytes(const ColArgs& A)
 {
-    return (A.lazy_last != nullptr && A.rho != nullptr) ? (size_t)A.P * sizeof(float) : 0;
+    return (A.lazy_last != nullptr && A.rho != nullptr) ? 2 * (size_t)A.P * sizeof(float) : 0;
 }
 
 // k_cols_empty with LE = smallest power of two >= K/VEC lanes per column
