@@ -604,17 +604,19 @@ static int build_nonempty_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_t
     return FM_OK;
 }
 
-static int build_short_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
+static int build_short_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata, int seg,
                             LongIndex* out, hipStream_t st)
 {
-    return build_nonempty_list(m, ptr, ncols_total, D, nstrata, fm_tune().seg, &out->short_col, &out->nshort,
+    return build_nonempty_list(m, ptr, ncols_total, D, nstrata, seg, &out->short_col, &out->nshort,
                                &out->h_short_off, st);
 }
 
 int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
                         LongIndex* out, hipStream_t st)
 {
-    FM_TRY(build_short_list(m, ptr, ncols_total, D, nstrata, out, st));
+    // the launches of one stratum are small: shorter items give them more groups to spread over
+    const int seg = fm_tune().seg_strat;
+    FM_TRY(build_short_list(m, ptr, ncols_total, D, nstrata, seg, out, st));
     out->nlong = out->nitems = 0;
     out->h_long_off.assign(nstrata + 1, 0);
     out->h_item_off.assign(nstrata + 1, 0);
@@ -625,7 +627,6 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
     FM_TRY(fm_dev_alloc(m, (void**)&ti, (size_t)(ntiles + 1) * sizeof(int64_t)));
     FM_HIP(m, hipMemsetAsync(tl, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
     FM_HIP(m, hipMemsetAsync(ti, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
-    const int seg = fm_tune().seg;
     hipLaunchKernelGGL(k_long_count, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, seg, tl, ti);
     FM_HIP(m, hipGetLastError());
     FM_TRY(fm_scan_exclusive_i64(m, tl, ntiles + 1, st));
@@ -683,7 +684,12 @@ static FmTune& tune_mut()
     static FmTune t = {env_int("FM_SEG", 256, 16, 1 << 20), env_int("FM_PANEL", 32768, 64, 1 << 30),
                        env_int("FM_HEAVY_PER_PANEL", 16, 1, 1 << 20), env_int("FM_VLONG", 512, 1, 1 << 30),
                        env_int("FM_MIN_PANELS", 8 * FM_XCDS, 1, 1 << 30), env_int("FM_TILE", 512, 64, 1 << 20),
-                       env_int("FM_TILE_MIN", 8, 0, 1 << 20), env_int("FM_TILE_SEG", 256, 16, 1 << 20)};
+                       env_int("FM_TILE_MIN", 8, 0, 1 << 20), env_int("FM_TILE_SEG", 256, 16, 1 << 20), 0};
+    static const bool once = [] {
+        t.seg_strat = env_int("FM_SEG_STRAT", t.seg < 128 ? t.seg : 128, 16, 1 << 20);
+        return true;
+    }();
+    (void)once;
     return t;
 }
 
@@ -701,7 +707,7 @@ extern "C" int fm_set_tile_tuning(int32_t tile_rows, int32_t min_per_tile, int32
 extern "C" int fm_set_tuning(int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t vlong, int32_t min_panels)
 {
     FmTune& t = tune_mut();
-    if (seg > 0) t.seg = seg < 16 ? 16 : seg;
+    if (seg > 0) t.seg = t.seg_strat = seg < 16 ? 16 : seg;
     if (panel > 0) t.panel = panel < 64 ? 64 : panel;
     if (heavy_per_panel > 0) t.heavy_per_panel = heavy_per_panel;
     if (vlong > 0) t.vlong = vlong;
@@ -713,7 +719,7 @@ int fm_build_full_index(fm_matrix* m, hipStream_t st)
 {
     LongIndex* out = &m->lfull;
     const FmTune& T = fm_tune();
-    FM_TRY(build_short_list(m, m->colptr, m->D, m->D, 1, out, st));
+    FM_TRY(build_short_list(m, m->colptr, m->D, m->D, 1, fm_tune().seg, out, st));
     out->nlong = out->nitems = 0;
     out->h_long_off.assign(2, 0);
     out->h_item_off.assign(2, 0);

@@ -18,7 +18,7 @@ constexpr int FM_MAXP = 4096;
 constexpr int FM_XCDS = 8;                // L2 domains; workgroup b runs on XCD b % 8
 
 // Tunables of the column-side work decomposition (read once from the environment:
-// FM_SEG, FM_PANEL, FM_HEAVY_PER_PANEL, FM_VLONG, FM_MIN_PANELS; or fm_set_tuning).
+// FM_SEG, FM_SEG_STRAT, FM_PANEL, FM_HEAVY_PER_PANEL, FM_VLONG, FM_MIN_PANELS; or fm_set_tuning).
 struct FmTune {
     int seg;              // entries per work item of a long column
     int panel;            // rows per panel of the L2-blocked traversal of heavy columns
@@ -28,6 +28,7 @@ struct FmTune {
     int tile;             // rows per LDS tile of the kernel for dense-ish columns
     int tile_min;         // a column is dense-ish if it averages this many entries per tile (0: none)
     int tile_seg;         // entries per item inside a tile
+    int seg_strat;        // `seg` of the per-stratum matrices (FM_SEG_STRAT; fm_set_tuning sets both)
 };
 const FmTune& fm_tune();
 
