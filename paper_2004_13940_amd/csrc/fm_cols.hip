@@ -20,19 +20,19 @@ namespace {
 
 // Accumulate one run of entries [beg,end) of a column into acc/gw/s2 (per-lane
 // partials for gw, s2; complete sums for acc's latent slice).
-template <int VEC, int L, int PACKED, bool NT>
+template <int VEC, int L, int PACKED, bool NT, bool LEAN = false>
 __device__ __forceinline__ void accumulate_entries(const ColArgs& A, int64_t beg, int64_t end, int sub, int kbase,
                                                    bool kact, float (&acc)[VEC], float& gw, float& s2)
 {
     if constexpr (PACKED == FM_PACKED_LANE) {
         // every lane reads inside the row: lanes past the scalars re-read its last VEC floats
         const int last = (int)A.gs - VEC;
-        fm_col_accumulate_packed<VEC, L, NT, true>(A.row, A.val, beg, end, A.G, A.gs, sub, kbase < last ? kbase : last,
-                                                   A.K, acc, gw, s2);
+        fm_col_accumulate_packed<VEC, L, NT, true, LEAN ? 1 : FmChunk<L>::CH>(
+            A.row, A.val, beg, end, A.G, A.gs, sub, kbase < last ? kbase : last, A.K, acc, gw, s2);
     } else if constexpr (PACKED == FM_PACKED_LOAD) {
         // idle lanes of a group wider than K/VEC read a valid slice and discard it
-        fm_col_accumulate_packed<VEC, L, NT, false>(A.row, A.val, beg, end, A.G, A.gs, sub, kact ? kbase : 0, A.K, acc,
-                                                    gw, s2);
+        fm_col_accumulate_packed<VEC, L, NT, false, LEAN ? 1 : FmChunk<L>::CH>(
+            A.row, A.val, beg, end, A.G, A.gs, sub, kact ? kbase : 0, A.K, acc, gw, s2);
     } else {
         const float* __restrict__ r = A.r;
         const int64_t rs = A.rs;
@@ -223,7 +223,9 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
 #pragma unroll
     for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
     float gw = 0.f, s2 = 0.f;
-    accumulate_entries<VEC, L, PACKED, true>(A, beg, end, sub, kbase, kact, acc, gw, s2);  // short columns: no reuse
+    // short columns: no reuse of the gathered rows.  Wide groups (few columns per wavefront) take
+    // the lean loop: fewer registers, so more wavefronts and more columns in flight.
+    accumulate_entries<VEC, L, PACKED, true, (L >= 16)>(A, beg, end, sub, kbase, kact, acc, gw, s2);
     gw = fm_group_sum<L>(gw);
     s2 = fm_group_sum<L>(s2);
     if (valid) finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, acc, gw, s2, F, c);

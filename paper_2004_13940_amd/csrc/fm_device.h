@@ -234,12 +234,12 @@ __device__ __forceinline__ void fm_load_row_packed(const float* __restrict__ row
     }
 }
 
-template <int VEC, int L, bool NT, bool SL, int S, class IX, class XV>
+template <int VEC, int L, bool NT, bool SL, int S, int MAXB = 16, class IX, class XV>
 __device__ __forceinline__ void fm_gather_slots_packed(const IX& ix, const XV& xv, const float* __restrict__ src,
                                                        int64_t stride, int kb, int K, bool sum_lane,
                                                        float (&acc)[VEC], float& gw, float& s2)
 {
-    constexpr int B = S < 16 ? S : 16;
+    constexpr int B = S < MAXB ? S : MAXB;
     fm_static_for<0, S / B>([&](auto bc) {
         constexpr int B0 = decltype(bc)::value * B;
         float g[B][VEC];
@@ -269,16 +269,17 @@ __device__ __forceinline__ void fm_gather_slots_packed(const IX& ix, const XV& x
 
 // kb: for SL the caller clamps it so that lanes past the scalars re-read the row's last VEC
 // floats; otherwise idle lanes pass 0.  Both discard their acc.
-template <int VEC, int L, bool NT, bool SL>
+template <int VEC, int L, bool NT, bool SL, int CH = FmChunk<L>::CH>
 __device__ __forceinline__ void fm_col_accumulate_packed(const int32_t* __restrict__ idx, const float* __restrict__ val,
                                                          int64_t beg, int64_t end, const float* __restrict__ src,
                                                          int64_t stride, int sub, int kb, int K, float (&acc)[VEC],
                                                          float& gw, float& s2)
 {
-    constexpr int CH = FmChunk<L>::CH;
     const bool sum_lane = SL ? sub == K / VEC : sub == 0;
     int64_t e = beg;
-    for (; e + L * CH <= end; e += L * CH) {
+    // the lean form of wide groups takes every entry through the four-at-a-time loop below
+    constexpr bool CHUNKS = !(CH == 1 && L >= 16);
+    for (; CHUNKS && e + L * CH <= end; e += L * CH) {
         int ix[CH];
         float xv[CH];
 #pragma unroll
@@ -287,7 +288,9 @@ __device__ __forceinline__ void fm_col_accumulate_packed(const int32_t* __restri
             ix[u] = idx[my];
             xv[u] = val[my];
         }
-        fm_gather_slots_packed<VEC, L, NT, SL, CH * L>(ix, xv, src, stride, kb, K, sum_lane, acc, gw, s2);
+        // (a single slot per step is the lean form: at most 8 gathers in flight there)
+        fm_gather_slots_packed<VEC, L, NT, SL, CH * L, CH == 1 ? 8 : 16>(ix, xv, src, stride, kb, K, sum_lane, acc, gw,
+                                                                         s2);
     }
     for (; e < end; e += L) {
         const int64_t want = e + sub;
