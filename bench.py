@@ -127,14 +127,24 @@ def main():
     dom_ms = kern[dominant]["avg_ms"]
     achieved = ab[dominant] / (dom_ms * 1e-3) / 1e9
     traffic = None
+    epoch_traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{wl.name}.json")
     if args.scale == 1.0 and os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(dominant, {}).get("hbm_bytes_per_launch")
+        tj = json.load(open(tpath))
+        traffic = tj.get(dominant, {}).get("hbm_bytes_per_launch")
+        epoch_traffic = sum(v["hbm_bytes_per_launch"] for k, v in tj.items() if isinstance(v, dict))
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "algorithmic_bytes_per_launch": ab[dominant], "avg_launch_ms": dom_ms,
                 "epoch_algorithmic_GBs": ab["epoch"] / (ms_per_step * 1e-3) / 1e9,
                 "epoch_frac": ab["epoch"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                # counted HBM bytes (rocprofv3 summary under profiles/) over the durations measured here:
+                # what the memory system actually moved, misses of the gathers included
+                "traffic_GBs": None if traffic is None else traffic / (dom_ms * 1e-3) / 1e9,
+                "traffic_frac": None if traffic is None else traffic / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "epoch_traffic": epoch_traffic,
+                "epoch_traffic_frac": None if epoch_traffic is None
+                else epoch_traffic / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                 "kernels": {k: {"avg_ms": v["avg_ms"], "algorithmic_GBs": ab[k] / (v["avg_ms"] * 1e-3) / 1e9}
                             for k, v in kern.items() if k in ab}}
 
