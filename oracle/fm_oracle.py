@@ -206,7 +206,7 @@ def refresh(X: Matrix, a, G, q, rows, cols, dw, dV, dn):
 
 
 def stratified_epoch(X: Matrix, y, w0, w, V, *, P, loss, s, lambda_w, lambda_v, eta,
-                     update_w0=True, reg_share=True, refresh_all_rows=False,
+                     update_w0=True, reg_share=True, refresh_all_rows=False, stale_aux=False,
                      cell_order=None, on_stratum=None, final_objective=True):
     """One doubly-separable stratified epoch (Sections 4.2-4.3, synchronous ring reading).
 
@@ -224,6 +224,10 @@ def stratified_epoch(X: Matrix, y, w0, w, V, *, P, loss, s, lambda_w, lambda_v, 
     column's delta (aggregates stay exact) instead of only each cell's own rows
     (aggregates of other row blocks go stale until the next re-computation, as
     the paper describes).
+    ``stale_aux``: no phase B at all: every cell step of the epoch reads the
+    aggregates computed at its start, and they are only recomputed by the next
+    epoch's forward (the two phases of Algorithm 1: update with stale G and A,
+    then re-computation).
     ``cell_order``: optional permutation of range(P) per stratum, to show that the
     result does not depend on the order of the cells.
     ``on_stratum(s, state)`` is called after every stratum with a dict of the live arrays.
@@ -247,7 +251,9 @@ def stratified_epoch(X: Matrix, y, w0, w, V, *, P, loss, s, lambda_w, lambda_v, 
                                  _f64(lambda_v), _i64(rb[p]), _i64(rb[p + 1]), _i64(cb[qb]),
                                  _i64(cb[qb + 1]), _p(X.colptr), _p(X.row), _p(X.cval), _p(y),
                                  _f64(w0), _p(a), _p(G), _p(q), _p(r), _p(w), _p(V), _p(dw), _p(dV), _p(dn))
-        if refresh_all_rows:  # phase B, exact: every column changed once in this stratum
+        if stale_aux:  # no phase B: the aggregates wait for the re-computation
+            pass
+        elif refresh_all_rows:  # phase B, exact: every column changed once in this stratum
             L.oracle_refresh(_i32(K), _i64(0), _i64(N), _i64(0), _i64(D), _p(X.rowptr), _p(X.col),
                              _p(X.val), _p(dw), _p(dV), _p(dn), _p(a), _p(G), _p(q))
         else:  # phase B, local: each cell refreshes its own rows with its own columns

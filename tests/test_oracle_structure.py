@@ -241,3 +241,63 @@ def test_full_regulariser_per_cell_differs_only_by_the_regulariser_share():
     c = O.stratified_epoch(X, y, 0.0, w, V, lambda_w=0.5, lambda_v=0.5, reg_share=False, **kw)
     d = O.stratified_epoch(X, y, 0.0, w, V, lambda_w=0.5, lambda_v=0.5, reg_share=True, **kw)
     assert np.linalg.norm(c[1]) < np.linalg.norm(d[1])  # full lambda per cell shrinks harder
+
+
+@pytest.mark.parametrize("loss", [O.LOSS_SQUARED, O.LOSS_LOGISTIC])
+def test_stale_aggregate_epoch_without_regulariser_is_the_full_gradient_epoch(loss):
+    """Every cell step of a stale epoch reads the aggregates (hence the multipliers r) of the
+    epoch's start, and every cell is visited once.  With lambda = 0 the steps on w and w0 add up
+    to one full-gradient step at the starting point, whatever P is.  The gradient of v_j also
+    holds v_j itself (the term -v_jk sum_i x_ij^2 r_i), which moves from one cell step to the
+    next: V follows the affine maps v <- v - eta (gV_p - s2_p v) in the order of the ring, with
+    gV_p, s2_p the sums over row block p at the frozen r and G (equal to the full step when P = 1)."""
+    rng, X, Xs, y, w, V = _rand_problem(41, 60, 26, 4, 0.3)
+    N, D = Xs.shape
+    kw = dict(loss=loss, s=1.0 / 60, lambda_w=0.0, lambda_v=0.0, eta=0.07)
+    w0a, wa, Va, _ = O.full_epoch(X, y, 0.2, w, V, **kw)
+    _, G0, _, yh = O.forward(X, 0.2, w, V)
+    _, r0 = O.loss_multiplier(loss, kw["s"], yh, y)
+    for P in (1, 3, 7):
+        w0b, wb, Vb, _, aux = O.stratified_epoch(X, y, 0.2, w, V, P=P, stale_aux=True, **kw)
+        np.testing.assert_allclose(wb, wa, rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(w0b, w0a, rtol=1e-12)
+        rb, cb = O.block_bounds(N, P), O.block_bounds(D, P)
+        want = V.copy()
+        for q in range(P):
+            J = slice(cb[q], cb[q + 1])
+            for st in range(P):
+                pb = (q - st) % P
+                Xp = Xs[rb[pb]:rb[pb + 1], J]
+                rp, Gp = r0[rb[pb]:rb[pb + 1]], G0[rb[pb]:rb[pb + 1]]
+                gV = Xp.T @ (rp[:, None] * Gp)
+                s2 = Xp.multiply(Xp).T @ rp
+                want[J] = want[J] - kw["eta"] * (gV - s2[:, None] * want[J])
+        np.testing.assert_allclose(Vb, want, rtol=1e-11, atol=1e-15)
+        if P == 1:
+            np.testing.assert_allclose(Vb, Va, rtol=1e-12, atol=1e-15)
+        # the aggregates were never touched: still those of the starting point
+        np.testing.assert_allclose(aux["G"], Xs @ V, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(aux["a"], Xs @ w, rtol=1e-12, atol=1e-14)
+
+
+def test_stale_aggregate_epoch_with_regulariser_shrinks_each_column_by_its_shares():
+    """With lambda > 0 and no data (y chosen so that r = 0: squared loss at y = yhat) a stale
+    epoch multiplies every w_j by prod_p (1 - eta rho_p lambda), rho_p = |I_p|/N."""
+    rng, X, Xs, y, w, V = _rand_problem(42, 50, 18, 3, 0.3)
+    _, _, _, yh = O.forward(X, 0.0, w, V)
+    P, eta, lw, lv = 4, 0.3, 0.2, 0.1
+    _, wb, Vb, _, _ = O.stratified_epoch(X, yh, 0.0, w, V, P=P, stale_aux=True, loss=O.LOSS_SQUARED, s=1.0,
+                                         lambda_w=lw, lambda_v=lv, eta=eta)
+    rb = O.block_bounds(X.N, P)
+    fw = np.prod([1 - eta * lw * (rb[p + 1] - rb[p]) / X.N for p in range(P)])
+    fv = np.prod([1 - eta * lv * (rb[p + 1] - rb[p]) / X.N for p in range(P)])
+    np.testing.assert_allclose(wb, w * fw, rtol=1e-12)
+    np.testing.assert_allclose(Vb, V * fv, rtol=1e-12)
+
+
+def test_stale_and_refreshed_epochs_differ_once_there_are_several_blocks():
+    rng, X, Xs, y, w, V = _rand_problem(43, 60, 26, 4, 0.3)
+    kw = dict(P=4, loss=O.LOSS_LOGISTIC, s=1.0, lambda_w=1e-3, lambda_v=1e-3, eta=0.05)
+    a = O.stratified_epoch(X, y, 0.0, w, V, **kw)
+    b = O.stratified_epoch(X, y, 0.0, w, V, stale_aux=True, **kw)
+    assert np.abs(a[2] - b[2]).max() > 1e-6
