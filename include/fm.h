@@ -59,6 +59,10 @@ typedef struct {
     int32_t refresh_all_rows;  /* stratified epoch: 0 = a cell refreshes only its own rows' aggregates
                                   (Section 4.2: other row blocks stay stale until the re-computation);
                                   1 = every stratum ends with an exact refresh of all rows */
+    int32_t stale_aux;         /* stratified epoch: 1 = the two phases of Algorithm 1: every cell step of
+                                  the epoch reads the aggregates computed at its start (no refresh between
+                                  strata; Section 4.2, staleness), and the next fm_stratified_begin
+                                  recomputes them.  Overrides refresh_all_rows. */
 } fm_params;
 
 /* ---- building the data structures (Section 3: X is read by rows for the score,

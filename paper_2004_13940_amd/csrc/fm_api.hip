@@ -596,10 +596,13 @@ static int stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const fl
     A.gs = x.gs;
     A.rs = x.ss;
     A.packed = fm_cols_packed_mode(p->K);
-    A.dV = m->dV;
-    A.dwn = m->dwn;
+    if (!p->stale_aux) {  // the changes are only recorded for the refresh
+        A.dV = m->dV;
+        A.dwn = m->dwn;
+    }
     fill_long(A, m->lstrat, s, true);
     FM_TRY(fm_launch_cols(m, A, true, st));
+    if (p->stale_aux) return FM_OK;  // Algorithm 1: the aggregates wait for the re-computation
     // phase B: incremental refresh of the aggregates and multipliers
     RowArgs R;
     memset(&R, 0, sizeof(R));
@@ -667,7 +670,7 @@ extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float
     // The refresh of a stratum reads the change of a column only where the column has entries in
     // its cell, so the regulariser-only steps of the other columns can wait (not when every row
     // is refreshed from every column's change).
-    const bool lazy = !p->refresh_all_rows && m->lazy_last != nullptr && fm_lazy_enabled();
+    const bool lazy = (!p->refresh_all_rows || p->stale_aux) && m->lazy_last != nullptr && fm_lazy_enabled();
     if (lazy) FM_HIP(m, hipMemsetAsync(m->lazy_last, 0, (size_t)m->D * sizeof(int32_t), st));
     for (int32_t s = 0; s < m->P; ++s) FM_TRY(stratified_step(m, p, s, y, w0, w, V, lazy, st));
     if (lazy) {

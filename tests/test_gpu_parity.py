@@ -243,7 +243,8 @@ def _run_stratified_epochs(B, wl, m, p, X, dev, host, epochs, check_strata=False
     for k, v in flags.items():
         setattr(p, k, int(v))
     kw = oracle_kw(wl)
-    okw = dict(reg_share=not flags.get("reg_full_per_cell", False), refresh_all_rows=flags.get("refresh_all_rows", False))
+    okw = dict(reg_share=not flags.get("reg_full_per_cell", False), refresh_all_rows=flags.get("refresh_all_rows", False),
+               stale_aux=flags.get("stale_aux", False))
     for ep in range(epochs):
         if check_strata:
             # step through the strata on both sides and compare the live aggregates
@@ -312,7 +313,8 @@ def test_scaled_workloads_full_and_stratified_epochs(idx, scale, epochs):
 
 @pytest.mark.parametrize("P,flags", [(1, {}), (3, {}), (7, {"refresh_all_rows": True}),
                                      (5, {"reg_full_per_cell": True}), (64, {}),
-                                     (4, {"refresh_all_rows": True, "reg_full_per_cell": True})])
+                                     (4, {"refresh_all_rows": True, "reg_full_per_cell": True}),
+                                     (6, {"stale_aux": True})])
 def test_stratified_variants_with_per_stratum_checks(P, flags):
     """P not dividing N or D, P = 1, P > D, exact refresh, full regulariser per cell; a dense
     column makes every stratum hold a column longer than one segment when P is small."""
@@ -325,6 +327,17 @@ def test_stratified_variants_with_per_stratum_checks(P, flags):
     m, p, X, dev, host = _run_full_epochs(B, wl, 0)
     m.fm_partition(P)
     _run_stratified_epochs(B, wl, m, p, X, dev, host, 2, check_strata=True, **flags)
+    m.close()
+
+
+def test_stale_aggregate_epochs_of_a_scaled_workload():
+    """Algorithm 1's two phases (no refresh between strata) through fm_stratified_epoch, where the
+    regulariser-only steps are postponed as well."""
+    B = _B()
+    wl = make_config(3, scale=0.1)
+    m, p, X, dev, host = _run_full_epochs(B, wl, 1)
+    m.fm_partition(wl.P)
+    _run_stratified_epochs(B, wl, m, p, X, dev, host, 3, stale_aux=True)
     m.close()
 
 
