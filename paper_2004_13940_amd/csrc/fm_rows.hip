@@ -131,25 +131,28 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
         const float da = fm_group_sum<L>(a_acc);
         const float dq = fm_group_sum<L>(q_acc);
         float pair = 0.f;
-        if (touched && kact) {
-            float g[VEC];
+        float g[VEC];
 #pragma unroll
-            for (int z = 0; z < VEC; ++z) {
-                g[z] = g_old[z] + acc[z];
-                pair += g[z] * g[z];
-            }
-            fm_store_vec<VEC>(A.G + row * A.gs + kbase, g);
+        for (int z = 0; z < VEC; ++z) {
+            g[z] = g_old[z] + acc[z];
+            pair += g[z] * g[z];
         }
+        if (!(touched && kact)) pair = 0.f;
         pair = fm_group_sum<L>(pair);
+        float a_i = 0.f, q_i = 0.f;
         if (touched && sub == 0) {
-            const float a_i = a_old + da;
-            const float q_i = q_old + dq;
-            A.a[row * A.ss] = a_i;
-            A.q[row * A.ss] = q_i;
+            a_i = a_old + da;
+            q_i = q_old + dq;
             const float yh = A.w0[0] + a_i + 0.5f * (pair - q_i);
             if (A.yhat != nullptr) A.yhat[row] = yh;
             loss_and_multiplier(A.loss, A.s, yh, A.y[row], l_i, r_i);
+        }
+        // all stores of a row together, so that its line is written back once
+        if (touched && kact) fm_store_vec<VEC>(A.G + row * A.gs + kbase, g);
+        if (touched && sub == 0) {
             A.r[row * A.ss] = r_i;
+            A.a[row * A.ss] = a_i;
+            A.q[row * A.ss] = q_i;
         }
     }
 
