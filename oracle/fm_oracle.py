@@ -1,8 +1,8 @@
 """fp64 CPU oracle for the FM pass -- TEST INFRASTRUCTURE ONLY.
 
-Thin numpy front end over the plain C loops in ``fm_oracle.c`` plus the two
-epoch drivers (full-gradient epoch, stratified epoch), written step by step in
-the paper's order.  Nothing here imports, or is imported by, the HIP library;
+Thin numpy front end over the plain C loops in ``fm_oracle.c`` plus the epoch
+drivers (full-gradient epoch, stratified epoch, mini-batch epoch), written step by
+step in the paper's order.  Nothing here imports, or is imported by, the HIP library;
 only tests, the smoke check and the benchmark's ``cpu_baseline`` leg use it.
 
 Pinned by tests/test_oracle_*.py against: the O(K D^2) pairwise definition
@@ -271,7 +271,53 @@ def stratified_epoch(X: Matrix, y, w0, w, V, *, P, loss, s, lambda_w, lambda_v, 
     return float(w0), w, V, obj, dict(a=a, G=G, q=q, r=r)
 
 
+def minibatch_epoch(X: Matrix, y, w0, w, V, *, B, loss, s, lambda_w, lambda_v, eta,
+                    update_w0=True, reg_share=True, on_batch=None, final_objective=True):
+    """One pass of mini-batch gradient descent over B contiguous row batches, in order
+    (Section 4.1: the stochastic updates, eqs. sgd updates of w_j and v_jk, taken a batch of
+    examples at a time instead of one; the batches are the floor-split row blocks).
+
+      for batch b = 0..B-1, rows I_b:
+          score the rows of I_b at the current parameters; multipliers r_i, i in I_b
+          gradient of  s * sum_{i in I_b} l_i  +  rho_b (lambda_w/2 |w|^2 + lambda_v/2 |V|^2)
+          step on w0, w, V with it                      (rho_b = |I_b|/N, or 1 if not reg_share)
+
+    With B = 1 this is the full-gradient epoch.  ``on_batch(b, state)`` is called after every step.
+    """
+    y = _c(y, np.float64)
+    w, V = _c(w, np.float64).copy(), _c(V, np.float64).copy()
+    w0 = float(w0)
+    K = V.shape[1]
+    N, D = X.N, X.D
+    rb = block_bounds(N, B)
+    r = np.zeros(N)
+    dw, dV, dn = np.zeros(D), np.zeros((D, K)), np.zeros(D)
+    for b in range(B):
+        lo, hi = int(rb[b]), int(rb[b + 1])
+        a, G, q, _ = forward(X, w0, w, V)  # only the rows of the batch are used
+        rho = (hi - lo) / N if reg_share else 1.0
+        cell_update(X, y, w0, w, V, a, G, q, r, (lo, hi), (0, D), loss=loss, s=s, eta=eta, rho=rho,
+                    lambda_w=lambda_w, lambda_v=lambda_v, dw=dw, dV=dV, dn=dn)
+        if update_w0:
+            w0 = w0 - eta * float(np.sum(r[lo:hi]))
+        if on_batch is not None:
+            on_batch(b, dict(w0=w0, w=w, V=V, r=r, rows=(lo, hi)))
+    obj = objective(loss, s, lambda_w, lambda_v, X, y, w0, w, V) if final_objective else None
+    return w0, w, V, obj
+
+
 # ---- integer structures the library must reproduce bit for bit -------------
+
+def batch_csc(X: Matrix, B, b):
+    """CSC (colptr over all D columns, row, val) of the matrix that keeps only the rows of
+    batch b of B (global row numbers)."""
+    rb = block_bounds(X.N, B)
+    cols = np.repeat(np.arange(X.D, dtype=np.int64), np.diff(X.colptr))
+    keep = (X.row >= rb[b]) & (X.row < rb[b + 1])
+    colptr = np.zeros(X.D + 1, np.int64)
+    np.cumsum(np.bincount(cols[keep], minlength=X.D), out=colptr[1:])
+    return colptr, X.row[keep], X.cval[keep]
+
 
 def stratum_of_entries(N, D, P, rows, cols):
     """Stratum (q - p) mod P of entries given by their row and column indices."""

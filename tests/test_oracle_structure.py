@@ -301,3 +301,79 @@ def test_stale_and_refreshed_epochs_differ_once_there_are_several_blocks():
     a = O.stratified_epoch(X, y, 0.0, w, V, **kw)
     b = O.stratified_epoch(X, y, 0.0, w, V, stale_aux=True, **kw)
     assert np.abs(a[2] - b[2]).max() > 1e-6
+
+
+@pytest.mark.parametrize("loss", [O.LOSS_SQUARED, O.LOSS_LOGISTIC])
+def test_single_batch_minibatch_epoch_is_the_full_gradient_epoch(loss):
+    rng, X, Xs, y, w, V = _rand_problem(51, 40, 18, 3, 0.3, loss)
+    kw = dict(loss=loss, s=1.0 / 40, lambda_w=1e-2, lambda_v=2e-2, eta=0.1)
+    w0a, wa, Va, _ = O.full_epoch(X, y, 0.3, w, V, **kw)
+    w0b, wb, Vb, _ = O.minibatch_epoch(X, y, 0.3, w, V, B=1, **kw)
+    np.testing.assert_allclose(w0b, w0a, rtol=1e-13)
+    np.testing.assert_allclose(wb, wa, rtol=1e-13, atol=1e-16)
+    np.testing.assert_allclose(Vb, Va, rtol=1e-13, atol=1e-16)
+
+
+@pytest.mark.parametrize("loss,share", [(O.LOSS_SQUARED, True), (O.LOSS_LOGISTIC, True), (O.LOSS_LOGISTIC, False)])
+def test_every_minibatch_step_is_a_gradient_step_on_the_batch_objective(loss, share):
+    """The move of a batch step, divided by -eta, is the gradient of
+    s sum_{i in batch} l_i + rho (lambda_w/2 |w|^2 + lambda_v/2 |V|^2) at the parameters the step
+    started from: checked by central differences of the objective of the sub-matrix made of the
+    batch's rows (an independent route: it never sees the other rows)."""
+    N, D, K, B = 37, 15, 3, 4
+    rng, X, Xs, y, w, V = _rand_problem(52, N, D, K, 0.35, loss)
+    lw, lv, eta, s = 0.05, 0.08, 0.2, 1.0 / N
+    rb = O.block_bounds(N, B)
+    prev = dict(w0=0.1, w=w.copy(), V=V.copy())
+    seen = []
+
+    def check(b, st):
+        lo, hi = st["rows"]
+        assert (lo, hi) == (rb[b], rb[b + 1])
+        sub = Xs[lo:hi].tocsr()
+        sub.sort_indices()
+        Xb = O.make_matrix(hi - lo, D, sub.indptr.astype(np.int64), sub.indices.astype(np.int32),
+                           sub.data.astype(np.float32))
+        rho = (hi - lo) / N if share else 1.0
+
+        def F(w0_, w_, V_):
+            o = O.objective(loss, s, rho * lw, rho * lv, Xb, y[lo:hi], w0_, w_, V_)
+            return o[0] + o[1]
+
+        h = 1e-6
+        gw0 = (F(prev["w0"] + h, prev["w"], prev["V"]) - F(prev["w0"] - h, prev["w"], prev["V"])) / (2 * h)
+        np.testing.assert_allclose((st["w0"] - prev["w0"]) / -eta, gw0, rtol=1e-6, atol=1e-9)
+        for _ in range(6):
+            j, k = int(rng.integers(D)), int(rng.integers(K))
+            e = np.zeros(D); e[j] = h
+            gw = (F(prev["w0"], prev["w"] + e, prev["V"]) - F(prev["w0"], prev["w"] - e, prev["V"])) / (2 * h)
+            np.testing.assert_allclose((st["w"][j] - prev["w"][j]) / -eta, gw, rtol=1e-6, atol=1e-9)
+            E = np.zeros((D, K)); E[j, k] = h
+            gv = (F(prev["w0"], prev["w"], prev["V"] + E) - F(prev["w0"], prev["w"], prev["V"] - E)) / (2 * h)
+            np.testing.assert_allclose((st["V"][j, k] - prev["V"][j, k]) / -eta, gv, rtol=1e-6, atol=1e-9)
+        prev.update(w0=st["w0"], w=st["w"].copy(), V=st["V"].copy())
+        seen.append(b)
+
+    O.minibatch_epoch(X, y, 0.1, w, V, B=B, loss=loss, s=s, lambda_w=lw, lambda_v=lv, eta=eta, reg_share=share,
+                      on_batch=check, final_objective=False)
+    assert seen == list(range(B))
+
+
+def test_batch_csc_keeps_each_entry_in_exactly_one_batch():
+    rng, X, Xs, y, w, V = _rand_problem(53, 29, 13, 2, 0.3)
+    B = 5
+    dense = Xs.toarray()
+    rb = O.block_bounds(29, B)
+    total = 0
+    for b in range(B):
+        colptr, row, val = O.batch_csc(X, B, b)
+        sub = np.zeros_like(dense)
+        for j in range(13):
+            for e in range(colptr[j], colptr[j + 1]):
+                sub[row[e], j] = val[e]
+            assert np.all(np.diff(row[colptr[j]:colptr[j + 1]]) > 0)
+        want = np.zeros_like(dense)
+        want[rb[b]:rb[b + 1]] = dense[rb[b]:rb[b + 1]]
+        np.testing.assert_array_equal(sub, want)
+        total += len(row)
+    assert total == len(X.col)
