@@ -96,6 +96,13 @@ int fm_get_stratum_csr(const fm_matrix* m, int32_t s, int64_t* rowptr /*N+1, sta
 int fm_get_stratum_csc(const fm_matrix* m, int32_t s, int64_t* colptr /*D+1, starts at 0*/,
                        int32_t* row, float* val);
 
+/* Row batches for fm_minibatch_epoch: B contiguous floor-split row blocks, and for every batch
+ * the CSC of the matrix restricted to its rows (rows keep their global numbers, ascending per
+ * column).  Needs fm_build_csc.  1 <= B <= 4096.  Independent of fm_partition. */
+int fm_partition_batches(fm_matrix* m, int32_t B, void* hip_stream);
+int fm_get_batch_csc(const fm_matrix* m, int32_t b, int64_t* colptr /*HOST D+1, starts at 0*/,
+                     int32_t* row /*HOST*/, float* val /*HOST*/);
+
 /* ---- the pass ---- */
 
 /* Steps 1-3: aggregates, predictions (eq. fm_model2), loss and multipliers.
@@ -141,6 +148,16 @@ int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y /*DEVICE N*/,
  * FINAL parameters (costs one more pass).  Needs fm_partition. */
 int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float* y, float* w0, float* w, float* V,
                         double* objective /*HOST 2*/, void* hip_stream);
+
+/* One pass of mini-batch gradient descent over the B row batches, in order (Section 4.1: the
+ * stochastic updates of w_j and v_jk, taken a batch of examples at a time).  For batch b, rows I_b:
+ *   steps 1-3 on the rows of I_b at the parameters as they stand;
+ *   gradient of  s sum_{i in I_b} l_i + rho_b (lambda_w/2 |w|^2 + lambda_v/2 |V|^2)  and the step on
+ *   w0 (if update_w0), w, V;  rho_b = |I_b|/N, or 1 with reg_full_per_cell.
+ * With B = 1 this is fm_sgd_epoch.  objective (HOST 2, nullable): from a fresh forward at the FINAL
+ * parameters (costs one more pass).  Needs fm_partition_batches. */
+int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float* y, float* w0, float* w, float* V,
+                       double* objective /*HOST 2*/, void* hip_stream);
 
 /* The three parts of fm_stratified_epoch, for callers that interleave their own work
  * (or inspect the aggregates) between strata: begin = re-computation pass, step = one

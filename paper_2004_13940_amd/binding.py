@@ -34,8 +34,9 @@ class FMError(RuntimeError):
 
 
 EXPORTS = ["fm_build_csr", "fm_build_csc", "fm_partition", "fm_get_csc", "fm_get_block_index",
-           "fm_get_stratum_nnz", "fm_get_stratum_csr", "fm_get_stratum_csc", "fm_forward", "fm_gradient",
-           "fm_sgd_epoch", "fm_stratified_epoch", "fm_stratified_begin", "fm_stratified_step",
+           "fm_get_stratum_nnz", "fm_get_stratum_csr", "fm_get_stratum_csc", "fm_partition_batches",
+           "fm_get_batch_csc", "fm_forward", "fm_gradient",
+           "fm_sgd_epoch", "fm_minibatch_epoch", "fm_stratified_epoch", "fm_stratified_begin", "fm_stratified_step",
            "fm_stratified_end", "fm_get_aux", "fm_profile_enable", "fm_profile_kernels",
            "fm_profile_kernel_name", "fm_profile_read", "fm_set_tuning", "fm_set_tile_tuning", "fm_destroy", "fm_last_error"]
 
@@ -182,6 +183,19 @@ class Matrix:
     def fm_get_stratum_csc(self, s):
         return self._get_stratum(load().fm_get_stratum_csc, s, self.D)
 
+    def fm_partition_batches(self, B, stream=None):
+        self._check(load().fm_partition_batches(self._h, ctypes.c_int32(B), _stream(stream)))
+        self.B = int(B)
+
+    def fm_get_batch_csc(self, b):
+        colptr = np.empty(self.D + 1, np.int64)
+        self._check(load().fm_get_batch_csc(self._h, ctypes.c_int32(b), _vp(colptr), _vp(None), _vp(None)))
+        n = int(colptr[-1])
+        row = np.empty(n, np.int32)
+        val = np.empty(n, np.float32)
+        self._check(load().fm_get_batch_csc(self._h, ctypes.c_int32(b), _vp(None), _vp(row), _vp(val)))
+        return colptr, row, val
+
     # -- the pass
     def fm_forward(self, p: fm_params, y, w0, w, V, yhat=None, a=None, G=None, q=None, r=None,
                    want_loss=False, stream=None):
@@ -211,6 +225,9 @@ class Matrix:
 
     def fm_sgd_epoch(self, p, y, w0, w, V, want_objective=False, stream=None):
         return self._epoch(load().fm_sgd_epoch, p, y, w0, w, V, want_objective, stream)
+
+    def fm_minibatch_epoch(self, p, y, w0, w, V, want_objective=False, stream=None):
+        return self._epoch(load().fm_minibatch_epoch, p, y, w0, w, V, want_objective, stream)
 
     def fm_stratified_epoch(self, p, y, w0, w, V, want_objective=False, stream=None):
         return self._epoch(load().fm_stratified_epoch, p, y, w0, w, V, want_objective, stream)

@@ -234,6 +234,24 @@ extern "C" int fm_get_stratum_csc(const fm_matrix* m, int32_t s, int64_t* colptr
     return get_stratum(m, s, false, colptr, row, val);
 }
 
+extern "C" int fm_get_batch_csc(const fm_matrix* m, int32_t b, int64_t* colptr, int32_t* row, float* val)
+{
+    if (m == nullptr) return FM_EINVAL;
+    fm_matrix* mm = const_cast<fm_matrix*>(m);
+    if (m->B == 0) return fm_fail(mm, FM_ESTATE, "row batches not built");
+    if (b < 0 || b >= m->B) return fm_fail(mm, FM_EINVAL, "batch %d outside [0,%d)", b, m->B);
+    FM_HIP(mm, hipDeviceSynchronize());
+    const int64_t off = m->h_batch_nnz_off[b], cnt = m->h_batch_nnz_off[b + 1] - off;
+    if (colptr) {
+        FM_HIP(mm, hipMemcpy(colptr, m->b_colptr + (int64_t)b * m->D, (size_t)(m->D + 1) * sizeof(int64_t),
+                             hipMemcpyDeviceToHost));
+        for (int64_t k = 0; k <= m->D; ++k) colptr[k] -= off;
+    }
+    if (row && cnt) FM_HIP(mm, hipMemcpy(row, m->b_row + off, (size_t)cnt * sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (val && cnt) FM_HIP(mm, hipMemcpy(val, m->b_cval + off, (size_t)cnt * sizeof(float), hipMemcpyDeviceToHost));
+    return FM_OK;
+}
+
 // ------------------------------------------------------------ workspace ----
 
 static int check_params(fm_matrix* m, const fm_params* p)
@@ -324,7 +342,7 @@ static int ensure_ws(fm_matrix* m, int32_t K)
     fm_drop_workspace(m);
     const size_t D = (size_t)m->D;
     FM_TRY(fm_dev_alloc(m, (void**)&m->aux, (size_t)std::max<int64_t>(fm_aux_floats(m->N, K), 1) * sizeof(float)));
-    const int64_t items = std::max<int64_t>(m->lfull.nitems, m->lstrat.nitems);
+    const int64_t items = std::max<int64_t>(std::max<int64_t>(m->lfull.nitems, m->lstrat.nitems), m->lbatch.nitems);
     FM_TRY(fm_dev_alloc(m, (void**)&m->part_acc, (size_t)std::max<int64_t>(items, 1) * K * sizeof(float)));
     FM_TRY(fm_dev_alloc(m, (void**)&m->part_gs, (size_t)std::max<int64_t>(items, 1) * sizeof(float2)));
     FM_TRY(fm_dev_alloc(m, (void**)&m->row_part, (size_t)std::max<int64_t>(fm_rows_grid(m->N, K), 1) * 2 * sizeof(float)));
@@ -681,6 +699,91 @@ extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float
     FM_TRY(fm_stratified_end(m, p, w0, hip_stream));
     if (objective != nullptr) {
         FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, nullptr, nullptr, nullptr, 2, true, st));
+        FM_TRY(fm_reduce_sum(m, w, m->D, 1, true, m->scal + 2, st));
+        FM_TRY(fm_reduce_sum(m, V, m->D * (int64_t)p->K, 1, true, m->scal + 3, st));
+        FM_HIP(m, hipMemcpyAsync(m->h_scal, m->scal, 4 * sizeof(double), hipMemcpyDeviceToHost, st));
+        FM_HIP(m, hipStreamSynchronize(st));
+        objective[0] = (double)p->loss_scale * m->h_scal[0];
+        objective[1] = 0.5 * (double)p->lambda_w * m->h_scal[2] + 0.5 * (double)p->lambda_v * m->h_scal[3];
+    }
+    return FM_OK;
+}
+
+// ------------------------------------------------------- mini-batch epoch ----
+
+extern "C" int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float* y, float* w0, float* w, float* V,
+                                  double* objective, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    FM_TRY(check_params(m, p));
+    if (m->B == 0) return fm_fail(m, FM_ESTATE, "fm_minibatch_epoch needs fm_partition_batches first");
+    if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
+        return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
+    hipStream_t st = (hipStream_t)hip_stream;
+    FM_TRY(ensure_ws(m, p->K));
+    m->aux_full = false;
+    const FmAux x = fm_aux_layout(m, p->K);
+    // a column without entries in a batch only takes the regulariser's step there: postponed
+    // until the column next has entries, or the epoch ends
+    const bool lazy = fm_lazy_enabled();
+    if (lazy) FM_HIP(m, hipMemsetAsync(m->lazy_last, 0, (size_t)m->D * sizeof(int32_t), st));
+    auto col_args = [&](int32_t b, ColArgs& A) {
+        base_col_args(m, p, A);
+        A.w = w;
+        A.V = V;
+        A.P = m->B;
+        A.s = b;
+        A.batch = 1;
+        if (!p->reg_full_per_cell) A.rho = m->d_brho;
+        if (lazy) A.lazy_last = m->lazy_last;
+    };
+    for (int32_t b = 0; b < m->B; ++b) {
+        const int64_t r0 = m->h_bb[b], nb = m->h_bb[b + 1] - r0;
+        if (nb > 0) {  // steps 1-3 on the rows of the batch, at the parameters as they stand
+            RowArgs R;
+            memset(&R, 0, sizeof(R));
+            R.N = nb;
+            R.K = p->K;
+            R.rowptr = m->rowptr + r0;
+            R.col = m->col;
+            R.val = m->val;
+            R.w0 = w0;
+            R.w = w;
+            R.V = V;
+            R.y = y + r0;
+            R.G = x.G + r0 * x.gs;
+            R.gs = x.gs;
+            R.ss = x.ss;
+            R.r = x.r + r0 * x.ss;
+            R.row_part = p->update_w0 ? m->row_part : nullptr;
+            R.loss = p->loss;
+            R.s = p->loss_scale;
+            FM_TRY(fm_launch_rows(m, R, false, st));
+            if (R.row_part != nullptr)
+                FM_TRY(fm_reduce_pairs(m, m->row_part, fm_rows_grid(nb, p->K), m->scal + 0, st));
+        }
+        // steps 4-5 over the batch's rows: gradient and step of every column that has entries there
+        ColArgs A;
+        col_args(b, A);
+        A.ptr = m->b_colptr + (int64_t)b * m->D;
+        A.row = m->b_row;
+        A.val = m->b_cval;
+        A.r = x.r;
+        A.G = x.G;
+        A.gs = x.gs;
+        A.rs = x.ss;
+        A.packed = fm_cols_packed_mode(p->K);
+        fill_long(A, m->lbatch, b, true);
+        FM_TRY(fm_launch_cols(m, A, true, st));
+        if (p->update_w0 && nb > 0) FM_TRY(fm_bias_step(m, w0, m->scal + 1, p->eta, nullptr, st));
+    }
+    if (lazy) {
+        ColArgs F;
+        col_args(m->B, F);
+        FM_TRY(fm_launch_cols_flush(m, F, st));
+    }
+    if (objective != nullptr) {
+        FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, nullptr, nullptr, nullptr, 1, true, st));
         FM_TRY(fm_reduce_sum(m, w, m->D, 1, true, m->scal + 2, st));
         FM_TRY(fm_reduce_sum(m, V, m->D * (int64_t)p->K, 1, true, m->scal + 3, st));
         FM_HIP(m, hipMemcpyAsync(m->h_scal, m->scal, 4 * sizeof(double), hipMemcpyDeviceToHost, st));

@@ -196,12 +196,17 @@ __global__ void k_stratum_keys(const int64_t* __restrict__ major, int64_t nmajor
     if (e >= n) return;
     const int64_t mj = owner_of(major, nmajor, e);
     const int64_t mn = minor[e];
-    const int64_t i = by_rows ? mj : mn;
-    const int64_t j = by_rows ? mn : mj;
+    const int64_t i = by_rows == 1 ? mj : mn;
+    const int64_t j = by_rows == 1 ? mn : mj;
     const int32_t p = fm_block_of(i, N, P);
-    const int32_t q = fm_block_of(j, D, P);
-    int32_t s = (q - p) % P;
-    if (s < 0) s += P;
+    int32_t s;
+    if (by_rows == 2) {  // row batches: the key is the row block alone
+        s = p;
+    } else {
+        const int32_t q = fm_block_of(j, D, P);
+        s = (q - p) % P;
+        if (s < 0) s += P;
+    }
     keys[e] = (uint32_t)s;
     idx[e] = (uint32_t)e;
     atomicAdd(&cnt[(int64_t)s * nmajor + mj], 1ull);
@@ -896,15 +901,15 @@ extern "C" int fm_build_csc(fm_matrix* m, void* hip_stream)
 }
 
 // One orientation of the per-stratum matrices.
+// (batches: the column orientation keyed by row block alone, P = number of batches)
 static int build_strata_side(fm_matrix* m, bool by_rows, hipStream_t st, int64_t** sptr_out, int32_t** sind_out,
-                             float** sval_out)
+                             float** sval_out, int32_t P, bool batches = false)
 {
     const int64_t n = m->nnz;
     const int64_t nmajor = by_rows ? m->N : m->D;
     const int64_t* major = by_rows ? m->rowptr : m->colptr;
     const int32_t* minor = by_rows ? m->col : m->crow;
     const float* val = by_rows ? m->val : m->cval;
-    const int32_t P = m->P;
     const size_t np = (size_t)P * (size_t)nmajor + 1;
     FM_TRY(fm_dev_alloc(m, (void**)sptr_out, np * sizeof(int64_t)));
     FM_TRY(fm_dev_alloc(m, (void**)sind_out, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
@@ -917,7 +922,7 @@ static int build_strata_side(fm_matrix* m, bool by_rows, hipStream_t st, int64_t
     FM_TRY(fm_dev_alloc(m, (void**)&k1, (size_t)n * 4));
     FM_TRY(fm_dev_alloc(m, (void**)&i1, (size_t)n * 4));
     hipLaunchKernelGGL(k_stratum_keys, dim3(blocks_for(n, 256)), dim3(256), 0, st, major, nmajor, minor, n, m->N,
-                       m->D, P, by_rows ? 1 : 0, k0, i0, (unsigned long long*)*sptr_out);
+                       m->D, P, batches ? 2 : (by_rows ? 1 : 0), k0, i0, (unsigned long long*)*sptr_out);
     FM_HIP(m, hipGetLastError());
     FM_TRY(fm_scan_exclusive_i64(m, *sptr_out, (int64_t)np, st));
     bool alt = false;
@@ -957,11 +962,11 @@ extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
     for (int32_t b = 0; b < P; ++b) h_rho[b] = (float)((double)(m->h_rb[b + 1] - m->h_rb[b]) / (double)m->N);
     FM_TRY(fm_dev_alloc(m, (void**)&m->d_rho, (size_t)P * sizeof(float)));
     FM_HIP(m, hipMemcpy(m->d_rho, h_rho.data(), (size_t)P * sizeof(float), hipMemcpyHostToDevice));
-    FM_TRY(fm_dev_alloc(m, (void**)&m->lazy_last, (size_t)m->D * sizeof(int32_t)));
+    FM_TRY(fm_ensure_lazy(m));
     FM_HIP(m, hipMemcpy(d_cb, m->h_cb.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
 
-    FM_TRY(build_strata_side(m, true, st, &m->s_rowptr, &m->s_col, &m->s_val));
-    FM_TRY(build_strata_side(m, false, st, &m->s_colptr, &m->s_row, &m->s_cval));
+    FM_TRY(build_strata_side(m, true, st, &m->s_rowptr, &m->s_col, &m->s_val, P));
+    FM_TRY(build_strata_side(m, false, st, &m->s_colptr, &m->s_row, &m->s_cval, P));
 
     // cell table: in stratum s column block q only holds entries of row block (q-s) mod P
     const int64_t nt = (int64_t)P * (P + 1);
@@ -991,6 +996,42 @@ extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
     // those of the next listed row begin)
     FM_TRY(build_nonempty_list(m, m->s_rowptr, (int64_t)P * m->N, m->N, P, 0x7fffffff, &m->s_touched, &m->ntouched,
                                &m->h_touch_off, st, &m->s_touched_beg));
+    FM_HIP(m, hipStreamSynchronize(st));
+    fm_drop_workspace(m);
+    return FM_OK;
+}
+
+int fm_ensure_lazy(fm_matrix* m)
+{
+    if (m->lazy_last != nullptr) return FM_OK;
+    return fm_dev_alloc(m, (void**)&m->lazy_last, (size_t)std::max<int64_t>(m->D, 1) * sizeof(int32_t));
+}
+
+extern "C" int fm_partition_batches(fm_matrix* m, int32_t B, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (!m->has_csc) return fm_fail(m, FM_ESTATE, "fm_partition_batches needs fm_build_csc first");
+    if (B < 1 || B > FM_MAXP) return fm_fail(m, FM_EINVAL, "B=%d outside 1..%d", B, FM_MAXP);
+    if (m->B != 0) return fm_fail(m, FM_ESTATE, "row batches are already built (B=%d)", m->B);
+    if (m->N < 1 || m->D < 1) return fm_fail(m, FM_EINVAL, "cannot split an empty matrix");
+    m->B = B;
+    m->h_bb.resize(B + 1);
+    std::vector<float> h_rho((size_t)B);
+    for (int32_t b = 0; b <= B; ++b) m->h_bb[b] = (int64_t)(((__int128)b * (__int128)m->N) / (__int128)B);
+    for (int32_t b = 0; b < B; ++b) h_rho[b] = (float)((double)(m->h_bb[b + 1] - m->h_bb[b]) / (double)m->N);
+    FM_TRY(fm_dev_alloc(m, (void**)&m->d_brho, (size_t)B * sizeof(float)));
+    FM_HIP(m, hipMemcpy(m->d_brho, h_rho.data(), (size_t)B * sizeof(float), hipMemcpyHostToDevice));
+    FM_TRY(fm_ensure_lazy(m));
+    FM_TRY(build_strata_side(m, false, st, &m->b_colptr, &m->b_row, &m->b_cval, B, true));
+    // entries of batch b: from the start of its first column to the start of the next batch's
+    m->h_batch_nnz_off.assign(B + 1, 0);
+    for (int32_t b = 0; b < B; ++b)
+        FM_HIP(m, hipMemcpyAsync(&m->h_batch_nnz_off[b], m->b_colptr + (int64_t)b * m->D, sizeof(int64_t),
+                                 hipMemcpyDeviceToHost, st));
+    FM_HIP(m, hipStreamSynchronize(st));
+    m->h_batch_nnz_off[B] = m->nnz;
+    FM_TRY(fm_build_long_index(m, m->b_colptr, (int64_t)B * m->D, m->D, B, &m->lbatch, st));
     FM_HIP(m, hipStreamSynchronize(st));
     fm_drop_workspace(m);
     return FM_OK;

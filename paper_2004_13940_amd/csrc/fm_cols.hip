@@ -51,6 +51,7 @@ __device__ __forceinline__ void accumulate_entries(const ColArgs& A, int64_t beg
 __device__ __forceinline__ float reg_share(const ColArgs& A, int32_t qb, int32_t t)
 {
     if (A.rho == nullptr) return 1.f;
+    if (A.batch) return A.rho[t];
     int32_t p = (qb - t) % A.P;
     if (p < 0) p += A.P;
     return A.rho[p];
@@ -71,6 +72,7 @@ struct StepFactors {
     const float* rho;
     float lv, lw, eta;
     int32_t P;
+    bool batch;  // step t acts on row block t, the next step on block t+1
     __device__ __forceinline__ float v(int32_t p) const
     {
         return tab != nullptr ? tab[p] : step_factor(rho != nullptr ? rho[p] : 1.f, lv, eta);
@@ -83,15 +85,21 @@ struct StepFactors {
     __device__ __forceinline__ int32_t block_at(int32_t qb, int32_t t) const
     {
         if (P <= 0) return 0;
+        if (batch) return t;
         int32_t p = (qb - t) % P;
         return p < 0 ? p + P : p;
     }
-    __device__ __forceinline__ int32_t next(int32_t p) const { return p == 0 ? (P > 0 ? P - 1 : 0) : p - 1; }
+    __device__ __forceinline__ int32_t next(int32_t p) const
+    {
+        if (P <= 0) return 0;
+        if (batch) return p + 1 < P ? p + 1 : p;
+        return p == 0 ? P - 1 : p - 1;
+    }
 };
 
 __device__ __forceinline__ StepFactors plain_factors(const ColArgs& A)
 {
-    return StepFactors{nullptr, A.rho, A.lambda_v, A.lambda_w, A.eta, A.rho != nullptr ? A.P : 0};
+    return StepFactors{nullptr, A.rho, A.lambda_v, A.lambda_w, A.eta, A.rho != nullptr ? A.P : 0, A.batch != 0};
 }
 
 // Kernels whose every thread gets here fill the table in LDS (2 P floats) when postponed steps
@@ -143,7 +151,7 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
                                               ColState<VEC> c)
 {
     const int K = A.K;
-    const int32_t qb = A.rho != nullptr ? fm_block_of(j, A.D, A.P) : 0;
+    const int32_t qb = (A.rho != nullptr && !A.batch) ? fm_block_of(j, A.D, A.P) : 0;
     const float rho = reg_share(A, qb, A.s);
     float dn = 0.f;
     if (kact) {
@@ -255,7 +263,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_empty(const ColArgs A)
         finish_column<VEC, LE, false>(A, j, sub, kbase, kact, acc, 0.f, 0.f, plain_factors(A),
                                       load_column<VEC, false>(A, j, sub, kbase, kact));
     } else {
-        const int32_t qb = A.rho != nullptr ? fm_block_of(j, A.D, A.P) : 0;
+        const int32_t qb = (A.rho != nullptr && !A.batch) ? fm_block_of(j, A.D, A.P) : 0;
         const float rho = reg_share(A, qb, A.s);
         float dn = 0.f;
         if (kact) {
@@ -297,7 +305,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
     if (j >= A.D) return;  // whole groups leave together
     const int32_t t0 = A.lazy_last[j];
     if (t0 >= A.s) return;
-    const int32_t qb = A.rho != nullptr ? fm_block_of(j, A.D, A.P) : 0;
+    const int32_t qb = (A.rho != nullptr && !A.batch) ? fm_block_of(j, A.D, A.P) : 0;
     const int kbase = sub * VEC;
     if (kbase < A.K) {
         float v[VEC];

@@ -123,6 +123,14 @@ struct fm_matrix {
     int64_t* s_touched_beg = nullptr;  // [ntouched+1] where the entries of each listed row begin
     int64_t ntouched = 0;
     std::vector<int64_t> h_touch_off;  // [P+1] offsets into s_touched
+    // row batches of the mini-batch epoch: per batch the CSC of the matrix restricted to its rows
+    int32_t B = 0;
+    std::vector<int64_t> h_bb, h_batch_nnz_off;  // [B+1] row bounds, [B+1] offsets into b_row/b_cval
+    int64_t* b_colptr = nullptr;  // [B*D+1] global offsets into b_row/b_cval
+    int32_t* b_row = nullptr;
+    float* b_cval = nullptr;
+    LongIndex lbatch;
+    float* d_brho = nullptr;  // [B] share |I_b|/N
     // workspace, sized for wsK
     int32_t wsK = 0;
     float* aux = nullptr;   // aggregates, see fm_aux_layout
@@ -185,6 +193,7 @@ int fm_sort_by_key_u32(fm_matrix* m, uint32_t* keys, uint32_t* idx, uint32_t* ke
 int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
                         LongIndex* out, hipStream_t st);
 int fm_build_full_index(fm_matrix* m, hipStream_t st);  // lfull, with the panel order of heavy columns
+int fm_ensure_lazy(fm_matrix* m);  // allocates lazy_last on first use
 
 // ---- pass kernels (fm_rows.hip / fm_cols.hip / fm_reduce.hip) ----
 struct RowArgs {
@@ -235,6 +244,7 @@ struct ColArgs {
     const float* rho;
     int64_t N;
     int32_t P, s;
+    int32_t batch;  // 1: steps are row batches, step t acts on row block t (else on (colblock - t) mod P)
     // nullable, update only: lazy_last[j] = number of strata of this epoch whose step column j has
     // taken.  A column that is empty in a cell only feels the regulariser there; with this array
     // those steps are postponed until the column next has entries (or the epoch ends) and then

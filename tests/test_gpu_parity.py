@@ -405,6 +405,114 @@ def test_postponed_regulariser_steps_give_the_bits_of_immediate_ones(idx, scale,
     m.close()
 
 
+# ------------------------------------------------------- mini-batch epochs ----
+
+@pytest.mark.parametrize("N,D,B,density", [(97, 31, 4, 0.2), (64, 50, 7, 0.1), (10, 40, 16, 0.3)])
+def test_batch_csc_is_bit_exact(N, D, B, density):
+    B_ = _B()
+    rng = np.random.default_rng(77 + B)
+    rowptr, col, val = random_csr(rng, N, D, density)
+    X = O.make_matrix(N, D, rowptr, col, val)
+    m = B_.Matrix(N, D, rowptr, col, val)
+    m.fm_build_csc()
+    m.fm_partition_batches(B)
+    for b in range(B):
+        colptr, row, v = m.fm_get_batch_csc(b)
+        wc, wr, wv = O.batch_csc(X, B, b)
+        np.testing.assert_array_equal(colptr, wc)
+        np.testing.assert_array_equal(row, wr)
+        np.testing.assert_array_equal(v, wv.astype(np.float32))
+    m.close()
+
+
+def _run_minibatch_epochs(Bm, wl, nb, epochs, full_reg=False, update_w0=True):
+    import torch
+    X = O.make_matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
+    m = Bm.Matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
+    m.fm_build_csc()
+    m.fm_partition_batches(nb)
+    p = Bm.make_params(wl.K, wl.loss, wl.lambda_w, wl.lambda_v, wl.eta, wl.loss_scale, int(update_w0),
+                       reg_full_per_cell=int(full_reg))
+    d_w0, d_w, d_V = dev_params(wl.w0, wl.w, wl.V)
+    d_y = to_dev(wl.y)
+    w0, w, V = float(wl.w0), wl.w.astype(np.float64), wl.V.astype(np.float64)
+    kw = oracle_kw(wl)
+    for ep in range(epochs):
+        obj = m.fm_minibatch_epoch(p, d_y, d_w0, d_w, d_V, want_objective=True)
+        w0, w, V, wobj = O.minibatch_epoch(X, wl.y, w0, w, V, B=nb, update_w0=update_w0, reg_share=not full_reg, **kw)
+        torch.cuda.synchronize()
+        _say(f"  mini-batch epoch {ep}: objective gpu {obj[0] + obj[1]:.8f} oracle {wobj[0] + wobj[1]:.8f}")
+        assert abs(obj[0] - wobj[0]) <= REL_TOL * abs(wobj[0])
+        assert abs(obj[1] - wobj[1]) <= REL_TOL * abs(wobj[1]) + 1e-12
+        assert_close(d_w.cpu().numpy(), w, f"w after mini-batch epoch {ep}")
+        assert_close(d_V.cpu().numpy().reshape(wl.D, wl.K), V, f"V after mini-batch epoch {ep}")
+        assert abs(d_w0.item() - w0) <= REL_TOL * max(abs(w0), 1e-3)
+    return m, p, (d_w0, d_w, d_V, d_y)
+
+
+@pytest.mark.parametrize("idx,scale,nb", [(1, 1.0, 5), (3, 0.1, 8), (4, 0.001, 10), (5, 0.002, 3), (2, 0.004, 4)])
+def test_minibatch_epochs_of_the_workloads(idx, scale, nb):
+    wl = make_config(idx, scale=scale)
+    if idx == 1:
+        wl.eta = 0.02  # a batch step with s = 1 still sees the curvature of 400 examples
+    _say("mini-batch", wl.name, wl.N, wl.D, wl.nnz, "K", wl.K, "batches", nb)
+    m, _, _ = _run_minibatch_epochs(_B(), wl, nb, 2, update_w0=bool(wl.update_w0))
+    m.close()
+
+
+@pytest.mark.parametrize("K,nb,full_reg", [(8, 1, False), (5, 6, False), (12, 9, True), (60, 4, False), (256, 3, False)])
+def test_minibatch_variants(K, nb, full_reg):
+    """Batch counts that do not divide N, more batches than some columns have entries, the literal
+    regulariser, one batch; a dense column is long in every batch."""
+    N, D = 1500, 70
+    rowptr, col, val, y, w0, w, V = _problem(500 + K, N, D, K, 0.08, O.LOSS_LOGISTIC, dense_cols=(3,))
+    V *= np.float32(0.3)
+    from paper_2004_13940_amd.workloads import Workload
+    wl = Workload("mb", N, D, K, rowptr, col, val, y, w0, w, V, O.LOSS_LOGISTIC, 1e-2, 2e-2, 0.3, 1.0 / N, 1, nb, 1)
+    m, _, _ = _run_minibatch_epochs(_B(), wl, nb, 2, full_reg=full_reg)
+    m.close()
+
+
+def test_single_batch_epoch_equals_full_gradient_epoch_on_gpu():
+    import torch
+    B = _B()
+    wl = make_config(3, scale=0.05)
+    m = B.Matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
+    m.fm_build_csc()
+    m.fm_partition_batches(1)
+    p = B.make_params(wl.K, wl.loss, wl.lambda_w, wl.lambda_v, wl.eta, wl.loss_scale, 1)
+    y = to_dev(wl.y)
+    a0, aw, aV = dev_params(wl.w0, wl.w, wl.V)
+    b0, bw, bV = dev_params(wl.w0, wl.w, wl.V)
+    m.fm_sgd_epoch(p, y, a0, aw, aV)
+    m.fm_minibatch_epoch(p, y, b0, bw, bV)
+    torch.cuda.synchronize()
+    # the long columns are cut into items differently (panel order against fixed segments), so the
+    # fp32 partial sums differ in the last bits: equal within rounding, not bit for bit
+    np.testing.assert_allclose(bw.cpu().numpy(), aw.cpu().numpy(), rtol=2e-5, atol=1e-9)
+    np.testing.assert_allclose(bV.cpu().numpy(), aV.cpu().numpy(), rtol=2e-5, atol=1e-9)
+    assert abs(a0.item() - b0.item()) <= 1e-6 * max(1.0, abs(a0.item()))
+    m.close()
+
+
+def test_minibatch_needs_its_partition():
+    B = _B()
+    wl = make_config(1)
+    m = B.Matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
+    m.fm_build_csc()
+    p = B.make_params(wl.K, wl.loss, wl.lambda_w, wl.lambda_v, wl.eta, wl.loss_scale, 0)
+    y = to_dev(wl.y)
+    w0, w, V = dev_params(wl.w0, wl.w, wl.V)
+    with pytest.raises(B.FMError):
+        m.fm_minibatch_epoch(p, y, w0, w, V)
+    with pytest.raises(B.FMError):
+        m.fm_partition_batches(0)
+    m.fm_partition_batches(3)
+    with pytest.raises(B.FMError):
+        m.fm_partition_batches(3)
+    m.close()
+
+
 def test_results_are_bit_reproducible():
     import torch
     B = _B()
