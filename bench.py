@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=10_000_000, help="rows of the workload the oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stratified", action="store_true", help="also time fm_stratified_epoch (reported in extra)")
+    ap.add_argument("--minibatch", type=int, default=0, metavar="B",
+                    help="also time fm_minibatch_epoch over B row batches (reported in extra)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain 1 GiB device copy three times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -160,6 +162,18 @@ def main():
         extra["stratified_ms_per_epoch"] = 1e3 * ts
         extra["stratified_nnz_per_s"] = wl.nnz / ts
         extra["P"] = wl.P
+
+    if args.minibatch > 0:
+        m.fm_partition_batches(args.minibatch)
+        m.fm_minibatch_epoch(p, y, w0, w, V)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        m.fm_minibatch_epoch(p, y, w0, w, V)
+        torch.cuda.synchronize()
+        tb = time.perf_counter() - t0
+        extra["minibatch_ms_per_epoch"] = 1e3 * tb
+        extra["minibatch_nnz_per_s"] = wl.nnz / tb
+        extra["B"] = args.minibatch
 
     cpu = None
     if not args.no_cpu_baseline:
