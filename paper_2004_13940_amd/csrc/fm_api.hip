@@ -390,10 +390,21 @@ static void fill_long(ColArgs& A, const LongIndex& li, int32_t s, bool strat)
     A.nshort = s1 - s0;
 }
 
+// FM_WHOLE_ROWS=0: the forward writes only the fields of a packed row that the epoch reads
+static bool fm_whole_rows()
+{
+    static const bool on = [] {
+        const char* e = getenv("FM_WHOLE_ROWS");
+        return !(e != nullptr && e[0] == '0');
+    }();
+    return on;
+}
+
 // RowArgs outputs pointing into the handle's aggregate rows [G | r | a | q | pad]
 static void aux_outputs(fm_matrix* m, int32_t K, RowArgs& A, bool with_aq)
 {
     const FmAux x = fm_aux_layout(m, K);
+    A.whole_rows = (fm_aux_packed(K) && A.y != nullptr && fm_whole_rows()) ? 1 : 0;
     A.G = x.G;
     A.gs = x.gs;
     A.ss = x.ss;
@@ -755,6 +766,7 @@ extern "C" int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float*
             R.gs = x.gs;
             R.ss = x.ss;
             R.r = x.r + r0 * x.ss;
+            R.whole_rows = (fm_aux_packed(p->K) && fm_whole_rows()) ? 1 : 0;
             R.row_part = p->update_w0 ? m->row_part : nullptr;
             R.loss = p->loss;
             R.s = p->loss_scale;

@@ -210,6 +210,7 @@ struct RowArgs {
     float *yhat, *a, *G, *q, *r;  // forward: nullable outputs ; refresh: in/out aggregates
     int64_t gs;         // floats between consecutive rows of G
     int64_t ss;         // floats between consecutive rows of r, a, q (1, or the aggregate row stride)
+    int32_t whole_rows; // forward into packed aggregate rows: write r, a, q and the padding with G
     float* row_part;    // nullable: [2*gridDim] loss and sum r per block
     const int32_t* rows;  // nullable: the launch covers rows[0..N) instead of rows 0..N-1, and
                           // rowptr[k], rowptr[k+1] bound the entries of rows[k]

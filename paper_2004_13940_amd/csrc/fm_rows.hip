@@ -116,15 +116,30 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
         pair = fm_group_sum<L>(pair);
         const float yh = A.w0[0] + a_i + 0.5f * (pair - q_i);
         if (valid) {
-            if (A.G != nullptr && kact) fm_store_vec<VEC>(A.G + row * A.gs + kbase, acc);
             if (sub == 0) {
+                if (A.yhat != nullptr) A.yhat[row] = yh;
+                if (A.y != nullptr) loss_and_multiplier(A.loss, A.s, yh, A.y[row], l_i, r_i);
+            }
+            if (A.G != nullptr && kact) fm_store_vec<VEC>(A.G + row * A.gs + kbase, acc);
+            if (A.whole_rows) {
+                // packed aggregate rows: [r | a | q] and the padding behind G go out as float4 too, so
+                // that every 128-byte line of the row is written whole
+                if constexpr (VEC == 4) {
+                    const int tail4 = (int)(A.gs - K) / 4;
+                    for (int t = sub; t < tail4; t += L) {
+                        float z[4] = {0.f, 0.f, 0.f, 0.f};
+                        if (t == 0) {
+                            z[0] = r_i;
+                            z[1] = a_i;
+                            z[2] = q_i;
+                        }
+                        fm_store_vec<4>(A.G + row * A.gs + K + 4 * t, z);
+                    }
+                }
+            } else if (sub == 0) {
                 if (A.a != nullptr) A.a[row * A.ss] = a_i;
                 if (A.q != nullptr) A.q[row * A.ss] = q_i;
-                if (A.yhat != nullptr) A.yhat[row] = yh;
-                if (A.y != nullptr) {
-                    loss_and_multiplier(A.loss, A.s, yh, A.y[row], l_i, r_i);
-                    if (A.r != nullptr) A.r[row * A.ss] = r_i;
-                }
+                if (A.y != nullptr && A.r != nullptr) A.r[row * A.ss] = r_i;
             }
         }
     } else {
