@@ -271,6 +271,19 @@ def stratified_epoch(X: Matrix, y, w0, w, V, *, P, loss, s, lambda_w, lambda_v, 
     return float(w0), w, V, obj, dict(a=a, G=G, q=q, r=r)
 
 
+def evaluate(X: Matrix, y, w0, w, V, loss):
+    """Predictive performance of the model on (X, y), as the paper's figures report it: mean loss,
+    root mean squared error of the score (regression) and accuracy of its sign (classification,
+    labels in {-1,+1}; a score of exactly 0 counts as +1).  Plain definitions on the scores."""
+    y = _c(y, np.float64)
+    _, _, _, yhat = forward(X, w0, w, V)
+    l, _ = loss_multiplier(loss, 1.0, yhat, y)
+    n = max(len(y), 1)
+    pred = np.where(yhat >= 0.0, 1.0, -1.0)
+    return dict(mean_loss=float(np.sum(l)) / n, rmse=float(np.sqrt(np.sum((yhat - y) ** 2) / n)),
+                accuracy=float(np.sum(pred == y)) / n)
+
+
 def minibatch_epoch(X: Matrix, y, w0, w, V, *, B, loss, s, lambda_w, lambda_v, eta,
                     update_w0=True, reg_share=True, on_batch=None, final_objective=True):
     """One pass of mini-batch gradient descent over B contiguous row batches, in order

@@ -256,6 +256,46 @@ def _cfg5(ss, scale):
                     {"teacher_K": 8, "zipf_s": 1.05})
 
 
+# --------------------------------------------------------------------------
+# small dense shapes (stand-ins for the three small data sets of the paper's
+# table of data set characteristics: same N, D, K and task; synthetic content)
+# --------------------------------------------------------------------------
+
+_SMALL = {"regression_513x8": (513, 8, 4, LOSS_SQUARED), "regression_303x13": (303, 13, 4, LOSS_SQUARED),
+          "classification_49990x22": (49_990, 22, 4, LOSS_LOGISTIC)}
+
+
+def make_small(name: str, seed: int | None = None, test_fraction: float = 0.25):
+    """(train, test) workloads of one of the small dense shapes: every feature stored in every row,
+    standard normal features, targets from a planted FM plus noise (regression) or the sign of the
+    planted score with 5 % flipped (classification).  The test rows are drawn from the same law."""
+    if name not in _SMALL:
+        raise ValueError("small workload must be one of " + ", ".join(_SMALL))
+    N, D, K, loss = _SMALL[name]
+    ss = np.random.SeedSequence(13940 + 100 + sorted(_SMALL).index(name) if seed is None else seed)
+    rng_x, rng_t, rng_p = (np.random.Generator(np.random.PCG64(q)) for q in ss.spawn(3))
+    Nt = max(1, int(round(N * test_fraction)))
+    w_star = rng_t.standard_normal(D) / np.sqrt(D)
+    V_star = rng_t.standard_normal((D, K)) * 0.5 / np.sqrt(D)
+    w0, w, V = _init_params(rng_p, D, K)
+    out = []
+    for n, tag in ((N, "train"), (Nt, "test")):
+        col = np.tile(np.arange(D, dtype=np.int32), n)
+        rowptr = np.arange(n + 1, dtype=np.int64) * D
+        val = rng_x.standard_normal(n * D, dtype=np.float32)
+        sc = _teacher_score(rowptr, col, val, n, D, w_star, V_star)
+        if loss == LOSS_SQUARED:
+            y = sc + 0.1 * rng_t.standard_normal(n)
+        else:
+            y = np.where(sc >= 0.0, 1.0, -1.0)
+            flip = rng_t.random(n) < 0.05
+            y = np.where(flip, -y, y)
+        out.append(Workload(f"{name}_{tag}", n, D, K, rowptr, col, val, y.astype(np.float32), w0, w.copy(), V.copy(),
+                            loss, 1e-3, 1e-3, 0.1 if loss == LOSS_SQUARED else 0.5, 1.0 / N, 20, 2, 1,
+                            {"teacher_K": K, "split": tag}))
+    return out[0], out[1]
+
+
 _RECIPES = {1: _cfg1, 2: _cfg2, 3: _cfg3, 4: _cfg4, 5: _cfg5}
 
 

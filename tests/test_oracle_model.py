@@ -238,3 +238,39 @@ def test_objective_decreases_for_small_step():
                                      lambda_v=1e-3, eta=0.2)
         assert sum(obj) < prev
         prev = sum(obj)
+
+
+def test_evaluate_against_hand_computed_scores():
+    """V = 0 makes the score w0 + x.w: four rows whose scores are 1.5, -0.5, 0 and 2 by hand."""
+    rowptr = np.array([0, 2, 3, 3, 5], np.int64)
+    col = np.array([0, 1, 1, 0, 2], np.int32)
+    val = np.array([1.0, 2.0, 1.0, 3.0, 1.0], np.float32)
+    X = O.make_matrix(4, 3, rowptr, col, val)
+    w = np.array([0.5, 0.5, 0.5])
+    V = np.zeros((3, 2))
+    # scores: 0 + (0.5 + 1.0) = 1.5 ; 0.5 ; 0 ; 1.5 + 0.5 = 2.0 -> shift by w0 = -1 for row 2: use w0 = 0
+    y = np.array([1.0, -1.0, 1.0, -1.0])
+    m = O.evaluate(X, y, 0.0, w, V, O.LOSS_SQUARED)
+    scores = np.array([1.5, 0.5, 0.0, 2.0])
+    assert abs(m["rmse"] - np.sqrt(((scores - y) ** 2).mean())) < 1e-15
+    assert abs(m["rmse"] - np.sqrt((0.25 + 2.25 + 1.0 + 9.0) / 4)) < 1e-15
+    assert m["accuracy"] == 0.5  # rows 0 and 2 (a score of 0 counts as +1) agree, rows 1 and 3 do not
+    assert abs(m["mean_loss"] - 0.5 * (0.25 + 2.25 + 1.0 + 9.0) / 4) < 1e-15
+    ml = O.evaluate(X, y, 0.0, w, V, O.LOSS_LOGISTIC)["mean_loss"]
+    want = np.mean([np.log1p(np.exp(-1.5)), np.log1p(np.exp(0.5)), np.log(2.0), np.log1p(np.exp(2.0))])
+    assert abs(ml - want) < 1e-14
+
+
+def test_small_dense_workloads_have_the_stated_shapes_and_are_learnable():
+    from paper_2004_13940_amd.workloads import make_small
+    for name, (N, D) in (("regression_513x8", (513, 8)), ("regression_303x13", (303, 13))):
+        tr, te = make_small(name)
+        assert (tr.N, tr.D, tr.K) == (N, D, 4) and te.D == D and tr.nnz == N * D
+        X, Xt = (O.make_matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val) for wl in (tr, te))
+        w0, w, V = float(tr.w0), tr.w.astype(np.float64), tr.V.astype(np.float64)
+        before = O.evaluate(Xt, te.y, w0, w, V, tr.loss)["rmse"]
+        for _ in range(200):
+            w0, w, V, _ = O.full_epoch(X, tr.y, w0, w, V, loss=tr.loss, s=tr.loss_scale, lambda_w=tr.lambda_w,
+                                       lambda_v=tr.lambda_v, eta=tr.eta)
+        after = O.evaluate(Xt, te.y, w0, w, V, tr.loss)["rmse"]
+        assert after < 0.8 * before
