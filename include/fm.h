@@ -117,6 +117,17 @@ int fm_forward(fm_matrix* m, const fm_params* p, const float* y /*DEVICE N, null
                float* q /*DEVICE N*/, float* r /*DEVICE N*/, double* loss_sum /*HOST*/,
                void* hip_stream);
 
+/* Predictive performance of (w0, w, V) on this matrix and labels y, as the paper's figures report
+ * it (Section 5, test RMSE for regression and test accuracy for classification):
+ *   metrics[0] = mean loss (1/N) sum_i l_i   (p->loss; loss_scale is not applied)
+ *   metrics[1] = sqrt((1/N) sum_i (yhat_i - y_i)^2)
+ *   metrics[2] = fraction of i with sign(yhat_i) == y_i, y in {-1,+1}, yhat_i == 0 counted as +1
+ * metrics is HOST 3; the call waits for the stream.  The scores are staged in the handle's aggregate
+ * storage: aggregates of an earlier pass are gone afterwards (fm_get_aux then fails with FM_ESTATE). */
+int fm_evaluate(fm_matrix* m, const fm_params* p, const float* y /*DEVICE N*/, const float* w0 /*DEVICE 1*/,
+                const float* w /*DEVICE D*/, const float* V /*DEVICE D*K*/, double* metrics /*HOST 3*/,
+                void* hip_stream);
+
 /* Step 4: gradients of  s sum_i l_i + lambda_w/2 |w|^2 + lambda_v/2 |V|^2  from given r, G
  * (eqs. updates_w0/updates_w/updates_v, regulariser with the sign of gradient descent):
  *   grad_w0 = sum_i r_i

@@ -35,7 +35,7 @@ class FMError(RuntimeError):
 
 EXPORTS = ["fm_build_csr", "fm_build_csc", "fm_partition", "fm_get_csc", "fm_get_block_index",
            "fm_get_stratum_nnz", "fm_get_stratum_csr", "fm_get_stratum_csc", "fm_partition_batches",
-           "fm_get_batch_csc", "fm_forward", "fm_gradient",
+           "fm_get_batch_csc", "fm_forward", "fm_evaluate", "fm_gradient",
            "fm_sgd_epoch", "fm_minibatch_epoch", "fm_stratified_epoch", "fm_stratified_begin", "fm_stratified_step",
            "fm_stratified_end", "fm_get_aux", "fm_profile_enable", "fm_profile_kernels",
            "fm_profile_kernel_name", "fm_profile_read", "fm_set_tuning", "fm_set_tile_tuning", "fm_destroy", "fm_last_error"]
@@ -225,6 +225,13 @@ class Matrix:
 
     def fm_sgd_epoch(self, p, y, w0, w, V, want_objective=False, stream=None):
         return self._epoch(load().fm_sgd_epoch, p, y, w0, w, V, want_objective, stream)
+
+    def fm_evaluate(self, p, y, w0, w, V, stream=None):
+        _dev(y, self.N, "y"); _dev(w0, 1, "w0"); _dev(w, self.D, "w"); _dev(V, self.D * p.K, "V")
+        out = (ctypes.c_double * 3)()
+        self._check(load().fm_evaluate(self._h, ctypes.byref(p), _vp(y), _vp(w0), _vp(w), _vp(V), out,
+                                       _stream(stream)))
+        return dict(mean_loss=out[0], rmse=out[1], accuracy=out[2])
 
     def fm_minibatch_epoch(self, p, y, w0, w, V, want_objective=False, stream=None):
         return self._epoch(load().fm_minibatch_epoch, p, y, w0, w, V, want_objective, stream)

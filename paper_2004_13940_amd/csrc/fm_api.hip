@@ -1,4 +1,5 @@
 // C-ABI entry points and the epoch drivers.
+#include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -333,6 +334,7 @@ void fm_drop_workspace(fm_matrix* m)
     m->part_gs = nullptr;
     m->wsK = 0;
     m->aux_full = false;
+    m->aux_held = false;
 }
 
 // (re)allocate the per-K workspace
@@ -441,6 +443,7 @@ static int run_forward(fm_matrix* m, const fm_params* p, const float* y, const f
         A.ss = 1;
     } else {
         aux_outputs(m, p->K, A, mode == 2);
+        m->aux_held = true;
     }
     A.row_part = (want_sums && y != nullptr) ? m->row_part : nullptr;
     A.loss = p->loss;
@@ -470,6 +473,50 @@ extern "C" int fm_forward(fm_matrix* m, const fm_params* p, const float* y, cons
         FM_HIP(m, hipStreamSynchronize(st));
         *loss_sum = m->h_scal[0];
     }
+    return FM_OK;
+}
+
+extern "C" int fm_evaluate(fm_matrix* m, const fm_params* p, const float* y, const float* w0, const float* w,
+                           const float* V, double* metrics, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    FM_TRY(check_params(m, p));
+    if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr || metrics == nullptr)
+        return fm_fail(m, FM_EINVAL, "y, w0, w, V, metrics must not be NULL");
+    hipStream_t st = (hipStream_t)hip_stream;
+    FM_TRY(ensure_ws(m, p->K));
+    metrics[0] = metrics[1] = metrics[2] = 0.0;
+    if (m->N == 0) return FM_OK;
+    // the scores go to the start of the aggregate storage, which holds nothing afterwards
+    m->aux_held = false;
+    m->aux_full = false;
+    RowArgs A;
+    memset(&A, 0, sizeof(A));
+    A.N = m->N;
+    A.K = p->K;
+    A.rowptr = m->rowptr;
+    A.col = m->col;
+    A.val = m->val;
+    A.w0 = w0;
+    A.w = w;
+    A.V = V;
+    A.y = y;
+    A.yhat = m->aux;
+    A.gs = p->K;
+    A.ss = 1;
+    A.row_part = m->row_part;
+    A.loss = p->loss;
+    A.s = 1.f;
+    FM_TRY(fm_launch_rows(m, A, false, st));
+    FM_TRY(fm_reduce_pairs(m, m->row_part, fm_rows_grid(m->N, p->K), m->scal + 0, st));
+    FM_TRY(fm_reduce_eval(m, m->aux, y, m->N, 0, m->scal + 4, st));
+    FM_TRY(fm_reduce_eval(m, m->aux, y, m->N, 1, m->scal + 5, st));
+    FM_HIP(m, hipMemcpyAsync(m->h_scal, m->scal, 6 * sizeof(double), hipMemcpyDeviceToHost, st));
+    FM_HIP(m, hipStreamSynchronize(st));
+    const double n = (double)m->N;
+    metrics[0] = m->h_scal[0] / n;
+    metrics[1] = sqrt(m->h_scal[4] / n);
+    metrics[2] = m->h_scal[5] / n;
     return FM_OK;
 }
 
@@ -733,6 +780,7 @@ extern "C" int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float*
     hipStream_t st = (hipStream_t)hip_stream;
     FM_TRY(ensure_ws(m, p->K));
     m->aux_full = false;
+    m->aux_held = true;
     const FmAux x = fm_aux_layout(m, p->K);
     // a column without entries in a batch only takes the regulariser's step there: postponed
     // until the column next has entries, or the epoch ends
@@ -810,7 +858,7 @@ extern "C" int fm_get_aux(const fm_matrix* m, float* a, float* G, float* q, floa
 {
     if (m == nullptr) return FM_EINVAL;
     fm_matrix* mm = const_cast<fm_matrix*>(m);
-    if (m->wsK == 0) return fm_fail(mm, FM_ESTATE, "no aggregates held yet");
+    if (m->wsK == 0 || !m->aux_held) return fm_fail(mm, FM_ESTATE, "no aggregates held");
     if ((a != nullptr || q != nullptr) && !m->aux_full)
         return fm_fail(mm, FM_ESTATE, "a and q are only held after a stratified call");
     hipStream_t st = (hipStream_t)hip_stream;

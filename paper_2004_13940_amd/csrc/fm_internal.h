@@ -142,6 +142,7 @@ struct fm_matrix {
     double* scal = nullptr;     // device scalars: 0 loss, 1 sum r, 2 |w|^2, 3 |V|^2
     double* h_scal = nullptr;   // pinned mirror
     bool aux_full = false;      // a, q valid (not only G, r)
+    bool aux_held = false;      // the aggregate rows hold the result of a pass (fm_get_aux may read them)
     // side streams so that the LDS-bound and the memory-bound column kernels overlap
     hipStream_t side1 = nullptr, side2 = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join1 = nullptr, ev_join2 = nullptr;
@@ -280,6 +281,7 @@ int fm_launch_cols_flush(fm_matrix* m, const ColArgs& A, hipStream_t st);
 
 int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st);
 int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, int64_t stride, bool square, double* out1, hipStream_t st);
+int fm_reduce_eval(fm_matrix* m, const float* yhat, const float* y, int64_t n, int what, double* out1, hipStream_t st);
 int fm_bias_step(fm_matrix* m, float* w0, const double* rsum, float eta, float* grad_w0_out, hipStream_t st);
 
 // lanes per row/column group and floats per lane for a given K; false if K unsupported

@@ -66,6 +66,29 @@ __global__ __launch_bounds__(RED_THREADS) void k_reduce_stage2(const double* __r
     if (threadIdx.x == 0) out1[0] = t;
 }
 
+// what = 0: sum of (yhat - y)^2 ; what = 1: number of i with sign(yhat_i) == y_i (0 counts as +1)
+__global__ __launch_bounds__(RED_THREADS) void k_eval_stage1(const float* __restrict__ yhat,
+                                                             const float* __restrict__ y, int64_t n, int what,
+                                                             double* __restrict__ tmp)
+{
+    __shared__ double sh[RED_THREADS / 64];
+    const int64_t chunk = (n + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = (int64_t)blockIdx.x * chunk;
+    const int64_t hi = lo + chunk < n ? lo + chunk : n;
+    double s = 0.0;
+    for (int64_t i = lo + threadIdx.x; i < hi; i += RED_THREADS) {
+        const float f = yhat[i], t = y[i];
+        if (what == 0) {
+            const double d = (double)f - (double)t;
+            s += d * d;
+        } else {
+            s += ((f >= 0.f ? 1.f : -1.f) == t) ? 1.0 : 0.0;
+        }
+    }
+    const double tot = block_sum_1024(s, sh);
+    if (threadIdx.x == 0) tmp[blockIdx.x] = tot;
+}
+
 __global__ void k_bias(float* w0, const double* rsum, float eta, float* grad_out)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -94,6 +117,20 @@ int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, int64_t stride, bool 
     if (nb > RED_BLOCKS) nb = RED_BLOCKS;
     ProfScope ps(m, st, FMK_REDUCE);
     hipLaunchKernelGGL(k_reduce_stage1, dim3(nb), dim3(RED_THREADS), 0, st, x, n, stride, square ? 1 : 0, tmp);
+    FM_HIP(m, hipGetLastError());
+    hipLaunchKernelGGL(k_reduce_stage2, dim3(1), dim3(RED_THREADS), 0, st, (const double*)tmp, nb, out1);
+    FM_HIP(m, hipGetLastError());
+    return FM_OK;
+}
+
+int fm_reduce_eval(fm_matrix* m, const float* yhat, const float* y, int64_t n, int what, double* out1, hipStream_t st)
+{
+    double* tmp = m->scal + 8;
+    int nb = (int)((n + 16 * RED_THREADS - 1) / (16 * RED_THREADS));
+    if (nb < 1) nb = 1;
+    if (nb > RED_BLOCKS) nb = RED_BLOCKS;
+    ProfScope ps(m, st, FMK_REDUCE);
+    hipLaunchKernelGGL(k_eval_stage1, dim3(nb), dim3(RED_THREADS), 0, st, yhat, y, n, what, tmp);
     FM_HIP(m, hipGetLastError());
     hipLaunchKernelGGL(k_reduce_stage2, dim3(1), dim3(RED_THREADS), 0, st, (const double*)tmp, nb, out1);
     FM_HIP(m, hipGetLastError());

@@ -513,6 +513,57 @@ def test_minibatch_needs_its_partition():
     m.close()
 
 
+# ------------------------------------------- small dense shapes, metrics ----
+
+@pytest.mark.parametrize("name,mode", [("regression_513x8", "full"), ("regression_303x13", "stratified"),
+                                       ("classification_49990x22", "minibatch")])
+def test_small_dense_shapes_train_and_evaluate_like_the_oracle(name, mode):
+    """The three small shapes of the paper's data set table (synthetic content): some epochs on the
+    training rows, then mean loss, RMSE and accuracy on held-out rows, GPU against oracle."""
+    import torch
+    from paper_2004_13940_amd.workloads import make_small
+    B = _B()
+    tr, te = make_small(name)
+    X, Xt = (O.make_matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val) for wl in (tr, te))
+    m = B.Matrix(tr.N, tr.D, tr.rowptr, tr.col, tr.val)
+    mt = B.Matrix(te.N, te.D, te.rowptr, te.col, te.val)
+    m.fm_build_csc()
+    p = B.make_params(tr.K, tr.loss, tr.lambda_w, tr.lambda_v, tr.eta, tr.loss_scale, 1)
+    d_w0, d_w, d_V = dev_params(tr.w0, tr.w, tr.V)
+    d_y, d_yt = to_dev(tr.y), to_dev(te.y)
+    w0, w, V = float(tr.w0), tr.w.astype(np.float64), tr.V.astype(np.float64)
+    kw = oracle_kw(tr)
+    if mode == "stratified":
+        m.fm_partition(tr.P)
+    if mode == "minibatch":
+        m.fm_partition_batches(10)
+    first = None
+    for ep in range(8):
+        if mode == "full":
+            m.fm_sgd_epoch(p, d_y, d_w0, d_w, d_V)
+            w0, w, V, _ = O.full_epoch(X, tr.y, w0, w, V, **kw)
+        elif mode == "stratified":
+            m.fm_stratified_epoch(p, d_y, d_w0, d_w, d_V)
+            w0, w, V, _, _ = O.stratified_epoch(X, tr.y, w0, w, V, P=tr.P, final_objective=False, **kw)
+        else:
+            m.fm_minibatch_epoch(p, d_y, d_w0, d_w, d_V)
+            w0, w, V, _ = O.minibatch_epoch(X, tr.y, w0, w, V, B=10, final_objective=False, **kw)
+        got = mt.fm_evaluate(p, d_yt, d_w0, d_w, d_V)
+        want = O.evaluate(Xt, te.y, w0, w, V, tr.loss)
+        first = first or want
+        assert abs(got["mean_loss"] - want["mean_loss"]) <= REL_TOL * want["mean_loss"]
+        assert abs(got["rmse"] - want["rmse"]) <= REL_TOL * want["rmse"]
+        # a score within rounding of 0 may fall on either side
+        assert abs(got["accuracy"] - want["accuracy"]) <= 2.0 / te.N
+    _say(f"  {name} ({mode}): test metrics first {first} last {want}")
+    assert want["mean_loss"] < first["mean_loss"]
+    assert_close(d_V.cpu().numpy().reshape(tr.D, tr.K), V, "V")
+    with pytest.raises(B.FMError):  # the evaluation used the aggregate storage of its handle
+        mt.fm_get_aux(tr.K, r=torch.empty(te.N, device="cuda"))
+    m.close()
+    mt.close()
+
+
 def test_results_are_bit_reproducible():
     import torch
     B = _B()
