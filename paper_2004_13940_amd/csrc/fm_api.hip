@@ -386,7 +386,6 @@ static void fill_long(ColArgs& A, const LongIndex& li, int32_t s, bool strat)
     A.vlong = strat ? nullptr : li.vlong;
     A.nvlong = strat ? 0 : li.nvlong;
     A.vlong_items = fm_tune().vlong;
-    A.seg = fm_tune().seg;
     const int64_t s0 = strat ? li.h_short_off[s] : 0, s1 = strat ? li.h_short_off[s + 1] : li.nshort;
     A.short_col = li.short_col != nullptr ? li.short_col + s0 : nullptr;
     A.nshort = s1 - s0;

@@ -955,9 +955,7 @@ extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
         m->h_cb[b] = (int64_t)(((__int128)b * (__int128)m->D) / (__int128)P);
     }
     int64_t* d_cb = nullptr;
-    FM_TRY(fm_dev_alloc(m, (void**)&m->d_rb, (size_t)(P + 1) * sizeof(int64_t)));
     FM_TRY(fm_dev_alloc(m, (void**)&d_cb, (size_t)(P + 1) * sizeof(int64_t)));
-    FM_HIP(m, hipMemcpy(m->d_rb, m->h_rb.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
     std::vector<float> h_rho((size_t)P);
     for (int32_t b = 0; b < P; ++b) h_rho[b] = (float)((double)(m->h_rb[b + 1] - m->h_rb[b]) / (double)m->N);
     FM_TRY(fm_dev_alloc(m, (void**)&m->d_rho, (size_t)P * sizeof(float)));

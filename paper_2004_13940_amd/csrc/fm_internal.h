@@ -109,7 +109,6 @@ struct fm_matrix {
     // double partition and per-stratum matrices
     int32_t P = 0;
     std::vector<int64_t> h_rb, h_cb, h_cell_nnz, h_strat_nnz_off;  // bounds, P*P table, P+1 offsets
-    int64_t* d_rb = nullptr;
     float* d_rho = nullptr;        // [P] share |I_p|/N of the regulariser that a step on row block p applies
     int32_t* lazy_last = nullptr;  // [D] see ColArgs::lazy_last
     int64_t* s_rowptr = nullptr;  // [P*N+1] global offsets into s_col/s_val
@@ -162,8 +161,8 @@ struct fm_matrix {
 int fm_fail(fm_matrix* m, int code, const char* fmt, ...);
 int fm_dev_alloc(fm_matrix* m, void** p, size_t bytes);
 void fm_dev_free(fm_matrix* m, void* p);
-void fm_drop_workspace(fm_matrix* m);
-bool fm_side_streams(fm_matrix* m);  // creates them on first use; false if disabled (FM_SIDE_STREAMS=0)  // forces reallocation after the structures changed
+void fm_drop_workspace(fm_matrix* m);  // forces reallocation after the structures changed
+bool fm_side_streams(fm_matrix* m);    // creates them on first use; false if disabled (FM_SIDE_STREAMS=0)
 
 #define FM_HIP(m, expr)                                                                  \
     do {                                                                                 \
@@ -232,7 +231,6 @@ struct ColArgs {
     const float* G;
     int64_t gs, rs;  // row strides of G and r in floats
     int32_t packed;  // FM_PLANAR, or G rows are packed aggregate rows [G | r | a | q | pad]: FM_PACKED_*
-    int32_t seg;     // columns longer than this are split into items
     float* w;        // updated in place when update
     float* V;
     float* grad_w;   // !update: outputs (nullable)
