@@ -746,7 +746,7 @@ extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float
     // its cell, so the regulariser-only steps of the other columns can wait (not when every row
     // is refreshed from every column's change).
     const bool lazy = (!p->refresh_all_rows || p->stale_aux) && m->lazy_last != nullptr && fm_lazy_enabled();
-    if (lazy) FM_HIP(m, hipMemsetAsync(m->lazy_last, 0, (size_t)m->D * sizeof(int32_t), st));
+    if (lazy) FM_TRY(fm_fill_i32(m, m->lazy_last, m->D, 0, st));
     for (int32_t s = 0; s < m->P; ++s) FM_TRY(stratified_step(m, p, s, y, w0, w, V, lazy, st));
     if (lazy) {
         ColArgs F;
@@ -784,7 +784,7 @@ extern "C" int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float*
     // a column without entries in a batch only takes the regulariser's step there: postponed
     // until the column next has entries, or the epoch ends
     const bool lazy = fm_lazy_enabled();
-    if (lazy) FM_HIP(m, hipMemsetAsync(m->lazy_last, 0, (size_t)m->D * sizeof(int32_t), st));
+    if (lazy) FM_TRY(fm_fill_i32(m, m->lazy_last, m->D, 0, st));
     auto col_args = [&](int32_t b, ColArgs& A) {
         base_col_args(m, p, A);
         A.w = w;

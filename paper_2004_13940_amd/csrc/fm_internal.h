@@ -280,6 +280,7 @@ int fm_launch_cols_flush(fm_matrix* m, const ColArgs& A, hipStream_t st);
 int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st);
 int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, int64_t stride, bool square, double* out1, hipStream_t st);
 int fm_reduce_eval(fm_matrix* m, const float* yhat, const float* y, int64_t n, int what, double* out1, hipStream_t st);
+int fm_fill_i32(fm_matrix* m, int32_t* x, int64_t n, int32_t v, hipStream_t st);
 int fm_bias_step(fm_matrix* m, float* w0, const double* rsum, float eta, float* grad_w0_out, hipStream_t st);
 
 // lanes per row/column group and floats per lane for a given K; false if K unsupported

@@ -89,6 +89,12 @@ __global__ __launch_bounds__(RED_THREADS) void k_eval_stage1(const float* __rest
     if (threadIdx.x == 0) tmp[blockIdx.x] = tot;
 }
 
+__global__ void k_fill_i32(int32_t* __restrict__ x, int64_t n, int32_t v)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) x[i] = v;
+}
+
 __global__ void k_bias(float* w0, const double* rsum, float eta, float* grad_out)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -133,6 +139,17 @@ int fm_reduce_eval(fm_matrix* m, const float* yhat, const float* y, int64_t n, i
     hipLaunchKernelGGL(k_eval_stage1, dim3(nb), dim3(RED_THREADS), 0, st, yhat, y, n, what, tmp);
     FM_HIP(m, hipGetLastError());
     hipLaunchKernelGGL(k_reduce_stage2, dim3(1), dim3(RED_THREADS), 0, st, (const double*)tmp, nb, out1);
+    FM_HIP(m, hipGetLastError());
+    return FM_OK;
+}
+
+// A fill by a kernel (not a memset node), so that a caller may capture the epoch into a graph.
+int fm_fill_i32(fm_matrix* m, int32_t* x, int64_t n, int32_t v, hipStream_t st)
+{
+    if (n <= 0) return FM_OK;
+    const int64_t grid = (n + 255) / 256;
+    if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "fill too large");
+    hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)grid), dim3(256), 0, st, x, n, v);
     FM_HIP(m, hipGetLastError());
     return FM_OK;
 }
