@@ -326,12 +326,10 @@ bool fm_side_streams(fm_matrix* m)
 
 void fm_drop_workspace(fm_matrix* m)
 {
-    for (void* p : {(void*)m->aux, (void*)m->dV, (void*)m->dwn, (void*)m->part_acc, (void*)m->part_gs,
-                    (void*)m->row_part})
+    for (void* p : {(void*)m->aux, (void*)m->dV, (void*)m->dwn, (void*)m->part, (void*)m->row_part})
         fm_dev_free(m, p);
-    m->aux = m->dV = m->part_acc = m->row_part = nullptr;
+    m->aux = m->dV = m->part = m->row_part = nullptr;
     m->dwn = nullptr;
-    m->part_gs = nullptr;
     m->wsK = 0;
     m->aux_full = false;
     m->aux_held = false;
@@ -345,8 +343,8 @@ static int ensure_ws(fm_matrix* m, int32_t K)
     const size_t D = (size_t)m->D;
     FM_TRY(fm_dev_alloc(m, (void**)&m->aux, (size_t)std::max<int64_t>(fm_aux_floats(m->N, K), 1) * sizeof(float)));
     const int64_t items = std::max<int64_t>(std::max<int64_t>(m->lfull.nitems, m->lstrat.nitems), m->lbatch.nitems);
-    FM_TRY(fm_dev_alloc(m, (void**)&m->part_acc, (size_t)std::max<int64_t>(items, 1) * K * sizeof(float)));
-    FM_TRY(fm_dev_alloc(m, (void**)&m->part_gs, (size_t)std::max<int64_t>(items, 1) * sizeof(float2)));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->part,
+                        (size_t)std::max<int64_t>(items, 1) * (size_t)fm_part_stride(K) * sizeof(float)));
     FM_TRY(fm_dev_alloc(m, (void**)&m->row_part, (size_t)std::max<int64_t>(fm_rows_grid(m->N, K), 1) * 2 * sizeof(float)));
     if (m->P > 0) {
         FM_TRY(fm_dev_alloc(m, (void**)&m->dV, D * K * sizeof(float)));
@@ -530,8 +528,8 @@ static void base_col_args(fm_matrix* m, const fm_params* p, ColArgs& A)
     A.lambda_v = p->lambda_v;
     A.eta = p->eta;
     A.N = m->N;
-    A.part_acc = m->part_acc;
-    A.part_gs = m->part_gs;
+    A.part = m->part;
+    A.ps = fm_part_stride(p->K);
 }
 
 extern "C" int fm_gradient(fm_matrix* m, const fm_params* p, const float* r, const float* G, const float* w,

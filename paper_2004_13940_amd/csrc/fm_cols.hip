@@ -332,6 +332,36 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
     }
 }
 
+// Partial sums of item `it`: one row [acc_0..acc_{K-1} | gw | s2 | pad] of A.ps floats, a whole
+// number of 128-byte lines.  Items are written in processing order and read in column order, so
+// the rows are scattered: with float4 lanes the group writes the whole row, padding included, so
+// that no line is left partly written.
+template <int VEC, int L>
+__device__ __forceinline__ void store_partial(const ColArgs& A, int64_t it, int sub, int kbase, bool kact,
+                                              const float (&acc)[VEC], float gw, float s2)
+{
+    float* __restrict__ row = A.part + it * A.ps;
+    if constexpr (VEC == 4) {
+        for (int o = sub * 4; o < A.ps; o += L * 4) {
+            float z[4] = {0.f, 0.f, 0.f, 0.f};
+            if (o < A.K) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) z[t] = acc[t];  // first pass only: o == kbase
+            } else if (o == A.K) {
+                z[0] = gw;
+                z[1] = s2;
+            }
+            fm_store_vec<4>(row + o, z);
+        }
+    } else {
+        if (kact) fm_store_vec<VEC>(row + kbase, acc);
+        if (sub == 0) {
+            row[A.K] = gw;
+            row[A.K + 1] = s2;
+        }
+    }
+}
+
 // One group per item of a long column: partial sums only.  With an order array,
 // workgroup b takes its items from list b % FM_XCDS (the XCD it runs on).
 template <int VEC, int L, int PACKED>
@@ -385,10 +415,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
         accumulate_entries<VEC, L, PACKED, true>(A, beg, end, sub, kbase, kact, acc, gw, s2);
     gw = fm_group_sum<L>(gw);
     s2 = fm_group_sum<L>(s2);
-    if (valid) {
-        if (kact) fm_store_vec<VEC>(A.part_acc + it * A.K + kbase, acc);
-        if (sub == 0) A.part_gs[it] = make_float2(gw, s2);
-    }
+    if (valid) store_partial<VEC, L>(A, it, sub, kbase, kact, acc, gw, s2);
 }
 
 // Dense-ish columns, LDS-staged: workgroup t copies the aggregate rows [G | r] of row tile t
@@ -483,8 +510,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_tile(const ColArgs A)
         }
         gw = fm_group_sum<L>(gw);
         s2 = fm_group_sum<L>(s2);
-        if (kact) fm_store_vec<VEC>(A.part_acc + it * K + kbase, acc);
-        if (sub == 0) A.part_gs[it] = make_float2(gw, s2);
+        store_partial<4, L>(A, it, sub, kbase, kact, acc, gw, s2);
     }
 }
 
@@ -500,28 +526,30 @@ __device__ __forceinline__ void add_partials(const ColArgs& A, int64_t first, in
     int64_t it = first;
     for (; it + (U - 1) * step < last; it += U * step) {
         float p[U][VEC];
-        float2 gs[U];
+        float g0[U], g1[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            fm_load_vec<VEC>(A.part_acc + (it + u * step) * A.K + kb, p[u]);
-            gs[u] = A.part_gs[it + u * step];
+            const float* __restrict__ row = A.part + (it + u * step) * A.ps;
+            fm_load_vec<VEC>(row + kb, p[u]);
+            g0[u] = row[A.K];
+            g1[u] = row[A.K + 1];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int z = 0; z < VEC; ++z) acc[z] += (double)p[u][z];
-            gw += (double)gs[u].x;
-            s2 += (double)gs[u].y;
+            gw += (double)g0[u];
+            s2 += (double)g1[u];
         }
     }
     for (; it < last; it += step) {
+        const float* __restrict__ row = A.part + it * A.ps;
         float p[VEC];
-        fm_load_vec<VEC>(A.part_acc + it * A.K + kb, p);
+        fm_load_vec<VEC>(row + kb, p);
 #pragma unroll
         for (int z = 0; z < VEC; ++z) acc[z] += (double)p[z];
-        const float2 gs = A.part_gs[it];
-        gw += (double)gs.x;
-        s2 += (double)gs.y;
+        gw += (double)row[A.K];
+        s2 += (double)row[A.K + 1];
     }
 }
 

@@ -40,6 +40,8 @@ struct FmAux {
     int64_t gs, ss;
 };
 bool fm_aux_packed(int32_t K);
+// floats per row of partial sums [acc_0..acc_{K-1} | gw | s2 | pad]: a multiple of 32 (128 bytes)
+inline int64_t fm_part_stride(int32_t K) { return ((int64_t)K + 2 + 31) / 32 * 32; }
 // How the column kernels read the aggregate rows (ColArgs::packed).
 enum { FM_PLANAR = 0, FM_PACKED_LANE = 1, FM_PACKED_LOAD = 2 };
 // FM_PACKED_LANE when [G | r] of a packed row lies inside one 128-byte line, else FM_PACKED_LOAD
@@ -135,8 +137,7 @@ struct fm_matrix {
     float* aux = nullptr;   // aggregates, see fm_aux_layout
     float* dV = nullptr;    // [D*K] last step's change of V
     float2* dwn = nullptr;  // [D] (change of w_j, change of |v_j|^2)
-    float* part_acc = nullptr;  // [max items * K]
-    float2* part_gs = nullptr;  // [max items]
+    float* part = nullptr;      // [max items * part_stride(K)] partial sums of the items, see fm_part_stride
     float* row_part = nullptr;  // [2 * row blocks]: loss, sum r
     double* scal = nullptr;     // device scalars: 0 loss, 1 sum r, 2 |w|^2, 3 |V|^2
     double* h_scal = nullptr;   // pinned mirror
@@ -270,8 +271,8 @@ struct ColArgs {
     const int32_t* vlong;          // nullable: long columns finished by a whole workgroup
     int64_t nvlong;
     int32_t vlong_items;           // threshold that defines vlong
-    float* part_acc;                // indexed by absolute item id
-    float2* part_gs;
+    float* part;                    // rows [acc | gw | s2 | pad] of ps floats, indexed by absolute item id
+    int64_t ps;
 };
 int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st);
 // takes the postponed regulariser steps of every column up to stratum A.s (exclusive)
