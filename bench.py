@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=10_000_000, help="rows of the workload the oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stratified", action="store_true", help="also time fm_stratified_epoch (reported in extra)")
+    ap.add_argument("--parts", action="store_true",
+                    help="also time fm_forward and fm_gradient on their own (reported in extra)")
     ap.add_argument("--minibatch", type=int, default=0, metavar="B",
                     help="also time fm_minibatch_epoch over B row batches (reported in extra)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -162,6 +164,29 @@ def main():
         extra["stratified_ms_per_epoch"] = 1e3 * ts
         extra["stratified_nnz_per_s"] = wl.nnz / ts
         extra["P"] = wl.P
+
+    if args.parts:
+        # the two halves of the pass through their own entry points (dense caller-side arrays)
+        yhat = torch.empty(wl.N, device="cuda")
+        a = torch.empty(wl.N, device="cuda")
+        q = torch.empty(wl.N, device="cuda")
+        r = torch.empty(wl.N, device="cuda")
+        G = torch.empty(wl.N * wl.K, device="cuda")
+        gw = torch.empty(wl.D, device="cuda")
+        gV = torch.empty(wl.D * wl.K, device="cuda")
+        gw0 = torch.empty(1, device="cuda")
+        for name, fn in (("forward", lambda: m.fm_forward(p, y, w0, w, V, yhat=yhat, a=a, G=G, q=q, r=r)),
+                         ("gradient", lambda: m.fm_gradient(p, r, G, w, V, gw0, gw, gV))):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            tp = (time.perf_counter() - t0) / args.steps
+            extra[f"{name}_ms"] = 1e3 * tp
+            extra[f"{name}_nnz_per_s"] = wl.nnz / tp
+        del yhat, a, q, r, G, gw, gV
 
     if args.minibatch > 0:
         m.fm_partition_batches(args.minibatch)

@@ -552,10 +552,24 @@ extern "C" int fm_gradient(fm_matrix* m, const fm_params* p, const float* r, con
     A.ptr = m->colptr;
     A.row = m->crow;
     A.val = m->cval;
-    A.r = r;
-    A.G = G;
-    A.gs = p->K;
-    A.rs = 1;
+    if (fm_aux_packed(p->K)) {
+        // one streaming pass puts r and G into packed aggregate rows, so that every gather of the
+        // column pass is one request (and dense-ish columns can be staged through LDS)
+        FM_TRY(fm_pack_aux(m, r, G, st));
+        m->aux_held = true;
+        m->aux_full = false;
+        const FmAux x = fm_aux_layout(m, p->K);
+        A.r = x.r;
+        A.G = x.G;
+        A.gs = x.gs;
+        A.rs = x.ss;
+        A.packed = fm_cols_packed_mode(p->K);
+    } else {
+        A.r = r;
+        A.G = G;
+        A.gs = p->K;
+        A.rs = 1;
+    }
     A.w = const_cast<float*>(w);
     A.V = const_cast<float*>(V);
     A.grad_w = grad_w;

@@ -220,6 +220,7 @@ struct RowArgs {
 };
 int fm_launch_rows(fm_matrix* m, const RowArgs& A, bool refresh, hipStream_t st);
 int64_t fm_rows_grid(int64_t N, int32_t K);
+int fm_pack_aux(fm_matrix* m, const float* r, const float* G, hipStream_t st);  // packed layout only
 int fm_unpack_aux(fm_matrix* m, float* a, float* G, float* q, float* r, hipStream_t st);
 
 struct ColArgs {

@@ -247,6 +247,38 @@ __global__ void k_unpack_aux(const FmAux x, int64_t N, int32_t K, float* a, floa
 }
 }  // namespace
 
+namespace {
+// Caller-side dense r[N], G[N x K] into the packed aggregate rows [G | r | 0 | 0 | pad], one float4
+// per thread, whole rows written.
+__global__ void k_pack_aux(const FmAux x, int64_t N, int32_t K, const float* __restrict__ r,
+                           const float* __restrict__ G)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t per = x.gs / 4;  // float4 per row
+    if (t >= N * per) return;
+    const int64_t i = t / per;
+    const int o = (int)(t % per) * 4;
+    float z[4] = {0.f, 0.f, 0.f, 0.f};
+    if (o < K)
+        fm_load_vec<4>(G + i * K + o, z);
+    else if (o == K)
+        z[0] = r[i];
+    fm_store_vec<4>(x.G + i * x.gs + o, z);
+}
+}  // namespace
+
+int fm_pack_aux(fm_matrix* m, const float* r, const float* G, hipStream_t st)
+{
+    const FmAux x = fm_aux_layout(m, m->wsK);
+    const int64_t total = m->N * (x.gs / 4);
+    if (total <= 0) return FM_OK;
+    const int64_t grid = (total + 255) / 256;
+    if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "aggregate copy too large");
+    hipLaunchKernelGGL(k_pack_aux, dim3((unsigned)grid), dim3(256), 0, st, x, m->N, m->wsK, r, G);
+    FM_HIP(m, hipGetLastError());
+    return FM_OK;
+}
+
 int fm_unpack_aux(fm_matrix* m, float* a, float* G, float* q, float* r, hipStream_t st)
 {
     const int64_t total = m->N * (int64_t)(m->wsK + 3);
