@@ -619,9 +619,8 @@ static int build_short_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_tota
 int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
                         LongIndex* out, hipStream_t st)
 {
-    // the launches of one stratum are small: shorter items give them more groups to spread over
-    const int seg = fm_tune().seg_strat;
-    FM_TRY(build_short_list(m, ptr, ncols_total, D, nstrata, seg, out, st));
+    out->nshort = 0;
+    out->h_short_off.assign(nstrata + 1, 0);
     out->nlong = out->nitems = 0;
     out->h_long_off.assign(nstrata + 1, 0);
     out->h_item_off.assign(nstrata + 1, 0);
@@ -630,6 +629,23 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
     int64_t *tl = nullptr, *ti = nullptr;
     FM_TRY(fm_dev_alloc(m, (void**)&tl, (size_t)(ntiles + 1) * sizeof(int64_t)));
     FM_TRY(fm_dev_alloc(m, (void**)&ti, (size_t)(ntiles + 1) * sizeof(int64_t)));
+    // Item length.  The launches of one stratum are small: when full-length items would leave a
+    // stratum with too few of them to fill the chip, they are halved (more groups to spread over,
+    // at the price of more partial sums); a fixed FM_SEG_STRAT or fm_set_tuning overrides this.
+    int seg = fm_tune().seg_strat;
+    if (seg <= 0) {
+        seg = fm_tune().seg;
+        FM_HIP(m, hipMemsetAsync(ti, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
+        FM_HIP(m, hipMemsetAsync(tl, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
+        hipLaunchKernelGGL(k_long_count, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, seg, tl, ti);
+        FM_HIP(m, hipGetLastError());
+        FM_TRY(fm_scan_exclusive_i64(m, ti, ntiles + 1, st));
+        int64_t n_full = 0;
+        FM_HIP(m, hipMemcpyAsync(&n_full, ti + ntiles, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+        FM_HIP(m, hipStreamSynchronize(st));
+        if (n_full / nstrata < 12288 && seg > 128) seg = 128;
+    }
+    FM_TRY(build_short_list(m, ptr, ncols_total, D, nstrata, seg, out, st));
     FM_HIP(m, hipMemsetAsync(tl, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
     FM_HIP(m, hipMemsetAsync(ti, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
     hipLaunchKernelGGL(k_long_count, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, seg, tl, ti);
@@ -691,7 +707,7 @@ static FmTune& tune_mut()
                        env_int("FM_MIN_PANELS", 8 * FM_XCDS, 1, 1 << 30), env_int("FM_TILE", 512, 64, 1 << 20),
                        env_int("FM_TILE_MIN", 8, 0, 1 << 20), env_int("FM_TILE_SEG", 256, 16, 1 << 20), 0};
     static const bool once = [] {
-        t.seg_strat = env_int("FM_SEG_STRAT", t.seg < 128 ? t.seg : 128, 16, 1 << 20);
+        t.seg_strat = env_int("FM_SEG_STRAT", 0, 0, 1 << 20);  // 0: chosen per matrix
         return true;
     }();
     (void)once;

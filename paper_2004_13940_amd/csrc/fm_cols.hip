@@ -72,7 +72,7 @@ struct StepFactors {
     const float* rho;
     float lv, lw, eta;
     int32_t P;
-    bool batch;  // step t acts on row block t, the next step on block t+1
+    bool batch;  // step t acts on row block t, the next step on block t+1 (else on the block before, cyclically)
     __device__ __forceinline__ float v(int32_t p) const
     {
         return tab != nullptr ? tab[p] : step_factor(rho != nullptr ? rho[p] : 1.f, lv, eta);
@@ -89,11 +89,12 @@ struct StepFactors {
         int32_t p = (qb - t) % P;
         return p < 0 ? p + P : p;
     }
+    // (two operations: this sits in the loop over postponed steps; with P == 0 the factors ignore p,
+    // and a walk over batches ends before p reaches P)
     __device__ __forceinline__ int32_t next(int32_t p) const
     {
-        if (P <= 0) return 0;
-        if (batch) return p + 1 < P ? p + 1 : p;
-        return p == 0 ? P - 1 : p - 1;
+        p += batch ? 1 : -1;
+        return p < 0 ? P - 1 : p;
     }
 };
 
@@ -757,7 +758,7 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     // memory-bound ones; the finish kernels wait for all three.
     const int64_t ntile_items = A.order != nullptr ? A.nitems - A.list_off[FM_XCDS] : 0;
     // (not while per-kernel timing is on: each kernel is then timed alone on the launch stream)
-    const bool side = ntile_items > 0 && !m->prof && fm_side_streams(m);
+    const bool side = (ntile_items > 0 || (A.nitems > 0 && A.nshort > 0)) && !m->prof && fm_side_streams(m);
     hipStream_t s_cols = st, s_tile = st;
     if (side) {
         FM_HIP(m, hipEventRecord(m->ev_fork, st));

@@ -28,7 +28,7 @@ struct FmTune {
     int tile;             // rows per LDS tile of the kernel for dense-ish columns
     int tile_min;         // a column is dense-ish if it averages this many entries per tile (0: none)
     int tile_seg;         // entries per item inside a tile
-    int seg_strat;        // `seg` of the per-stratum matrices (FM_SEG_STRAT; fm_set_tuning sets both)
+    int seg_strat;        // `seg` of the per-stratum matrices (FM_SEG_STRAT; fm_set_tuning sets both); 0: automatic
 };
 const FmTune& fm_tune();
 
