@@ -265,23 +265,24 @@ static int check_params(fm_matrix* m, const fm_params* p)
     return FM_OK;
 }
 
-// Packed rows are the default whenever a row is a whole number of float4 (K % 4 == 0) and
-// a column group of 64 lanes can cover it; FM_AUX_PACKED=0 selects the planar layout.
+// Packed rows are used when [G | r] of a row fits one 128-byte line (a whole number of float4,
+// K <= 28): a column-side gather is then a single request.  For larger K a row of G is one or
+// more whole lines by itself and the planar layout gathers fewer of them.  FM_AUX_PACKED=0
+// selects the planar layout always.
 bool fm_aux_packed(int32_t K)
 {
     static const bool allow = [] {
         const char* e = getenv("FM_AUX_PACKED");
         return !(e != nullptr && *e == '0');
     }();
-    return allow && K % 4 == 0 && K <= 252;
+    return allow && K % 4 == 0 && K + 1 <= 32;
 }
 
 static int64_t packed_stride(int32_t K) { return ((int64_t)K + 3 + 15) / 16 * 16; }
 
 int fm_cols_packed_mode(int32_t K)
 {
-    if (!fm_aux_packed(K)) return FM_PLANAR;
-    return K + 1 <= 32 ? FM_PACKED_LANE : FM_PACKED_LOAD;
+    return fm_aux_packed(K) ? FM_PACKED_LANE : FM_PLANAR;
 }
 
 int64_t fm_aux_floats(int64_t N, int32_t K) { return fm_aux_packed(K) ? N * packed_stride(K) : N * ((int64_t)K + 3); }

@@ -27,17 +27,13 @@ __device__ __forceinline__ void accumulate_entries(const ColArgs& A, int64_t beg
     if constexpr (PACKED == FM_PACKED_LANE) {
         // every lane reads inside the row: lanes past the scalars re-read its last VEC floats
         const int last = (int)A.gs - VEC;
-        fm_col_accumulate_packed<VEC, L, NT, true, LEAN ? 1 : FmChunk<L>::CH>(
-            A.row, A.val, beg, end, A.G, A.gs, sub, kbase < last ? kbase : last, A.K, acc, gw, s2);
-    } else if constexpr (PACKED == FM_PACKED_LOAD) {
-        // idle lanes of a group wider than K/VEC read a valid slice and discard it
-        fm_col_accumulate_packed<VEC, L, NT, false, LEAN ? 1 : FmChunk<L>::CH>(
-            A.row, A.val, beg, end, A.G, A.gs, sub, kact ? kbase : 0, A.K, acc, gw, s2);
+        fm_col_accumulate_packed<VEC, L, NT>(A.row, A.val, beg, end, A.G, A.gs, sub, kbase < last ? kbase : last,
+                                             A.K / VEC, acc, gw, s2);
     } else {
         const float* __restrict__ r = A.r;
         const int64_t rs = A.rs;
         float unused = 0.f;
-        fm_gather_accumulate<VEC, L, false>(A.row, A.val, beg, end, A.G, A.gs, sub, kact ? kbase : 0, acc, unused,
+        fm_gather_accumulate<VEC, L, false, LEAN ? 1 : FmChunk<L>::CH>(A.row, A.val, beg, end, A.G, A.gs, sub, kact ? kbase : 0, acc, unused,
                                             [&](int i, float x) {
                                                 const float xr = x * r[(int64_t)i * rs];
                                                 gw += xr;
@@ -419,8 +415,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_long(const ColArgs A)
     if (valid) store_partial<VEC, L>(A, it, sub, kbase, kact, acc, gw, s2);
 }
 
-// Dense-ish columns, LDS-staged: workgroup t copies the aggregate rows [G | r] of row tile t
-// (tile_rows rows of packed aggregate rows) into LDS once, then its groups walk the tile's items
+// Dense-ish columns, LDS-staged: workgroup t copies G and r of the tile_rows rows of row tile t
+// (packed or planar aggregates) into LDS once, then its groups walk the tile's items
 // (pieces of dense-ish columns whose rows lie inside the tile) and gather G and r from LDS.
 // One partial sum per item, as in k_cols_long.  L lanes of VEC=4 latent dimensions per group.
 template <int L>
@@ -432,13 +428,14 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_tile(const ColArgs A)
     const int K = A.K;
     const int S = K;
     float* __restrict__ tile_r = tile + A.tile_rows * K;
-    const int chunks = K / VEC + 1;  // float4 chunks read per row (the last one holds r, a, q)
+    const int chunks = K / VEC;  // float4 chunks of G per row
     const int64_t t = blockIdx.x;
     const int64_t row0 = t * A.tile_rows;
     const int64_t nrows = (A.N - row0) < A.tile_rows ? (A.N - row0) : A.tile_rows;
     {   // copy in batches of eight float4 per thread: all loads of a batch are issued before the first store
         const int total = (int)nrows * chunks;
         const float* __restrict__ src = A.G + row0 * A.gs;
+        const float* __restrict__ rsrc = A.r + row0 * A.rs;
         constexpr int U = 8;
         for (int c0 = threadIdx.x; c0 < total; c0 += U * FM_BLOCK) {
             float4 v[U];
@@ -455,12 +452,11 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_tile(const ColArgs A)
             for (int u = 0; u < U; ++u) {
                 if (dst[u] < 0) continue;
                 const int rr = dst[u] >> 8, ch = dst[u] & 255;
-                if (ch < chunks - 1)
-                    *reinterpret_cast<float4*>(tile + rr * S + ch * VEC) = v[u];
-                else
-                    tile_r[rr] = v[u].x;
+                *reinterpret_cast<float4*>(tile + rr * S + ch * VEC) = v[u];
             }
         }
+        // r of the rows (a loop of its own: no branch between the loads of a batch above)
+        for (int rr = threadIdx.x; rr < (int)nrows; rr += FM_BLOCK) tile_r[rr] = rsrc[(int64_t)rr * A.rs];
     }
     __syncthreads();
 
@@ -665,7 +661,8 @@ inline bool launch_tile(fm_matrix* m, const ColArgs& A, hipStream_t st)
     (void)m;
     if (A.ntiles <= 0 || A.ntiles > 0x7fffffffLL || A.K % 4 != 0) return false;
     const size_t lds = (size_t)A.tile_rows * (size_t)(A.K + 1) * sizeof(float);
-    if (lds > 150 * 1024) return false;
+    // at least two workgroups per compute unit, or the copy of one tile cannot overlap the work on another
+    if (lds > 72 * 1024) return false;
     int need = A.K / 4, l = 1;
     while (l < need) l <<= 1;
     switch (l) {
@@ -770,7 +767,7 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     if (ntile_items > 0) {  // items of dense-ish columns, sorted by row tile
         ProfScope ps(m, s_tile, FMK_COLS_TILE);
         bool staged = false;
-        if constexpr (PACKED != FM_PLANAR) staged = launch_tile(m, A, s_tile);
+        if constexpr (VEC == 4) staged = launch_tile(m, A, s_tile);
         if (!staged) {  // same items through global memory
             ColArgs B = A;
             B.lin_mode = 1;
@@ -880,7 +877,6 @@ int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     int vec, lanes;
     if (!cols_shape(A.K, A.packed, &vec, &lanes)) return fm_fail(m, FM_EINVAL, "unsupported K=%d", A.K);
     if (A.packed == FM_PACKED_LANE) return launch_cols_v<4, FM_PACKED_LANE>(m, lanes, A, update, st);
-    if (A.packed == FM_PACKED_LOAD) return launch_cols_v<4, FM_PACKED_LOAD>(m, lanes, A, update, st);
     switch (vec) {
         case 4: return launch_cols_v<4, FM_PLANAR>(m, lanes, A, update, st);
         case 2: return launch_cols_v<2, FM_PLANAR>(m, lanes, A, update, st);

@@ -163,7 +163,10 @@ __device__ __forceinline__ void fm_gather_accumulate(const int32_t* __restrict__
                                                      Own&& own)
 {
     int64_t e = beg;
-    for (; e + L * CH <= end; e += L * CH) {
+    // the lean form (CH == 1) of wide groups takes every entry through the four-at-a-time loop below:
+    // few registers, so that more rows or columns are in flight
+    constexpr bool CHUNKS = !(CH == 1 && L >= 16);
+    for (; CHUNKS && e + L * CH <= end; e += L * CH) {
         int ix[CH];
         float mu[CH];
 #pragma unroll
@@ -213,53 +216,39 @@ __device__ __forceinline__ void fm_gather_accumulate(const int32_t* __restrict__
     }
 }
 
-// Column-side variant for packed aggregate rows [G_0..G_{K-1} | r | a | q | pad].  A group of
-// L lanes reads the K latent values of a row, VEC per lane, and the row's r in one of two ways:
-//   SL (scalar lane): the row [G | r] lies inside one 128-byte line, the group is one lane wider
-//      than the latent values need, and lane rl = K/VEC picks up r with the same request;
-//   otherwise every lane also loads r (same or next line), and the group is K/VEC lanes wide.
+// Column-side variant for packed aggregate rows [G_0..G_{K-1} | r | a | q | pad] whose [G | r] lies
+// inside one 128-byte line: a group of L lanes, one lane wider than the latent values need, reads
+// the row with a single request, and lane rl = K/VEC picks up r for the others.
 // Per entry (row i, value x):
 //   acc[z] += x r_i G_i[kb+z]     on the latent lanes,
-//   gw += x r_i, s2 += x^2 r_i    on one lane of the group (the others keep 0).
-template <int VEC, bool NT, bool SL>
-__device__ __forceinline__ void fm_load_row_packed(const float* __restrict__ row, int kb, int K, float (&g)[VEC],
-                                                   float& r)
-{
-    if constexpr (NT) {
-        fm_load_vec_nt<VEC>(row + kb, g);
-        if constexpr (!SL) r = __builtin_nontemporal_load(row + K);
-    } else {
-        fm_load_vec<VEC>(row + kb, g);
-        if constexpr (!SL) r = row[K];
-    }
-}
-
-template <int VEC, int L, bool NT, bool SL, int S, int MAXB = 16, class IX, class XV>
+//   gw += x r_i, s2 += x^2 r_i    on the scalar lane (the others keep 0).
+template <int VEC, int L, bool NT, int S, int MAXB = 16, class IX, class XV>
 __device__ __forceinline__ void fm_gather_slots_packed(const IX& ix, const XV& xv, const float* __restrict__ src,
-                                                       int64_t stride, int kb, int K, bool sum_lane,
+                                                       int64_t stride, int kb, int rl, bool scalar_lane,
                                                        float (&acc)[VEC], float& gw, float& s2)
 {
     constexpr int B = S < MAXB ? S : MAXB;
     fm_static_for<0, S / B>([&](auto bc) {
         constexpr int B0 = decltype(bc)::value * B;
         float g[B][VEC];
-        float rr[SL ? 1 : B];
         float xt[B];
         fm_static_for<0, B>([&](auto sc) {
             constexpr int s = B0 + decltype(sc)::value;
             constexpr int u = s / L, T = s % L;
             const int it = fm_bcast_i<L, T>(ix[u]);
             xt[s - B0] = fm_bcast_f<L, T>(xv[u]);
-            fm_load_row_packed<VEC, NT, SL>(src + (int64_t)it * stride, kb, K, g[s - B0], rr[SL ? 0 : s - B0]);
+            if constexpr (NT)
+                fm_load_vec_nt<VEC>(src + (int64_t)it * stride + kb, g[s - B0]);
+            else
+                fm_load_vec<VEC>(src + (int64_t)it * stride + kb, g[s - B0]);
         });
 #pragma unroll
         for (int s = 0; s < B; ++s) {
-            float r;
-            if constexpr (SL) r = __shfl(g[s][0], K / VEC, L); else r = rr[s];
+            const float r = __shfl(g[s][0], rl, L);
             const float m = xt[s] * r;
 #pragma unroll
             for (int z = 0; z < VEC; ++z) acc[z] += m * g[s][z];
-            if (sum_lane) {
+            if (scalar_lane) {
                 gw += m;
                 s2 += xt[s] * m;
             }
@@ -267,19 +256,18 @@ __device__ __forceinline__ void fm_gather_slots_packed(const IX& ix, const XV& x
     });
 }
 
-// kb: for SL the caller clamps it so that lanes past the scalars re-read the row's last VEC
-// floats; otherwise idle lanes pass 0.  Both discard their acc.
-template <int VEC, int L, bool NT, bool SL, int CH = FmChunk<L>::CH>
+// kb: the caller clamps it so that lanes past the scalars re-read the row's last VEC floats
+// (they discard their acc).
+template <int VEC, int L, bool NT>
 __device__ __forceinline__ void fm_col_accumulate_packed(const int32_t* __restrict__ idx, const float* __restrict__ val,
                                                          int64_t beg, int64_t end, const float* __restrict__ src,
-                                                         int64_t stride, int sub, int kb, int K, float (&acc)[VEC],
+                                                         int64_t stride, int sub, int kb, int rl, float (&acc)[VEC],
                                                          float& gw, float& s2)
 {
-    const bool sum_lane = SL ? sub == K / VEC : sub == 0;
+    constexpr int CH = FmChunk<L>::CH;
+    const bool scalar_lane = sub == rl;
     int64_t e = beg;
-    // the lean form of wide groups takes every entry through the four-at-a-time loop below
-    constexpr bool CHUNKS = !(CH == 1 && L >= 16);
-    for (; CHUNKS && e + L * CH <= end; e += L * CH) {
+    for (; e + L * CH <= end; e += L * CH) {
         int ix[CH];
         float xv[CH];
 #pragma unroll
@@ -288,9 +276,7 @@ __device__ __forceinline__ void fm_col_accumulate_packed(const int32_t* __restri
             ix[u] = idx[my];
             xv[u] = val[my];
         }
-        // (a single slot per step is the lean form: at most 8 gathers in flight there)
-        fm_gather_slots_packed<VEC, L, NT, SL, CH * L, CH == 1 ? 8 : 16>(ix, xv, src, stride, kb, K, sum_lane, acc, gw,
-                                                                         s2);
+        fm_gather_slots_packed<VEC, L, NT, CH * L>(ix, xv, src, stride, kb, rl, scalar_lane, acc, gw, s2);
     }
     for (; e < end; e += L) {
         const int64_t want = e + sub;
@@ -301,13 +287,12 @@ __device__ __forceinline__ void fm_col_accumulate_packed(const int32_t* __restri
         ix[0] = idx[my];
         xv[0] = has ? val[my] : 0.f;
         if constexpr (L <= 4) {
-            fm_gather_slots_packed<VEC, L, NT, SL, L>(ix, xv, src, stride, kb, K, sum_lane, acc, gw, s2);
+            fm_gather_slots_packed<VEC, L, NT, L>(ix, xv, src, stride, kb, rl, scalar_lane, acc, gw, s2);
         } else {
             // wide groups: only the entries that exist, four gathers at a time
             const int nv = (int)((end - e) < L ? (end - e) : L);
             for (int t0 = 0; t0 < nv; t0 += 4) {
                 float g[4][VEC];
-                float rr[4];
                 float xt[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
@@ -315,15 +300,18 @@ __device__ __forceinline__ void fm_col_accumulate_packed(const int32_t* __restri
                     const int it = __shfl(ix[0], t, L);
                     const float x = __shfl(xv[0], t, L);
                     xt[u] = t0 + u < nv ? x : 0.f;
-                    fm_load_row_packed<VEC, NT, SL>(src + (int64_t)it * stride, kb, K, g[u], rr[u]);
+                    if constexpr (NT)
+                        fm_load_vec_nt<VEC>(src + (int64_t)it * stride + kb, g[u]);
+                    else
+                        fm_load_vec<VEC>(src + (int64_t)it * stride + kb, g[u]);
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    if constexpr (SL) rr[u] = __shfl(g[u][0], K / VEC, L);
-                    const float m = xt[u] * rr[u];
+                    const float r = __shfl(g[u][0], rl, L);
+                    const float m = xt[u] * r;
 #pragma unroll
                     for (int z = 0; z < VEC; ++z) acc[z] += m * g[u][z];
-                    if (sum_lane) {
+                    if (scalar_lane) {
                         gw += m;
                         s2 += xt[u] * m;
                     }

@@ -32,9 +32,9 @@ struct FmTune {
 };
 const FmTune& fm_tune();
 
-// Where the handle keeps the aggregates.  Packed: one row [G_0..G_{K-1}, r, a, q, pad] per
-// example with a stride that is a multiple of 16 floats.  Planar (default): G dense [N x K],
-// then r, a, q as dense vectors.
+// Where the handle keeps the aggregates.  Packed (when [G | r] fits one 128-byte line: K % 4 == 0,
+// K <= 28): one row [G_0..G_{K-1}, r, a, q, pad] per example with a stride that is a multiple of
+// 16 floats.  Planar otherwise: G dense [N x K], then r, a, q as dense vectors.
 struct FmAux {
     float *G, *r, *a, *q;
     int64_t gs, ss;
@@ -43,8 +43,7 @@ bool fm_aux_packed(int32_t K);
 // floats per row of partial sums [acc_0..acc_{K-1} | gw | s2 | pad]: a multiple of 32 (128 bytes)
 inline int64_t fm_part_stride(int32_t K) { return ((int64_t)K + 2 + 31) / 32 * 32; }
 // How the column kernels read the aggregate rows (ColArgs::packed).
-enum { FM_PLANAR = 0, FM_PACKED_LANE = 1, FM_PACKED_LOAD = 2 };
-// FM_PACKED_LANE when [G | r] of a packed row lies inside one 128-byte line, else FM_PACKED_LOAD
+enum { FM_PLANAR = 0, FM_PACKED_LANE = 1 };
 int fm_cols_packed_mode(int32_t K);
 int64_t fm_aux_floats(int64_t N, int32_t K);
 struct fm_matrix;
@@ -232,7 +231,7 @@ struct ColArgs {
     const float* r;
     const float* G;
     int64_t gs, rs;  // row strides of G and r in floats
-    int32_t packed;  // FM_PLANAR, or G rows are packed aggregate rows [G | r | a | q | pad]: FM_PACKED_*
+    int32_t packed;  // FM_PLANAR, or FM_PACKED_LANE: G rows are packed aggregate rows [G | r | a | q | pad]
     float* w;        // updated in place when update
     float* V;
     float* grad_w;   // !update: outputs (nullable)
