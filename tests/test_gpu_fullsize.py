@@ -106,3 +106,35 @@ def test_full_size_stratum_on_sampled_cells(full):
     assert_close(ga.cpu().numpy(), fa, "a after the epoch")
     assert abs(obj[0] - wl.loss_scale * fl.sum()) <= REL_TOL * wl.loss_scale * fl.sum()
     assert np.isfinite(sum(obj)) and sum(obj) < np.log(2.0)  # the epoch made progress from the start value
+
+
+def test_full_size_minibatch_epoch_and_gradient_entry_point(full):
+    """Three row batches at full size: every output against the oracle; then fm_gradient (which packs
+    the caller's r, G into aggregate rows first) on a sample of columns of each class."""
+    import torch
+    wl, m, X, B = full
+    p = B.make_params(wl.K, wl.loss, wl.lambda_w, wl.lambda_v, wl.eta, wl.loss_scale, wl.update_w0)
+    d_w0, d_w, d_V = dev_params(wl.w0, wl.w, wl.V)
+    d_y = to_dev(wl.y)
+    nb = 3
+    m.fm_partition_batches(nb)
+    obj = m.fm_minibatch_epoch(p, d_y, d_w0, d_w, d_V, want_objective=True)
+    kw = dict(loss=wl.loss, s=wl.loss_scale, lambda_w=wl.lambda_w, lambda_v=wl.lambda_v, eta=wl.eta,
+              update_w0=bool(wl.update_w0))
+    w0, w, V, wobj = O.minibatch_epoch(X, wl.y, float(wl.w0), wl.w, wl.V, B=nb, **kw)
+    _say(f"full-size mini-batch epoch: objective gpu {sum(obj):.8f} oracle {sum(wobj):.8f}")
+    assert abs(obj[0] - wobj[0]) <= REL_TOL * abs(wobj[0])
+    assert_close(d_w.cpu().numpy(), w, "w after the full-size mini-batch epoch")
+    assert_close(d_V.cpu().numpy().reshape(wl.D, wl.K), V, "V after the full-size mini-batch epoch")
+    assert abs(d_w0.item() - w0) <= REL_TOL * max(abs(w0), 1e-3)
+    # gradient entry point at the new parameters
+    a, G, q, yh = O.forward(X, w0, w, V)
+    _, r = O.loss_multiplier(wl.loss, wl.loss_scale, yh, wl.y)
+    r32, G32, w32, V32 = (x.astype(np.float32) for x in (r, G, w, V))  # the same inputs on both sides
+    gw0, gw, gV = O.gradient(X, r32, G32, w32, V32, wl.lambda_w, wl.lambda_v)
+    del a, q, yh, r, G
+    o_w0, o_w, o_V = torch.empty(1, device="cuda"), torch.empty(wl.D, device="cuda"), torch.empty(wl.D * wl.K, device="cuda")
+    m.fm_gradient(p, to_dev(r32), to_dev(G32.reshape(-1)), to_dev(w32), to_dev(V32.reshape(-1)), o_w0, o_w, o_V)
+    assert_close(o_w.cpu().numpy(), gw, "grad_w at full size")
+    assert_close(o_V.cpu().numpy().reshape(wl.D, wl.K), gV, "grad_V at full size")
+    assert abs(o_w0.item() - gw0) <= REL_TOL * max(abs(gw0), 1e-6)
