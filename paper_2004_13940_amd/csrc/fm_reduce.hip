@@ -20,17 +20,38 @@ __device__ __forceinline__ double block_sum_1024(double v, double* sh)
     return t;  // valid in thread 0
 }
 
-// part holds nblocks interleaved pairs (x0,x1); out2 receives the two totals.
-__global__ __launch_bounds__(RED_THREADS) void k_reduce_pairs(const float* __restrict__ part, int64_t nblocks,
-                                                              double* __restrict__ out2)
+// part holds n interleaved pairs (x0,x1).  Stage 1: workgroup b sums its contiguous share of the
+// pairs into tmp[2b], tmp[2b+1]; stage 2: one workgroup adds the nb partial pairs into out2.
+__global__ __launch_bounds__(RED_THREADS) void k_reduce_pairs(const float* __restrict__ part, int64_t n,
+                                                              double* __restrict__ tmp)
 {
     __shared__ double sh[RED_THREADS / 64];
+    const int64_t chunk = (n + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = (int64_t)blockIdx.x * chunk;
+    const int64_t hi = lo + chunk < n ? lo + chunk : n;
     double s0 = 0.0, s1 = 0.0;
     const float2* p2 = reinterpret_cast<const float2*>(part);
-    for (int64_t i = threadIdx.x; i < nblocks; i += RED_THREADS) {
+    for (int64_t i = lo + threadIdx.x; i < hi; i += RED_THREADS) {
         const float2 v = p2[i];
         s0 += (double)v.x;
         s1 += (double)v.y;
+    }
+    const double t0 = block_sum_1024(s0, sh);
+    const double t1 = block_sum_1024(s1, sh);
+    if (threadIdx.x == 0) {
+        tmp[2 * blockIdx.x] = t0;
+        tmp[2 * blockIdx.x + 1] = t1;
+    }
+}
+
+__global__ __launch_bounds__(RED_THREADS) void k_reduce_pairs_final(const double* __restrict__ tmp, int nb,
+                                                                    double* __restrict__ out2)
+{
+    __shared__ double sh[RED_THREADS / 64];
+    double s0 = 0.0, s1 = 0.0;
+    for (int i = threadIdx.x; i < nb; i += RED_THREADS) {
+        s0 += tmp[2 * i];
+        s1 += tmp[2 * i + 1];
     }
     const double t0 = block_sum_1024(s0, sh);
     const double t1 = block_sum_1024(s1, sh);
@@ -108,8 +129,15 @@ __global__ void k_bias(float* w0, const double* rsum, float eta, float* grad_out
 
 int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st)
 {
+    // scal[8..8+RED_BLOCKS) is the stage-1 scratch (pairs: at most RED_BLOCKS / 2 workgroups)
+    double* tmp = m->scal + 8;
+    int nb = (int)((nblocks + 4 * RED_THREADS - 1) / (4 * RED_THREADS));
+    if (nb < 1) nb = 1;
+    if (nb > RED_BLOCKS / 2) nb = RED_BLOCKS / 2;
     ProfScope ps(m, st, FMK_REDUCE);
-    hipLaunchKernelGGL(k_reduce_pairs, dim3(1), dim3(RED_THREADS), 0, st, part, nblocks, out2);
+    hipLaunchKernelGGL(k_reduce_pairs, dim3(nb), dim3(RED_THREADS), 0, st, part, nblocks, tmp);
+    FM_HIP(m, hipGetLastError());
+    hipLaunchKernelGGL(k_reduce_pairs_final, dim3(1), dim3(RED_THREADS), 0, st, (const double*)tmp, nb, out2);
     FM_HIP(m, hipGetLastError());
     return FM_OK;
 }
