@@ -152,6 +152,18 @@ def main():
                 "kernels": {k: {"avg_ms": v["avg_ms"], "algorithmic_GBs": ab[k] / (v["avg_ms"] * 1e-3) / 1e9}
                             for k, v in kern.items() if k in ab}}
 
+    # ceiling of the traffic these kernels are bound by: random 128-byte line reads from a buffer of the
+    # size of the aggregates, measured here; beside it the lines per second the dominant kernel moves
+    # according to the committed counter summary
+    try:
+        line_peak = B.fm_probe_gather(max(1 << 20, min(wl.N * 128, 8 << 30)), 128)
+    except Exception as e:  # a failed calibration must not lose the measurement
+        print(f"[bench] gather calibration failed: {e}", file=sys.stderr, flush=True)
+        line_peak = None
+    roofline["random_line_reads_per_s"] = line_peak
+    roofline["lines_per_s"] = None if traffic is None else traffic / 128.0 / (dom_ms * 1e-3)
+    roofline["line_frac"] = None if (traffic is None or not line_peak) else roofline["lines_per_s"] / line_peak
+
     extra = {"column_classes": ab["classes"], "gen_s": t_gen, "upload_s": t_up, "csc_build_s": t_csc, "sha256": wl.sha256()[:16]}
     if args.stratified:
         m.fm_partition(wl.P)

@@ -209,6 +209,12 @@ int fm_set_tuning(int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t v
  * min_per_tile < 0 keeps the current value. */
 int fm_set_tile_tuning(int32_t tile_rows, int32_t min_per_tile, int32_t tile_seg);
 
+/* Calibration for benchmarks, not part of the method: rows of row_bytes (64 or 128) read per second
+ * from pseudo-random places of a zeroed device buffer of buffer_bytes (1 MiB .. 64 GiB) that the call
+ * allocates and frees.  This is the traffic the pass kernels are bound by (gathers of V rows and of
+ * aggregate rows).  rows_per_s is HOST 1; the call waits for the stream. */
+int fm_probe_gather(int64_t buffer_bytes, int32_t row_bytes, double* rows_per_s, void* hip_stream);
+
 int fm_destroy(fm_matrix* m);
 const char* fm_last_error(const fm_matrix* m); /* m may be NULL: last build error of this thread */
 

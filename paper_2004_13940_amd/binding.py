@@ -38,7 +38,7 @@ EXPORTS = ["fm_build_csr", "fm_build_csc", "fm_partition", "fm_get_csc", "fm_get
            "fm_get_batch_csc", "fm_forward", "fm_evaluate", "fm_gradient",
            "fm_sgd_epoch", "fm_minibatch_epoch", "fm_stratified_epoch", "fm_stratified_begin", "fm_stratified_step",
            "fm_stratified_end", "fm_get_aux", "fm_profile_enable", "fm_profile_kernels",
-           "fm_profile_kernel_name", "fm_profile_read", "fm_set_tuning", "fm_set_tile_tuning", "fm_destroy", "fm_last_error"]
+           "fm_profile_kernel_name", "fm_profile_read", "fm_set_tuning", "fm_set_tile_tuning", "fm_probe_gather", "fm_destroy", "fm_last_error"]
 
 _lib = None
 
@@ -93,6 +93,16 @@ def make_params(K, loss, lambda_w, lambda_v, eta, loss_scale=1.0, update_w0=1, r
                 refresh_all_rows=0, stale_aux=0) -> fm_params:
     return fm_params(int(K), int(loss), float(lambda_w), float(lambda_v), float(eta), float(loss_scale),
                      int(update_w0), int(reg_full_per_cell), int(refresh_all_rows), int(stale_aux))
+
+
+def fm_probe_gather(buffer_bytes, row_bytes=128, stream=None):
+    """Rows of ``row_bytes`` read per second from random places of a buffer of ``buffer_bytes``."""
+    out = ctypes.c_double(0.0)
+    rc = load().fm_probe_gather(ctypes.c_int64(int(buffer_bytes)), ctypes.c_int32(int(row_bytes)), ctypes.byref(out),
+                                _stream(stream))
+    if rc != FM_OK:
+        raise FMError(rc, "fm_probe_gather failed")
+    return out.value
 
 
 def fm_set_tuning(seg=0, panel=0, heavy_per_panel=0, vlong=0, min_panels=0):

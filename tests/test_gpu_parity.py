@@ -652,3 +652,13 @@ def test_state_and_argument_errors_are_reported():
         m.fm_stratified_step(p, 0, d_y, d_w0, d_w, d_V)  # no begin yet
     assert e.value.code == -5
     m.close()
+
+
+def test_gather_probe_reports_a_plausible_rate_and_rejects_bad_arguments():
+    B = _B()
+    rate = B.fm_probe_gather(64 << 20, 128)
+    assert 1e9 < rate < 1e12
+    with pytest.raises(B.FMError):
+        B.fm_probe_gather(64 << 20, 96)
+    with pytest.raises(B.FMError):
+        B.fm_probe_gather(1000, 64)
