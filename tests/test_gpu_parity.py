@@ -460,10 +460,12 @@ def test_minibatch_epochs_of_the_workloads(idx, scale, nb):
     m.close()
 
 
-@pytest.mark.parametrize("K,nb,full_reg", [(8, 1, False), (5, 6, False), (12, 9, True), (60, 4, False), (256, 3, False)])
+@pytest.mark.parametrize("K,nb,full_reg", [(8, 1, False), (5, 6, False), (12, 9, True), (60, 4, False), (256, 3, False),
+                                          (4, 2000, False)])
 def test_minibatch_variants(K, nb, full_reg):
     """Batch counts that do not divide N, more batches than some columns have entries, the literal
-    regulariser, one batch; a dense column is long in every batch."""
+    regulariser, one batch, more batches than rows (a quarter of them empty); a dense column is long
+    in every batch that is large enough."""
     N, D = 1500, 70
     rowptr, col, val, y, w0, w, V = _problem(500 + K, N, D, K, 0.08, O.LOSS_LOGISTIC, dense_cols=(3,))
     V *= np.float32(0.3)
