@@ -133,7 +133,8 @@ int fm_evaluate(fm_matrix* m, const fm_params* p, const float* y /*DEVICE N*/, c
  *   grad_w0 = sum_i r_i
  *   grad_w  = X^T r + lambda_w w
  *   grad_V  = X^T (r . G) - diag((X o X)^T r) V + lambda_v V
- * Atomic-free pass over the CSC copy; needs fm_build_csc.  Outputs may be NULL. */
+ * Atomic-free pass over the CSC copy; needs fm_build_csc.  Outputs may be NULL.  For K that the
+ * handle keeps as packed aggregate rows (K % 4 == 0, K <= 28) r and G are first copied into them. */
 int fm_gradient(fm_matrix* m, const fm_params* p, const float* r /*DEVICE N*/, const float* G /*DEVICE N*K*/,
                 const float* w /*DEVICE D*/, const float* V /*DEVICE D*K*/,
                 float* grad_w0 /*DEVICE 1*/, float* grad_w /*DEVICE D*/, float* grad_V /*DEVICE D*K*/,
@@ -155,6 +156,10 @@ int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y /*DEVICE N*/,
  *       step on w_J, V_J (regulariser share per fm_params), deltas kept,
  *       incremental refresh a_I += X_IJ dw_J, G_I += X_IJ dV_J, q_I likewise, r_I recomputed;
  *   bias step from the multipliers as they stand (if update_w0).
+ * A column with no entry in its cell only takes the regulariser's step there, as one multiplication
+ * by 1 - eta rho lambda; this call may take such steps later (before the column's next step with
+ * data, or at the end of the epoch), in order, with the bits of taking them at once.
+ * With stale_aux the refresh line is skipped (Algorithm 1's update phase).
  * objective (HOST 2, nullable): data term and regulariser from a fresh forward at the
  * FINAL parameters (costs one more pass).  Needs fm_partition. */
 int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float* y, float* w0, float* w, float* V,
@@ -179,15 +184,16 @@ int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const float*
                        float* w, float* V, void* hip_stream);
 int fm_stratified_end(fm_matrix* m, const fm_params* p, float* w0, void* hip_stream);
 
-/* Copy the aggregates the handle holds (valid after fm_sgd_epoch or any stratified call)
- * into caller DEVICE arrays; any may be NULL. */
+/* Copy the aggregates the handle holds (after fm_sgd_epoch, fm_minibatch_epoch or any stratified
+ * call; a and q only after a stratified call; nothing after fm_evaluate: FM_ESTATE) into caller
+ * DEVICE arrays; any may be NULL. */
 int fm_get_aux(const fm_matrix* m, float* a /*N*/, float* G /*N*K*/, float* q /*N*/, float* r /*N*/,
                void* hip_stream);
 
 /* Per-kernel timing with HIP events on the launch stream.  While enabled, every kernel
  * launch of this handle is bracketed by two events, and kernels that normally overlap on
- * internal side streams run back to back on the launch stream, so that each is timed alone.  fm_profile_read waits for the
- * stream, then reports for kernel id k (0 <= k < fm_profile_kernels()) the number of
+ * internal side streams run back to back on the launch stream, so that each is timed alone.
+ * fm_profile_read waits for the stream, then reports for kernel id k (0 <= k < fm_profile_kernels()) the number of
  * launches and their total time in milliseconds since the last reset, and resets. */
 int fm_profile_enable(fm_matrix* m, int32_t on);
 int fm_profile_kernels(void);
@@ -196,7 +202,8 @@ int fm_profile_read(fm_matrix* m, int64_t* launches /*HOST nk*/, double* total_m
 
 /* Work-decomposition knobs of the column side, for callers that tune or test them; they
  * apply to matrices whose CSC is built afterwards.  A value <= 0 keeps the current one.
- *   seg              entries per work item of a long column                      (default 256)
+ *   seg              entries per work item of a long column                      (default 256; the
+ *                    per-stratum and per-batch matrices use 256 or 128, chosen per matrix, unless set here)
  *   panel            rows per panel of the L2-blocked traversal of heavy columns (default 32768)
  *   heavy_per_panel  a column is heavy if it averages this many entries per panel (default 16)
  *   vlong            columns with more items are summed by a whole workgroup      (default 512)
