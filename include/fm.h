@@ -158,7 +158,8 @@ int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y /*DEVICE N*/,
  *   bias step from the multipliers as they stand (if update_w0).
  * A column with no entry in its cell only takes the regulariser's step there, as one multiplication
  * by 1 - eta rho lambda; this call may take such steps later (before the column's next step with
- * data, or at the end of the epoch), in order, with the bits of taking them at once.
+ * data, or at the end of the epoch) as one multiplication by their product, formed in fp64: equal to
+ * taking them one by one up to the rounding of those fp32 multiplications.
  * With stale_aux the refresh line is skipped (Algorithm 1's update phase).
  * objective (HOST 2, nullable): data term and regulariser from a fresh forward at the
  * FINAL parameters (costs one more pass).  Needs fm_partition. */

@@ -655,6 +655,16 @@ extern "C" int fm_stratified_begin(fm_matrix* m, const fm_params* p, const float
     return FM_OK;
 }
 
+// Regulariser shares of P floor-split row blocks: the table, the bounds, and the two values it holds.
+static void set_shares(ColArgs& A, const float* rho, const int64_t* bounds, int64_t N, int32_t P)
+{
+    A.rho = rho;
+    A.rb = bounds;
+    const int64_t base = N / P;
+    A.rho_small = (float)((double)base / (double)N);
+    A.rho_big = (float)((double)(base + 1) / (double)N);
+}
+
 // Column-side arguments of stratum s (s == P: the flush after the last stratum).
 static void strat_col_args(fm_matrix* m, const fm_params* p, int32_t s, float* w, float* V, bool lazy, ColArgs& A)
 {
@@ -663,7 +673,7 @@ static void strat_col_args(fm_matrix* m, const fm_params* p, int32_t s, float* w
     A.V = V;
     A.P = m->P;
     A.s = s;
-    if (!p->reg_full_per_cell) A.rho = m->d_rho;
+    if (!p->reg_full_per_cell) set_shares(A, m->d_rho, m->d_rb, m->N, m->P);
     if (lazy) A.lazy_last = m->lazy_last;
 }
 
@@ -805,7 +815,7 @@ extern "C" int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float*
         A.P = m->B;
         A.s = b;
         A.batch = 1;
-        if (!p->reg_full_per_cell) A.rho = m->d_brho;
+        if (!p->reg_full_per_cell) set_shares(A, m->d_brho, m->d_bb, m->N, m->B);
         if (lazy) A.lazy_last = m->lazy_last;
     };
     for (int32_t b = 0; b < m->B; ++b) {

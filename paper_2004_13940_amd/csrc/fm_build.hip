@@ -976,6 +976,8 @@ extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
     for (int32_t b = 0; b < P; ++b) h_rho[b] = (float)((double)(m->h_rb[b + 1] - m->h_rb[b]) / (double)m->N);
     FM_TRY(fm_dev_alloc(m, (void**)&m->d_rho, (size_t)P * sizeof(float)));
     FM_HIP(m, hipMemcpy(m->d_rho, h_rho.data(), (size_t)P * sizeof(float), hipMemcpyHostToDevice));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->d_rb, (size_t)(P + 1) * sizeof(int64_t)));
+    FM_HIP(m, hipMemcpy(m->d_rb, m->h_rb.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
     FM_TRY(fm_ensure_lazy(m));
     FM_HIP(m, hipMemcpy(d_cb, m->h_cb.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
 
@@ -1036,6 +1038,8 @@ extern "C" int fm_partition_batches(fm_matrix* m, int32_t B, void* hip_stream)
     for (int32_t b = 0; b < B; ++b) h_rho[b] = (float)((double)(m->h_bb[b + 1] - m->h_bb[b]) / (double)m->N);
     FM_TRY(fm_dev_alloc(m, (void**)&m->d_brho, (size_t)B * sizeof(float)));
     FM_HIP(m, hipMemcpy(m->d_brho, h_rho.data(), (size_t)B * sizeof(float), hipMemcpyHostToDevice));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->d_bb, (size_t)(B + 1) * sizeof(int64_t)));
+    FM_HIP(m, hipMemcpy(m->d_bb, m->h_bb.data(), (size_t)(B + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
     FM_TRY(fm_ensure_lazy(m));
     FM_TRY(build_strata_side(m, false, st, &m->b_colptr, &m->b_row, &m->b_cval, B, true));
     // entries of batch b: from the start of its first column to the start of the next batch's

@@ -53,66 +53,56 @@ __device__ __forceinline__ float reg_share(const ColArgs& A, int32_t qb, int32_t
     return A.rho[p];
 }
 
-// A column with no entries in its cell only feels the regulariser: x <- x - eta rho lambda x.
-// That step is taken as one rounded multiplication by c = 1 - eta (rho lambda), so that a run
-// of postponed steps costs one multiplication each and gives the bits of immediate ones.
+// A column with no entries in its cell only feels the regulariser: x <- x - eta rho lambda x,
+// taken as one rounded multiplication by c = 1 - eta (rho lambda).
 __device__ __forceinline__ float step_factor(float rho, float lambda, float eta)
 {
     return __fsub_rn(1.f, __fmul_rn(eta, __fmul_rn(rho, lambda)));
 }
 
-// Factors of the regulariser-only step per row block: from a table staged in LDS ([P] for V,
-// then [P] for w), or computed from the table of shares.
-struct StepFactors {
-    const float* tab;
-    const float* rho;
-    float lv, lw, eta;
-    int32_t P;
-    bool batch;  // step t acts on row block t, the next step on block t+1 (else on the block before, cyclically)
-    __device__ __forceinline__ float v(int32_t p) const
-    {
-        return tab != nullptr ? tab[p] : step_factor(rho != nullptr ? rho[p] : 1.f, lv, eta);
-    }
-    __device__ __forceinline__ float w(int32_t p) const
-    {
-        return tab != nullptr ? tab[P + p] : step_factor(rho != nullptr ? rho[p] : 1.f, lw, eta);
-    }
-    // row block that column block qb meets in stratum t, and the one it meets next
-    __device__ __forceinline__ int32_t block_at(int32_t qb, int32_t t) const
-    {
-        if (P <= 0) return 0;
-        if (batch) return t;
-        int32_t p = (qb - t) % P;
-        return p < 0 ? p + P : p;
-    }
-    // (two operations: this sits in the loop over postponed steps; with P == 0 the factors ignore p,
-    // and a walk over batches ends before p reaches P)
-    __device__ __forceinline__ int32_t next(int32_t p) const
-    {
-        p += batch ? 1 : -1;
-        return p < 0 ? P - 1 : p;
-    }
-};
-
-__device__ __forceinline__ StepFactors plain_factors(const ColArgs& A)
+__device__ __forceinline__ double pow_int(double c, uint32_t n)
 {
-    return StepFactors{nullptr, A.rho, A.lambda_v, A.lambda_w, A.eta, A.rho != nullptr ? A.P : 0, A.batch != 0};
+    double r = 1.0;
+    while (n != 0) {
+        if (n & 1u) r *= c;
+        c *= c;
+        n >>= 1;
+    }
+    return r;
 }
 
-// Kernels whose every thread gets here fill the table in LDS (2 P floats) when postponed steps
-// may have to be taken: a walk over strata then costs an LDS read per stratum.
-__device__ __forceinline__ StepFactors stage_factors(const ColArgs& A, float* sh)
+// Postponed regulariser-only steps t0 .. t1-1 of a column of column block qb, as one factor each
+// for v_j and w_j.  The floor split makes row blocks of two sizes only, so the steps have two
+// factors only, and the run is  c_small^(n - n_big) * c_big^(n_big)  with n_big read off the block
+// bounds; the product is formed in fp64 and rounded once, which is closer to the exact product than
+// the n rounded multiplications of steps taken one by one (a single step gives its factor exactly).
+__device__ __forceinline__ void catch_up_factors(const ColArgs& A, int32_t qb, int32_t t0, int32_t t1, float& fv,
+                                                 float& fw)
 {
-    StepFactors F = plain_factors(A);
-    if (A.lazy_last == nullptr || A.rho == nullptr) return F;  // uniform over the launch
-    for (int i = threadIdx.x; i < A.P; i += FM_BLOCK) {
-        const float rho = A.rho[i];
-        sh[i] = step_factor(rho, A.lambda_v, A.eta);
-        sh[A.P + i] = step_factor(rho, A.lambda_w, A.eta);
+    fv = fw = 1.f;
+    const int32_t n = t1 - t0;
+    if (n <= 0) return;
+    if (A.rho == nullptr) {  // every step applies the whole regulariser
+        fv = (float)pow_int((double)step_factor(1.f, A.lambda_v, A.eta), (uint32_t)n);
+        fw = (float)pow_int((double)step_factor(1.f, A.lambda_w, A.eta), (uint32_t)n);
+        return;
     }
-    __syncthreads();
-    F.tab = sh;
-    return F;
+    int64_t rows;  // rows of the row blocks that the steps t0 .. t1-1 act on
+    if (A.batch) {
+        rows = A.rb[t1] - A.rb[t0];
+    } else {  // blocks p0, p0-1, ..., cyclically
+        int32_t p0 = (qb - t0) % A.P;
+        if (p0 < 0) p0 += A.P;
+        const int32_t lo = p0 - n + 1;
+        rows = lo >= 0 ? A.rb[p0 + 1] - A.rb[lo] : (A.rb[p0 + 1] - A.rb[0]) + (A.rb[A.P] - A.rb[A.P + lo]);
+    }
+    const int64_t base = A.N / A.P;  // rows of a small block; a big one has one more
+    const uint32_t n_big = (uint32_t)(rows - (int64_t)n * base);
+    const uint32_t n_small = (uint32_t)n - n_big;
+    fv = (float)(pow_int((double)step_factor(A.rho_small, A.lambda_v, A.eta), n_small) *
+                 pow_int((double)step_factor(A.rho_big, A.lambda_v, A.eta), n_big));
+    fw = (float)(pow_int((double)step_factor(A.rho_small, A.lambda_w, A.eta), n_small) *
+                 pow_int((double)step_factor(A.rho_big, A.lambda_w, A.eta), n_big));
 }
 
 // What the step of column j needs from memory besides the data sums; loaded early by the
@@ -144,22 +134,19 @@ __device__ __forceinline__ ColState<VEC> load_column(const ColArgs& A, int64_t j
 // step (optionally recording the change for the incremental refresh).
 template <int VEC, int L, bool UPDATE>
 __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int sub, int kbase, bool kact,
-                                              const float (&acc)[VEC], float gw, float s2, const StepFactors& F,
-                                              ColState<VEC> c)
+                                              const float (&acc)[VEC], float gw, float s2, ColState<VEC> c)
 {
     const int K = A.K;
     const int32_t qb = (A.rho != nullptr && !A.batch) ? fm_block_of(j, A.D, A.P) : 0;
     const float rho = reg_share(A, qb, A.s);
+    float fv = 1.f, fw = 1.f;
+    if (c.t0 < A.s) catch_up_factors(A, qb, c.t0, A.s, fv, fw);  // postponed regulariser-only steps
     float dn = 0.f;
     if (kact) {
         float g[VEC];
-        int32_t p = F.block_at(qb, c.t0);
-#pragma unroll 4
-        for (int32_t t = c.t0; t < A.s; ++t) {  // postponed regulariser-only steps
-            const float f = F.v(p);
-            p = F.next(p);
+        if (c.t0 < A.s) {
 #pragma unroll
-            for (int z = 0; z < VEC; ++z) c.v[z] = __fmul_rn(c.v[z], f);
+            for (int z = 0; z < VEC; ++z) c.v[z] = __fmul_rn(c.v[z], fv);
         }
         const float rl = __fmul_rn(rho, A.lambda_v);
 #pragma unroll
@@ -183,12 +170,7 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
     }
     if (sub == 0) {
         float wj = c.w;
-        int32_t p = F.block_at(qb, c.t0);
-#pragma unroll 4
-        for (int32_t t = c.t0; t < A.s; ++t) {
-            wj = __fmul_rn(wj, F.w(p));
-            p = F.next(p);
-        }
+        if (c.t0 < A.s) wj = __fmul_rn(wj, fw);
         const float g = __fmaf_rn(__fmul_rn(rho, A.lambda_w), wj, gw);
         if constexpr (UPDATE) {
             const float d = __fmul_rn(-A.eta, g);
@@ -210,8 +192,6 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
     const int wave = threadIdx.x / FM_WAVE;
     const int sub = lane & (L - 1);
     const int grp = lane / L;
-    extern __shared__ float sh_fac[];  // 2 A.P floats when postponed steps may be pending, else none
-    const StepFactors F = UPDATE ? stage_factors(A, sh_fac) : plain_factors(A);
     const int64_t pos = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
     const bool valid = pos < A.nshort;
     int64_t j = 0, beg = 0, end = 0;
@@ -233,7 +213,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
     accumulate_entries<VEC, L, PACKED, true, (L >= 16)>(A, beg, end, sub, kbase, kact, acc, gw, s2);
     gw = fm_group_sum<L>(gw);
     s2 = fm_group_sum<L>(s2);
-    if (valid) finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, acc, gw, s2, F, c);
+    if (valid) finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, acc, gw, s2, c);
 }
 
 // Columns with nothing stored (in this matrix or stratum) only feel the regulariser; one group
@@ -257,7 +237,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_empty(const ColArgs A)
         float acc[VEC];
 #pragma unroll
         for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
-        finish_column<VEC, LE, false>(A, j, sub, kbase, kact, acc, 0.f, 0.f, plain_factors(A),
+        finish_column<VEC, LE, false>(A, j, sub, kbase, kact, acc, 0.f, 0.f,
                                       load_column<VEC, false>(A, j, sub, kbase, kact));
     } else {
         const int32_t qb = (A.rho != nullptr && !A.batch) ? fm_block_of(j, A.D, A.P) : 0;
@@ -286,8 +266,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_empty(const ColArgs A)
     }
 }
 
-// The postponed regulariser steps of every column, strata lazy_last[j] .. A.s-1 in order;
-// one group of LE lanes per column, consecutive columns in consecutive groups.
+// The postponed regulariser steps of every column, strata lazy_last[j] .. A.s-1; one group of LE
+// lanes per column, consecutive columns in consecutive groups.
 template <int VEC, int LE>
 __global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
 {
@@ -296,37 +276,22 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
     const int wave = threadIdx.x / FM_WAVE;
     const int sub = lane & (LE - 1);
     const int grp = lane / LE;
-    extern __shared__ float sh_fac[];  // 2 A.P floats
-    const StepFactors F = stage_factors(A, sh_fac);
     const int64_t j = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
     if (j >= A.D) return;  // whole groups leave together
     const int32_t t0 = A.lazy_last[j];
     if (t0 >= A.s) return;
     const int32_t qb = (A.rho != nullptr && !A.batch) ? fm_block_of(j, A.D, A.P) : 0;
+    float fv, fw;
+    catch_up_factors(A, qb, t0, A.s, fv, fw);
     const int kbase = sub * VEC;
     if (kbase < A.K) {
         float v[VEC];
         fm_load_vec<VEC>(A.V + j * A.K + kbase, v);
-        int32_t p = F.block_at(qb, t0);
-#pragma unroll 4
-        for (int32_t t = t0; t < A.s; ++t) {
-            const float f = F.v(p);
-            p = F.next(p);
 #pragma unroll
-            for (int z = 0; z < VEC; ++z) v[z] = __fmul_rn(v[z], f);
-        }
+        for (int z = 0; z < VEC; ++z) v[z] = __fmul_rn(v[z], fv);
         fm_store_vec<VEC>(A.V + j * A.K + kbase, v);
     }
-    if (sub == 0) {
-        float wj = A.w[j];
-        int32_t p = F.block_at(qb, t0);
-#pragma unroll 4
-        for (int32_t t = t0; t < A.s; ++t) {
-            wj = __fmul_rn(wj, F.w(p));
-            p = F.next(p);
-        }
-        A.w[j] = wj;
-    }
+    if (sub == 0) A.w[j] = __fmul_rn(A.w[j], fw);
 }
 
 // Partial sums of item `it`: one row [acc_0..acc_{K-1} | gw | s2 | pad] of A.ps floats, a whole
@@ -587,7 +552,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_finish_wave(const ColArgs A)
         float accf[VEC];
 #pragma unroll
         for (int z = 0; z < VEC; ++z) accf[z] = (float)acc[z];
-        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)gw, (float)s2, plain_factors(A),
+        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)gw, (float)s2,
                                       load_column<VEC, UPDATE>(A, j, sub, kbase, kact));
     }
 }
@@ -633,7 +598,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_finish_block(const ColArgs A)
         float accf[VEC];
 #pragma unroll
         for (int z = 0; z < VEC; ++z) accf[z] = (float)tot[z];
-        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)tg, (float)ts, plain_factors(A),
+        finish_column<VEC, L, UPDATE>(A, j, sub, kbase, kact, accf, (float)tg, (float)ts,
                                       load_column<VEC, UPDATE>(A, j, sub, kbase, kact));
     }
 }
@@ -677,12 +642,6 @@ inline bool launch_tile(fm_matrix* m, const ColArgs& A, hipStream_t st)
     return false;
 }
 
-// dynamic LDS of the kernels that stage the table of shares (see stage_shares)
-static size_t share_table_bytes(const ColArgs& A)
-{
-    return (A.lazy_last != nullptr && A.rho != nullptr) ? 2 * (size_t)A.P * sizeof(float) : 0;
-}
-
 // k_cols_empty with LE = smallest power of two >= K/VEC lanes per column
 template <int VEC, int LE>
 int launch_empty_l(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
@@ -722,7 +681,7 @@ int launch_flush_l(fm_matrix* m, const ColArgs& A, hipStream_t st)
     const int64_t grid = (A.D + per - 1) / per;
     if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
     ProfScope ps(m, st, FMK_COLS);
-    hipLaunchKernelGGL((k_cols_flush<VEC, LE>), dim3((unsigned)grid), dim3(FM_BLOCK), share_table_bytes(A), st, A);
+    hipLaunchKernelGGL((k_cols_flush<VEC, LE>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
     FM_HIP(m, hipGetLastError());
     return FM_OK;
 }
@@ -802,8 +761,7 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
         if (g1 > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
         if (g1 > 0) {
             if (update)
-                hipLaunchKernelGGL((k_cols<VEC, L, true, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK),
-                                   share_table_bytes(A), s_cols, A);
+                hipLaunchKernelGGL((k_cols<VEC, L, true, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK), 0, s_cols, A);
             else
                 hipLaunchKernelGGL((k_cols<VEC, L, false, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK), 0, s_cols, A);
             FM_HIP(m, hipGetLastError());

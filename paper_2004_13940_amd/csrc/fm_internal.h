@@ -111,6 +111,8 @@ struct fm_matrix {
     int32_t P = 0;
     std::vector<int64_t> h_rb, h_cb, h_cell_nnz, h_strat_nnz_off;  // bounds, P*P table, P+1 offsets
     float* d_rho = nullptr;        // [P] share |I_p|/N of the regulariser that a step on row block p applies
+    int64_t* d_rb = nullptr;       // [P+1] row block bounds
+    int64_t* d_bb = nullptr;       // [B+1] batch bounds
     int32_t* lazy_last = nullptr;  // [D] see ColArgs::lazy_last
     int64_t* s_rowptr = nullptr;  // [P*N+1] global offsets into s_col/s_val
     int32_t* s_col = nullptr;
@@ -243,13 +245,15 @@ struct ColArgs {
     float lambda_w, lambda_v, eta;
     // regulariser share: rho = 1 when rho == nullptr, else rho[p] = |I_p|/N with p = (colblock(j) - s) mod P
     const float* rho;
+    const int64_t* rb;           // with rho: [P+1] bounds of the row blocks (strata) or batches
+    float rho_small, rho_big;    // with rho: the shares of a block of floor(N/P) rows and of one more
     int64_t N;
     int32_t P, s;
     int32_t batch;  // 1: steps are row batches, step t acts on row block t (else on (colblock - t) mod P)
     // nullable, update only: lazy_last[j] = number of strata of this epoch whose step column j has
     // taken.  A column that is empty in a cell only feels the regulariser there; with this array
     // those steps are postponed until the column next has entries (or the epoch ends) and then
-    // taken in order, so no pass over the columns that are empty in a stratum is needed.
+    // taken as one multiplication, so no pass over the columns that are empty in a stratum is needed.
     int32_t* lazy_last;
     // long-column items
     const int32_t* long_col;

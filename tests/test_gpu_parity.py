@@ -379,9 +379,11 @@ def test_single_block_stratified_epoch_equals_full_gradient_epoch_on_gpu():
 
 
 @pytest.mark.parametrize("idx,scale,P,full_reg", [(3, 0.05, 8, False), (5, 0.002, 16, False), (5, 0.002, 5, True)])
-def test_postponed_regulariser_steps_give_the_bits_of_immediate_ones(idx, scale, P, full_reg):
+def test_postponed_regulariser_steps_agree_with_immediate_ones(idx, scale, P, full_reg):
     """fm_stratified_epoch lets a column that is empty in its cell take its regulariser-only steps
-    later, in order; fm_stratified_step takes every step at once.  Same arithmetic, same bits."""
+    later, as one multiplication by their product (formed in fp64); fm_stratified_step takes every
+    step at once, one rounded multiplication each.  They differ by the rounding of at most P - 1
+    fp32 multiplications."""
     import torch
     B = _B()
     wl = make_config(idx, scale=scale)
@@ -400,7 +402,10 @@ def test_postponed_regulariser_steps_give_the_bits_of_immediate_ones(idx, scale,
             m.fm_stratified_step(p, s, y, b0, bw, bV)
         m.fm_stratified_end(p, b0)
         torch.cuda.synchronize()
-        assert torch.equal(aw, bw) and torch.equal(aV, bV) and torch.equal(a0, b0)
+        tol = 2.0 ** -23 * P
+        for x, z in ((aw, bw), (aV, bV), (a0, b0)):
+            x, z = x.cpu().numpy().astype(np.float64), z.cpu().numpy().astype(np.float64)
+            assert np.abs(x - z).max() <= tol * max(np.abs(z).max(), 1e-30)
     assert not torch.equal(aw, to_dev(wl.w))
     m.close()
 
