@@ -669,3 +669,47 @@ def test_gather_probe_reports_a_plausible_rate_and_rejects_bad_arguments():
         B.fm_probe_gather(64 << 20, 96)
     with pytest.raises(B.FMError):
         B.fm_probe_gather(1000, 64)
+
+
+def test_random_shapes_through_every_epoch_kind():
+    """Seeded sweep over shapes, latent sizes (every lane layout, packed and planar aggregates), losses,
+    partitions and flags: one epoch of each kind against the oracle."""
+    import torch
+    from paper_2004_13940_amd.workloads import Workload
+    B = _B()
+    rng = np.random.default_rng(20241127)
+    Ks = [1, 2, 3, 4, 6, 7, 8, 12, 16, 24, 28, 32, 36, 48, 64, 128]
+    for case in range(32):
+        K = int(Ks[case % len(Ks)])
+        N = int(rng.integers(40, 900))
+        D = int(rng.integers(5, 120))
+        dens = float(rng.uniform(0.03, 0.5))
+        loss = int(rng.integers(0, 2))
+        P = int(rng.integers(1, 10))
+        nb = int(rng.integers(1, 10))
+        dense = tuple(int(c) for c in rng.choice(D, size=int(rng.integers(0, 3)), replace=False))
+        rowptr, col, val, y, w0, w, V = _problem(7000 + case, N, D, K, dens, loss, dense_cols=dense)
+        V *= np.float32(0.3)
+        if loss == O.LOSS_SQUARED:
+            y = (y * 0.5).astype(np.float32)
+        wl = Workload("rnd", N, D, K, rowptr, col, val, y, w0, w, V, loss, float(rng.uniform(0, 0.05)),
+                      float(rng.uniform(0, 0.05)), 0.1, 1.0 / N, 1, P, int(rng.integers(0, 2)))
+        flags = {}
+        if rng.random() < 0.3:
+            flags["reg_full_per_cell"] = True
+        mode = rng.integers(0, 3)
+        if mode == 1:
+            flags["refresh_all_rows"] = True
+        elif mode == 2:
+            flags["stale_aux"] = True
+        _say(f"case {case}: N={N} D={D} K={K} nnz={len(col)} loss={loss} P={P} B={nb} dense={dense} flags={flags}")
+        m, p, X, dev, host = _run_full_epochs(B, wl, 1)
+        m.fm_partition(P)
+        host = _run_stratified_epochs(B, wl, m, p, X, dev, host, 1, **flags)
+        m.close()
+        for k in flags:
+            setattr(p, k, 0)
+        m2, _, _ = _run_minibatch_epochs(B, wl, nb, 1, full_reg=bool(flags.get("reg_full_per_cell")),
+                                         update_w0=bool(wl.update_w0))
+        m2.close()
+    torch.cuda.synchronize()
