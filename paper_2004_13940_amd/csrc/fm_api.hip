@@ -105,6 +105,10 @@ extern "C" int fm_destroy(fm_matrix* m)
 {
     if (m == nullptr) return FM_OK;
     (void)hipDeviceSynchronize();
+    fm_drop_graph(m);
+    if (m->gstream != nullptr) (void)hipStreamDestroy(m->gstream);
+    if (m->g_in != nullptr) (void)hipEventDestroy(m->g_in);
+    if (m->g_out != nullptr) (void)hipEventDestroy(m->g_out);
     for (void* p : m->allocs) (void)hipFree(p);
     if (m->h_scal != nullptr) (void)hipHostFree(m->h_scal);
     if (m->side1 != nullptr) (void)hipStreamDestroy(m->side1);
@@ -325,8 +329,17 @@ bool fm_side_streams(fm_matrix* m)
     return m->side_state == 1;
 }
 
+void fm_drop_graph(fm_matrix* m)
+{
+    if (m->gexec != nullptr) {
+        (void)hipGraphExecDestroy(m->gexec);
+        m->gexec = nullptr;
+    }
+}
+
 void fm_drop_workspace(fm_matrix* m)
 {
+    fm_drop_graph(m);
     for (void* p : {(void*)m->aux, (void*)m->dV, (void*)m->dwn, (void*)m->part, (void*)m->row_part})
         fm_dev_free(m, p);
     m->aux = m->dV = m->part = m->row_part = nullptr;
@@ -760,15 +773,11 @@ extern "C" int fm_stratified_end(fm_matrix* m, const fm_params* p, float* w0, vo
     return FM_OK;
 }
 
-extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float* y, float* w0, float* w, float* V,
-                                   double* objective, void* hip_stream)
+// Everything one stratified epoch enqueues (no allocation, no host transfer, no wait).
+static int enqueue_stratified_epoch(fm_matrix* m, const fm_params* p, const float* y, float* w0, float* w, float* V,
+                                    bool lazy, hipStream_t st)
 {
-    FM_TRY(fm_stratified_begin(m, p, y, w0, w, V, hip_stream));
-    hipStream_t st = (hipStream_t)hip_stream;
-    // The refresh of a stratum reads the change of a column only where the column has entries in
-    // its cell, so the regulariser-only steps of the other columns can wait (not when every row
-    // is refreshed from every column's change).
-    const bool lazy = (!p->refresh_all_rows || p->stale_aux) && m->lazy_last != nullptr && fm_lazy_enabled();
+    FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, nullptr, nullptr, nullptr, 2, false, st));
     if (lazy) FM_TRY(fm_fill_i32(m, m->lazy_last, m->D, 0, st));
     for (int32_t s = 0; s < m->P; ++s) FM_TRY(stratified_step(m, p, s, y, w0, w, V, lazy, st));
     if (lazy) {
@@ -776,7 +785,112 @@ extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float
         strat_col_args(m, p, m->P, w, V, true, F);
         FM_TRY(fm_launch_cols_flush(m, F, st));
     }
-    FM_TRY(fm_stratified_end(m, p, w0, hip_stream));
+    if (p->update_w0) {
+        const FmAux x = fm_aux_layout(m, p->K);
+        FM_TRY(fm_reduce_sum(m, x.r, m->N, x.ss, false, m->scal + 1, st));
+        FM_TRY(fm_bias_step(m, w0, m->scal + 1, p->eta, nullptr, st));
+    }
+    return FM_OK;
+}
+
+// FM_GRAPH=0: never replay the stratified epoch from a captured graph.  By default a graph is used
+// for matrices whose strata are small enough for the launches to dominate.
+static int fm_graph_mode()
+{
+    static const int mode = [] {
+        const char* e = getenv("FM_GRAPH");
+        if (e == nullptr || *e == 0) return 1;            // automatic
+        return e[0] == '0' ? 0 : (e[0] == '2' ? 2 : 1);   // 0 off, 2 always
+    }();
+    return mode;
+}
+
+static bool graph_ready(fm_matrix* m)
+{
+    if (m->graph_state == 0) {
+        m->graph_state = -1;
+        if (hipStreamCreateWithFlags(&m->gstream, hipStreamNonBlocking) == hipSuccess &&
+            hipEventCreateWithFlags(&m->g_in, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&m->g_out, hipEventDisableTiming) == hipSuccess)
+            m->graph_state = 1;
+        else
+            (void)hipGetLastError();
+    }
+    return m->graph_state == 1;
+}
+
+// Capture the epoch on the internal stream (or reuse the capture made for the same arguments) and
+// replay it between two events on the caller's stream.  Returns FM_ESTATE if no graph could be
+// built: the caller then enqueues the epoch directly.
+static int replay_stratified_epoch(fm_matrix* m, const fm_params* p, const float* y, float* w0, float* w, float* V,
+                                   bool lazy, hipStream_t st)
+{
+    const void* key[4] = {y, w0, w, V};
+    const bool same = m->gexec != nullptr && memcmp(&m->gkey_p, p, sizeof(fm_params)) == 0 &&
+                      memcmp(m->gkey_ptr, key, sizeof(key)) == 0 && m->gkey_lazy == lazy;
+    if (!same) {
+        fm_drop_graph(m);
+        (void)fm_side_streams(m);  // created outside the capture
+        if (hipStreamBeginCapture(m->gstream, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+            (void)hipGetLastError();
+            return FM_ESTATE;
+        }
+        const int rc = enqueue_stratified_epoch(m, p, y, w0, w, V, lazy, m->gstream);
+        hipGraph_t graph = nullptr;
+        const hipError_t e = hipStreamEndCapture(m->gstream, &graph);
+        if (rc != FM_OK || e != hipSuccess || graph == nullptr) {
+            (void)hipGetLastError();
+            if (graph != nullptr) (void)hipGraphDestroy(graph);
+            return FM_ESTATE;
+        }
+        const hipError_t ei = hipGraphInstantiate(&m->gexec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (ei != hipSuccess) {
+            (void)hipGetLastError();
+            m->gexec = nullptr;
+            return FM_ESTATE;
+        }
+        m->gkey_p = *p;
+        memcpy(m->gkey_ptr, key, sizeof(key));
+        m->gkey_lazy = lazy;
+    }
+    FM_HIP(m, hipEventRecord(m->g_in, st));
+    FM_HIP(m, hipStreamWaitEvent(m->gstream, m->g_in, 0));
+    FM_HIP(m, hipGraphLaunch(m->gexec, m->gstream));
+    FM_HIP(m, hipEventRecord(m->g_out, m->gstream));
+    FM_HIP(m, hipStreamWaitEvent(st, m->g_out, 0));
+    return FM_OK;
+}
+
+extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float* y, float* w0, float* w, float* V,
+                                   double* objective, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    FM_TRY(check_params(m, p));
+    if (m->P == 0) return fm_fail(m, FM_ESTATE, "stratified calls need fm_partition first");
+    if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
+        return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
+    hipStream_t st = (hipStream_t)hip_stream;
+    FM_TRY(ensure_strat_ws(m, p->K));
+    // The refresh of a stratum reads the change of a column only where the column has entries in
+    // its cell, so the regulariser-only steps of the other columns can wait (not when every row
+    // is refreshed from every column's change).
+    const bool lazy = (!p->refresh_all_rows || p->stale_aux) && m->lazy_last != nullptr && fm_lazy_enabled();
+    // small strata are bound by their launches: replay them from a graph
+    const int gmode = fm_graph_mode();
+    // (worth it from some tens of launches on: below that the two events and the graph launch cost more)
+    const bool small = m->nnz / m->P < (int64_t(1) << 20) && m->P >= 16;
+    bool done = false;
+    if (!m->prof && (gmode == 2 || (gmode == 1 && small)) && graph_ready(m)) {
+        const int rc = replay_stratified_epoch(m, p, y, w0, w, V, lazy, st);
+        if (rc == FM_OK)
+            done = true;
+        else if (rc != FM_ESTATE)
+            return rc;
+    }
+    if (!done) FM_TRY(enqueue_stratified_epoch(m, p, y, w0, w, V, lazy, st));
+    m->aux_full = true;
+    m->aux_held = true;
     if (objective != nullptr) {
         FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, nullptr, nullptr, nullptr, 2, true, st));
         FM_TRY(fm_reduce_sum(m, w, m->D, 1, true, m->scal + 2, st));

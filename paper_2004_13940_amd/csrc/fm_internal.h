@@ -148,6 +148,15 @@ struct fm_matrix {
     hipStream_t side1 = nullptr, side2 = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join1 = nullptr, ev_join2 = nullptr;
     int side_state = 0;  // 0 not tried, 1 ready, -1 unavailable or disabled
+    // the stratified epoch as a captured graph (launch-bound for small matrices), replayed while the
+    // caller passes the same parameters and arrays; built on an internal stream
+    hipStream_t gstream = nullptr;
+    hipEvent_t g_in = nullptr, g_out = nullptr;
+    hipGraphExec_t gexec = nullptr;
+    fm_params gkey_p = {};
+    const void* gkey_ptr[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool gkey_lazy = false;
+    int graph_state = 0;  // 0 not tried, 1 stream and events ready, -1 unavailable
     // profiling
     bool prof = false;
     std::vector<ProfRec> prof_recs;
@@ -164,6 +173,7 @@ int fm_fail(fm_matrix* m, int code, const char* fmt, ...);
 int fm_dev_alloc(fm_matrix* m, void** p, size_t bytes);
 void fm_dev_free(fm_matrix* m, void* p);
 void fm_drop_workspace(fm_matrix* m);  // forces reallocation after the structures changed
+void fm_drop_graph(fm_matrix* m);      // a captured epoch holds pointers into the workspace and the structures
 bool fm_side_streams(fm_matrix* m);    // creates them on first use; false if disabled (FM_SIDE_STREAMS=0)
 
 #define FM_HIP(m, expr)                                                                  \

@@ -713,3 +713,47 @@ def test_random_shapes_through_every_epoch_kind():
                                          update_w0=bool(wl.update_w0))
         m2.close()
     torch.cuda.synchronize()
+
+
+def test_replayed_stratified_epochs_stay_correct_between_other_work():
+    """With P >= 16 and small strata fm_stratified_epoch is captured once per set of arguments and
+    replayed; every replay is checked against the oracle, with other calls of the library (another
+    handle's epoch, a forward of this handle, a synchronisation) between the replays."""
+    import torch
+    B = _B()
+    wl = make_config(3, scale=0.1)
+    other = make_config(1)
+    mo = B.Matrix(other.N, other.D, other.rowptr, other.col, other.val)
+    mo.fm_build_csc()
+    po = B.make_params(other.K, other.loss, other.lambda_w, other.lambda_v, other.eta, other.loss_scale, 0)
+    o0, ow, oV = dev_params(other.w0, other.w, other.V)
+    oy = to_dev(other.y)
+    X = O.make_matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
+    m = B.Matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
+    m.fm_build_csc()
+    m.fm_partition(wl.P)
+    assert wl.P >= 16
+    p = B.make_params(wl.K, wl.loss, wl.lambda_w, wl.lambda_v, wl.eta, wl.loss_scale, 1)
+    d_w0, d_w, d_V = dev_params(wl.w0, wl.w, wl.V)
+    d_y = to_dev(wl.y)
+    yhat = torch.empty(wl.N, device="cuda")
+    w0, w, V = float(wl.w0), wl.w.astype(np.float64), wl.V.astype(np.float64)
+    kw = oracle_kw(wl)
+    for ep in range(5):
+        m.fm_stratified_epoch(p, d_y, d_w0, d_w, d_V)  # first call captures, the others replay
+        w0, w, V, _, _ = O.stratified_epoch(X, wl.y, w0, w, V, P=wl.P, final_objective=False, **kw)
+        mo.fm_sgd_epoch(po, oy, o0, ow, oV)
+        m.fm_forward(p, d_y, d_w0, d_w, d_V, yhat=yhat)
+        torch.cuda.synchronize()
+        assert_close(d_w.cpu().numpy(), w, f"w after replay {ep}")
+        assert_close(d_V.cpu().numpy().reshape(wl.D, wl.K), V, f"V after replay {ep}")
+        assert abs(d_w0.item() - w0) <= REL_TOL * max(abs(w0), 1e-3)
+        _, _, _, want = O.forward(X, w0, w, V)
+        assert_close(yhat.cpu().numpy(), want, f"scores after replay {ep}")
+    # new arrays: a new capture
+    e_w0, e_w, e_V = dev_params(wl.w0, wl.w, wl.V)
+    m.fm_stratified_epoch(p, d_y, e_w0, e_w, e_V)
+    w0b, wb, Vb, _, _ = O.stratified_epoch(X, wl.y, float(wl.w0), wl.w, wl.V, P=wl.P, final_objective=False, **kw)
+    assert_close(e_V.cpu().numpy().reshape(wl.D, wl.K), Vb, "V with new arrays")
+    m.close()
+    mo.close()
