@@ -211,9 +211,13 @@ int fm_profile_read(fm_matrix* m, int64_t* launches /*HOST nk*/, double* total_m
  *   min_panels       matrices with fewer panels use plain segments only           (default 64)
  * Results do not depend on these values beyond fp32 rounding. */
 int fm_set_tuning(int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t vlong, int32_t min_panels);
-/*   tile_rows     rows of aggregates staged in LDS by the kernel for dense-ish columns    (default 512)
- *   min_per_tile  a column is dense-ish if it averages this many entries per tile; 0 = none (default 8)
- *   tile_seg      entries per work item inside a tile                                     (default 256)
+/*   tile_rows     rows of aggregates staged in LDS by the kernel for dense-ish columns
+ *   min_per_tile  a column is dense-ish if it averages this many entries per tile; 0 = none
+ *   tile_seg      entries per work item inside a tile
+ * Defaults follow the shape of the matrix and the latent size of the pass: 1024 / 12 / 512 for tall
+ * matrices (N >= 2^21) while two tiles of 1024 rows fit the LDS of a compute unit (K a multiple of
+ * 4, K <= 16); 128 / 2 / 128 and 256 / 4 / 256 for matrices of fewer than 2^17 and 2^18 rows; else
+ * 512 / 8 / 256.
  * min_per_tile < 0 keeps the current value. */
 int fm_set_tile_tuning(int32_t tile_rows, int32_t min_per_tile, int32_t tile_seg);
 

@@ -354,6 +354,15 @@ static int ensure_ws(fm_matrix* m, int32_t K)
 {
     if (m->wsK == K) return FM_OK;
     fm_drop_workspace(m);
+    if (m->has_csc) {  // the LDS tiles of the dense-ish columns are shaped for K
+        int shape[3];
+        fm_tile_shape(m->N, K, &shape[0], &shape[1], &shape[2]);
+        if (memcmp(shape, m->lfull_shape, sizeof(shape)) != 0) {
+            FM_HIP(m, hipDeviceSynchronize());
+            FM_TRY(fm_build_full_index(m, K, nullptr));
+            FM_HIP(m, hipDeviceSynchronize());
+        }
+    }
     const size_t D = (size_t)m->D;
     FM_TRY(fm_dev_alloc(m, (void**)&m->aux, (size_t)std::max<int64_t>(fm_aux_floats(m->N, K), 1) * sizeof(float)));
     const int64_t items = std::max<int64_t>(std::max<int64_t>(m->lfull.nitems, m->lstrat.nitems), m->lbatch.nitems);

@@ -704,8 +704,8 @@ static FmTune& tune_mut()
 {
     static FmTune t = {env_int("FM_SEG", 256, 16, 1 << 20), env_int("FM_PANEL", 32768, 64, 1 << 30),
                        env_int("FM_HEAVY_PER_PANEL", 16, 1, 1 << 20), env_int("FM_VLONG", 512, 1, 1 << 30),
-                       env_int("FM_MIN_PANELS", 8 * FM_XCDS, 1, 1 << 30), env_int("FM_TILE", 512, 64, 1 << 20),
-                       env_int("FM_TILE_MIN", 8, 0, 1 << 20), env_int("FM_TILE_SEG", 256, 16, 1 << 20), 0};
+                       env_int("FM_MIN_PANELS", 8 * FM_XCDS, 1, 1 << 30), env_int("FM_TILE", 0, 0, 1 << 20),
+                       env_int("FM_TILE_MIN", -1, -1, 1 << 20), env_int("FM_TILE_SEG", 0, 0, 1 << 20), 0};
     static const bool once = [] {
         t.seg_strat = env_int("FM_SEG_STRAT", 0, 0, 1 << 20);  // 0: chosen per matrix
         return true;
@@ -736,10 +736,46 @@ extern "C" int fm_set_tuning(int32_t seg, int32_t panel, int32_t heavy_per_panel
     return FM_OK;
 }
 
-int fm_build_full_index(fm_matrix* m, hipStream_t st)
+// Frees the device arrays of an index and resets it.
+static void free_long_index(fm_matrix* m, LongIndex* li)
+{
+    for (void* p : {(void*)li->long_col, (void*)li->long_first, (void*)li->item_col, (void*)li->item_beg,
+                    (void*)li->item_len, (void*)li->short_col, (void*)li->order, (void*)li->ord_beg,
+                    (void*)li->ord_len, (void*)li->tile_ptr, (void*)li->vlong})
+        if (p != nullptr) fm_dev_free(m, p);
+    *li = LongIndex();
+}
+
+// Shape of the LDS tiles for N rows and latent size K (K = 0: not known yet).  Explicit settings win;
+// else two tiles must fit the LDS of a compute unit (1024 rows only while [G | r] of a row is at most
+// 17 floats) and the tile shrinks with the matrix.  Larger tiles mean fewer items, hence fewer partial sums to write and read back.
+void fm_tile_shape(int64_t N, int32_t K, int* tile_rows, int* tile_min, int* tile_seg)
+{
+    const FmTune& T = fm_tune();
+    // one workgroup works on one tile: tall matrices take big tiles (fewer items, hence fewer partial
+    // sums), short ones small tiles (enough workgroups to fill the chip)
+    int rows = 512, dense = 8, seg = 256;
+    if (K > 0 && K % 4 == 0 && K <= 16 && N >= (int64_t(1) << 21)) {
+        rows = 1024, dense = 12, seg = 512;
+    } else if (N < (int64_t(1) << 17)) {
+        rows = 128, dense = 2, seg = 128;
+    } else if (N < (int64_t(1) << 18)) {
+        rows = 256, dense = 4, seg = 256;
+    }
+    *tile_rows = T.tile > 0 ? (T.tile < 64 ? 64 : T.tile) : rows;
+    *tile_min = T.tile_min >= 0 ? T.tile_min : dense;
+    *tile_seg = T.tile_seg > 0 ? T.tile_seg : seg;
+}
+
+int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st)
 {
     LongIndex* out = &m->lfull;
-    const FmTune& T = fm_tune();
+    free_long_index(m, out);
+    FmTune T = fm_tune();
+    fm_tile_shape(m->N, K, &T.tile, &T.tile_min, &T.tile_seg);
+    m->lfull_shape[0] = T.tile;
+    m->lfull_shape[1] = T.tile_min;
+    m->lfull_shape[2] = T.tile_seg;
     FM_TRY(build_short_list(m, m->colptr, m->D, m->D, 1, fm_tune().seg, out, st));
     out->nlong = out->nitems = 0;
     out->h_long_off.assign(2, 0);
@@ -909,7 +945,7 @@ extern "C" int fm_build_csc(fm_matrix* m, void* hip_stream)
         fm_dev_free(m, k1);
         fm_dev_free(m, i1);
     }
-    FM_TRY(fm_build_full_index(m, st));
+    FM_TRY(fm_build_full_index(m, 0, st));
     FM_HIP(m, hipStreamSynchronize(st));
     m->has_csc = true;
     fm_drop_workspace(m);

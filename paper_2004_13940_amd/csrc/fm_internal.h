@@ -17,7 +17,8 @@ constexpr int FM_WAVES = FM_BLOCK / FM_WAVE;
 constexpr int FM_MAXP = 4096;
 constexpr int FM_XCDS = 8;                // L2 domains; workgroup b runs on XCD b % 8
 
-// Tunables of the column-side work decomposition (read once from the environment:
+// Tunables of the column-side work decomposition (tile, tile_min < 0, tile_seg: 0 or negative = chosen
+// per latent size, see fm_tile_shape; read once from the environment:
 // FM_SEG, FM_SEG_STRAT, FM_PANEL, FM_HEAVY_PER_PANEL, FM_VLONG, FM_MIN_PANELS; or fm_set_tuning).
 struct FmTune {
     int seg;              // entries per work item of a long column
@@ -107,6 +108,7 @@ struct fm_matrix {
     int32_t* crow = nullptr;
     float* cval = nullptr;
     LongIndex lfull;
+    int lfull_shape[3] = {0, 0, 0};  // tile rows, entries per tile that make a column dense-ish, item length in a tile
     // double partition and per-stratum matrices
     int32_t P = 0;
     std::vector<int64_t> h_rb, h_cb, h_cell_nnz, h_strat_nnz_off;  // bounds, P*P table, P+1 offsets
@@ -204,7 +206,9 @@ int fm_sort_by_key_u32(fm_matrix* m, uint32_t* keys, uint32_t* idx, uint32_t* ke
                        int64_t n, int bits, hipStream_t st, bool* result_in_alt);
 int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
                         LongIndex* out, hipStream_t st);
-int fm_build_full_index(fm_matrix* m, hipStream_t st);  // lfull, with the panel order of heavy columns
+// lfull, with the panel order of heavy columns and the LDS tiles shaped for latent size K (0: unknown)
+int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st);
+void fm_tile_shape(int64_t N, int32_t K, int* tile_rows, int* tile_min, int* tile_seg);
 int fm_ensure_lazy(fm_matrix* m);  // allocates lazy_last on first use
 
 // ---- pass kernels (fm_rows.hip / fm_cols.hip / fm_reduce.hip) ----
