@@ -314,10 +314,11 @@ def test_scaled_workloads_full_and_stratified_epochs(idx, scale, epochs):
 @pytest.mark.parametrize("P,flags", [(1, {}), (3, {}), (7, {"refresh_all_rows": True}),
                                      (5, {"reg_full_per_cell": True}), (64, {}),
                                      (4, {"refresh_all_rows": True, "reg_full_per_cell": True}),
-                                     (6, {"stale_aux": True})])
+                                     (6, {"stale_aux": True}), (200, {})])
 def test_stratified_variants_with_per_stratum_checks(P, flags):
-    """P not dividing N or D, P = 1, P > D, exact refresh, full regulariser per cell; a dense
-    column makes every stratum hold a column longer than one segment when P is small."""
+    """P not dividing N or D, P = 1, P > D (64, and 200: most column blocks empty, rows blocks of 11
+    or 12 rows), exact refresh, full regulariser per cell; a dense column makes every stratum hold a
+    column longer than one segment when P is small."""
     B = _B()
     N, D, K = 2300, 50, 8
     rowptr, col, val, y, w0, w, V = _problem(900 + P, N, D, K, 0.08, O.LOSS_LOGISTIC, dense_cols=(7,))
