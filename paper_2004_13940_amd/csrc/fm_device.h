@@ -99,6 +99,15 @@ __device__ __forceinline__ int fm_bcast_i(int v)
         return __builtin_amdgcn_mov_dpp(v, T == 0 ? 0xA0 : 0xF5, 0xf, 0xf, true);
     } else if constexpr (L == 4) {
         return __builtin_amdgcn_mov_dpp(v, T * 0x55, 0xf, 0xf, true);
+    } else if constexpr (L == 8) {
+        // two DPP moves instead of a trip through the LDS crossbar: every quad broadcasts its lane
+        // T % 4, then the quad that does not hold lane T takes the other quad's value (a row shift by
+        // four lanes, written only to the banks of those quads)
+        const int x = __builtin_amdgcn_mov_dpp(v, (T % 4) * 0x55, 0xf, 0xf, true);
+        if constexpr (T < 4)
+            return __builtin_amdgcn_update_dpp(x, x, 0x114 /* row_shr:4 */, 0xf, 0xa, false);
+        else
+            return __builtin_amdgcn_update_dpp(x, x, 0x104 /* row_shl:4 */, 0xf, 0x5, false);
     } else {
         return __shfl(v, T, L);
     }
