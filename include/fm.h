@@ -117,6 +117,26 @@ int fm_forward(fm_matrix* m, const fm_params* p, const float* y /*DEVICE N, null
                float* q /*DEVICE N*/, float* r /*DEVICE N*/, double* loss_sum /*HOST*/,
                void* hip_stream);
 
+/* fm_forward for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same computation and same DEVICE outputs as
+ * fm_forward, from the same kernels; what differs:
+ *   - the call allocates and frees nothing and never waits for the stream;
+ *   - sums (DEVICE, 2 doubles, nullable; needs y) receives sum_i l_i (unscaled) and sum_i r_i;
+ *   - the per-workgroup partial sums live in a static device array of 2 MiB + 16 KiB that every
+ *     GPU the library runs on holds until the process ends (its address is resolved when a handle
+ *     is created on that GPU).  With sums the row kernel may have at most 262,144 workgroups
+ *     (N <= 16,777,216 at K = 16; 64 / lanes-per-row rows per wavefront, 4 wavefronts per
+ *     workgroup): larger N return FM_ERANGE.  Nothing in the array has to start at zero;
+ *   - all calls on one GPU share that array: calls that overlap in time on one GPU (two streams, two
+ *     handles, two threads) race on it when both ask for sums;
+ *   - FM_ESTATE while fm_profile_enable is on (the timers create events), or when the current
+ *     device is not the one the handle was created on. */
+int fm_forward_noalloc(fm_matrix* m, const fm_params* p, const float* y /*DEVICE N, nullable*/,
+                       const float* w0 /*DEVICE 1*/, const float* w /*DEVICE D*/, const float* V /*DEVICE D*K*/,
+                       float* yhat /*DEVICE N*/, float* a /*DEVICE N*/, float* G /*DEVICE N*K*/,
+                       float* q /*DEVICE N*/, float* r /*DEVICE N*/, double* sums /*DEVICE 2*/,
+                       void* hip_stream);
+
 /* Predictive performance of (w0, w, V) on this matrix and labels y, as the paper's figures report
  * it (Section 5, test RMSE for regression and test accuracy for classification):
  *   metrics[0] = mean loss (1/N) sum_i l_i   (p->loss; loss_scale is not applied)

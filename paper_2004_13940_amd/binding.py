@@ -35,7 +35,7 @@ class FMError(RuntimeError):
 
 EXPORTS = ["fm_build_csr", "fm_build_csc", "fm_partition", "fm_get_csc", "fm_get_block_index",
            "fm_get_stratum_nnz", "fm_get_stratum_csr", "fm_get_stratum_csc", "fm_partition_batches",
-           "fm_get_batch_csc", "fm_forward", "fm_evaluate", "fm_gradient",
+           "fm_get_batch_csc", "fm_forward", "fm_forward_noalloc", "fm_evaluate", "fm_gradient",
            "fm_sgd_epoch", "fm_minibatch_epoch", "fm_stratified_epoch", "fm_stratified_begin", "fm_stratified_step",
            "fm_stratified_end", "fm_get_aux", "fm_profile_enable", "fm_profile_kernels",
            "fm_profile_kernel_name", "fm_profile_read", "fm_set_tuning", "fm_set_tile_tuning", "fm_probe_gather", "fm_destroy", "fm_last_error"]
@@ -217,6 +217,19 @@ class Matrix:
                                       _vp(a), _vp(G), _vp(q), _vp(r),
                                       ctypes.byref(loss) if want_loss else ctypes.c_void_p(None), _stream(stream)))
         return loss.value if want_loss else None
+
+    def fm_forward_noalloc(self, p: fm_params, y, w0, w, V, yhat=None, a=None, G=None, q=None, r=None,
+                           sums=None, stream=None):
+        """sums: float64 CUDA tensor of 2 elements (sum of losses, sum of multipliers) or None."""
+        import torch
+        N, D, K = self.N, self.D, p.K
+        _dev(y, N, "y"); _dev(w0, 1, "w0"); _dev(w, D, "w"); _dev(V, D * K, "V")
+        _dev(yhat, N, "yhat"); _dev(a, N, "a"); _dev(G, N * K, "G"); _dev(q, N, "q"); _dev(r, N, "r")
+        if sums is not None and not (isinstance(sums, torch.Tensor) and sums.is_cuda and sums.dtype == torch.float64
+                                     and sums.is_contiguous() and sums.numel() == 2):
+            raise TypeError("sums must be a contiguous float64 CUDA tensor of 2 elements")
+        self._check(load().fm_forward_noalloc(self._h, ctypes.byref(p), _vp(y), _vp(w0), _vp(w), _vp(V), _vp(yhat),
+                                              _vp(a), _vp(G), _vp(q), _vp(r), _vp(sums), _stream(stream)))
 
     def fm_gradient(self, p: fm_params, r, G, w, V, grad_w0=None, grad_w=None, grad_V=None, stream=None):
         N, D, K = self.N, self.D, p.K

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfm_mi355x.so")
-SOURCES = ["fm_api.hip", "fm_build.hip", "fm_rows.hip", "fm_cols.hip", "fm_reduce.hip", "fm_probe.hip"]
+SOURCES = ["fm_api.hip", "fm_build.hip", "fm_rows.hip", "fm_cols.hip", "fm_reduce.hip", "fm_probe.hip", "fm_noalloc.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -161,10 +161,11 @@ extern "C" int fm_build_csr(int64_t N, int64_t D, int64_t nnz, const int64_t* ro
     rc = up((void**)&m->rowptr, rowptr, (size_t)(N + 1) * sizeof(int64_t));
     if (rc == FM_OK) rc = up((void**)&m->col, col, (size_t)nnz * sizeof(int32_t));
     if (rc == FM_OK) rc = up((void**)&m->val, val, (size_t)nnz * sizeof(float));
-    if (rc == FM_OK) rc = fm_dev_alloc(m, (void**)&m->scal, (8 + 2048) * sizeof(double));
+    if (rc == FM_OK) rc = fm_dev_alloc(m, (void**)&m->scal, (8 + FM_REDUCE_TMP) * sizeof(double));
     if (rc == FM_OK && hipHostMalloc((void**)&m->h_scal, 8 * sizeof(double)) != hipSuccess)
         rc = fm_fail(m, FM_ENOMEM, "pinned allocation failed");
     if (rc == FM_OK && hipStreamSynchronize(st) != hipSuccess) rc = fm_fail(m, FM_EHIP, "upload failed");
+    if (rc == FM_OK) rc = fm_noalloc_init_device(m);  // set-up for fm_forward_noalloc on this device
     if (rc != FM_OK) {
         g_build_error = m->err;
         fm_destroy(m);

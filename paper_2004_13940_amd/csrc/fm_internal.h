@@ -235,6 +235,9 @@ struct RowArgs {
 };
 int fm_launch_rows(fm_matrix* m, const RowArgs& A, bool refresh, hipStream_t st);
 int64_t fm_rows_grid(int64_t N, int32_t K);
+// once per device, with that device current: resolves the address of the static scratch array of
+// fm_forward_noalloc (fm_noalloc.hip); called when a handle is created
+int fm_noalloc_init_device(fm_matrix* m);
 int fm_pack_aux(fm_matrix* m, const float* r, const float* G, hipStream_t st);  // packed layout only
 int fm_unpack_aux(fm_matrix* m, float* a, float* G, float* q, float* r, hipStream_t st);
 
@@ -296,7 +299,10 @@ int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st);
 // takes the postponed regulariser steps of every column up to stratum A.s (exclusive)
 int fm_launch_cols_flush(fm_matrix* m, const ColArgs& A, hipStream_t st);
 
-int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st);
+constexpr int FM_REDUCE_TMP = 2048;  // doubles of stage-1 scratch a reduction may use
+// tmp: FM_REDUCE_TMP doubles of device scratch, or nullptr for the handle's own
+int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st,
+                    double* tmp = nullptr);
 int fm_reduce_sum(fm_matrix* m, const float* x, int64_t n, int64_t stride, bool square, double* out1, hipStream_t st);
 int fm_reduce_eval(fm_matrix* m, const float* yhat, const float* y, int64_t n, int what, double* out1, hipStream_t st);
 int fm_fill_i32(fm_matrix* m, int32_t* x, int64_t n, int32_t v, hipStream_t st);

@@ -5,7 +5,7 @@
 namespace {
 
 constexpr int RED_THREADS = 1024;
-constexpr int RED_BLOCKS = 2048;
+constexpr int RED_BLOCKS = FM_REDUCE_TMP;
 
 __device__ __forceinline__ double block_sum_1024(double v, double* sh)
 {
@@ -127,10 +127,11 @@ __global__ void k_bias(float* w0, const double* rsum, float eta, float* grad_out
 
 }  // namespace
 
-int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st)
+int fm_reduce_pairs(fm_matrix* m, const float* part, int64_t nblocks, double* out2, hipStream_t st, double* tmp)
 {
-    // scal[8..8+RED_BLOCKS) is the stage-1 scratch (pairs: at most RED_BLOCKS / 2 workgroups)
-    double* tmp = m->scal + 8;
+    // stage-1 scratch of FM_REDUCE_TMP doubles (pairs: at most RED_BLOCKS / 2 workgroups); by default
+    // scal[8..8+RED_BLOCKS)
+    if (tmp == nullptr) tmp = m->scal + 8;
     int nb = (int)((nblocks + 4 * RED_THREADS - 1) / (4 * RED_THREADS));
     if (nb < 1) nb = 1;
     if (nb > RED_BLOCKS / 2) nb = RED_BLOCKS / 2;
