@@ -86,56 +86,87 @@ def _zipf_draw(rng: np.random.Generator, cdf: np.ndarray, size: int) -> np.ndarr
     return r
 
 
+_CHUNKS = 64    # fixed, so that the arrays do not depend on the number of threads
+_THREADS = 16
+
+
+def _row_chunks(N: int) -> list[tuple[int, int]]:
+    return [((c * N) // _CHUNKS, ((c + 1) * N) // _CHUNKS) for c in range(_CHUNKS) if (c * N) // _CHUNKS < ((c + 1) * N) // _CHUNKS]
+
+
 def _distinct_zipf_rows(rng, lengths: np.ndarray, cdf: np.ndarray,
                         rank_to_col: np.ndarray | None) -> tuple[np.ndarray, np.ndarray]:
     """Draw ``lengths[i]`` distinct Zipf columns for every row (collisions are
-    redrawn) and return (rowptr, sorted columns)."""
+    redrawn) and return (rowptr, sorted columns).  Rows are handled in fixed chunks, each with
+    its own child stream of ``rng``, by a pool of threads."""
     N = len(lengths)
     rowptr = np.zeros(N + 1, dtype=np.int64)
     np.cumsum(lengths, out=rowptr[1:])
-    nnz = int(rowptr[-1])
-    rows = np.repeat(np.arange(N, dtype=np.int64), lengths)
-    cols = _zipf_draw(rng, cdf, nnz).astype(np.int64)
+    cols = np.empty(int(rowptr[-1]), dtype=np.int32)
     Dn = len(cdf)
-    for _ in range(10_000):
-        key = rows * Dn + cols
-        order = np.argsort(key, kind="stable")
-        ks = key[order]
-        dup = np.zeros(nnz, dtype=bool)
-        dup[order[1:]] = ks[1:] == ks[:-1]
-        nd = int(dup.sum())
-        if nd == 0:
-            break
-        cols[dup] = _zipf_draw(rng, cdf, nd)
-    else:  # pragma: no cover
-        raise RuntimeError("could not make columns distinct")
-    if rank_to_col is not None:
-        cols = rank_to_col[cols]
-    key = rows * Dn + cols
-    key.sort()
-    cols = (key - rows * Dn).astype(np.int32)
+    chunks = _row_chunks(N)
+    streams = rng.spawn(len(chunks))
+
+    def work(t):
+        (lo, hi), g = chunks[t], streams[t]
+        n = int(rowptr[hi] - rowptr[lo])
+        rows = np.repeat(np.arange(lo, hi, dtype=np.int64), lengths[lo:hi])
+        # keys (row, column) kept sorted: duplicates are then neighbours, and since every row keeps
+        # its length the sorted keys line up with `rows` again after every round
+        key = rows * Dn + _zipf_draw(g, cdf, n)
+        for _ in range(10_000):
+            key.sort()
+            dup = np.flatnonzero(key[1:] == key[:-1]) + 1
+            if len(dup) == 0:
+                break
+            key[dup] = rows[dup] * Dn + _zipf_draw(g, cdf, len(dup))
+        else:  # pragma: no cover
+            raise RuntimeError("could not make columns distinct")
+        if rank_to_col is not None:
+            key = rows * Dn + rank_to_col[key - rows * Dn]
+            key.sort()
+        cols[rowptr[lo]:rowptr[hi]] = key - rows * Dn
+
+    with ThreadPoolExecutor(max_workers=_THREADS) as ex:
+        list(ex.map(work, range(len(chunks))))
     return rowptr, cols
 
 
 def _teacher_score(rowptr, col, val, N, D, w_star, V_star) -> np.ndarray:
     """Score of the planted teacher on every row (label synthesis only)."""
-    X = sp.csr_matrix((val.astype(np.float64), col, rowptr), shape=(N, D))
-    lin = X @ w_star
-    G = X @ V_star
-    X2 = X.copy()
-    X2.data **= 2
-    q = X2 @ (V_star ** 2).sum(axis=1)
-    return lin + 0.5 * ((G ** 2).sum(axis=1) - q)
+    n2 = (V_star ** 2).sum(axis=1)
+    out = np.empty(N)
+
+    def work(ch):
+        lo, hi = ch
+        e0, e1 = int(rowptr[lo]), int(rowptr[hi])
+        X = sp.csr_matrix((val[e0:e1].astype(np.float64), col[e0:e1], rowptr[lo:hi + 1] - e0), shape=(hi - lo, D))
+        G = X @ V_star
+        X2 = X.copy()
+        X2.data **= 2
+        out[lo:hi] = X @ w_star + 0.5 * ((G ** 2).sum(axis=1) - X2 @ n2)
+
+    with ThreadPoolExecutor(max_workers=_THREADS) as ex:
+        list(ex.map(work, _row_chunks(N)))
+    return out
 
 
 def _init_params(rng, D, K):
     w0 = np.float32(0.0)
     w = np.zeros(D, dtype=np.float32)
     V = np.empty((D, K), dtype=np.float32)
-    step = max(1, (1 << 24) // max(K, 1))
-    for a in range(0, D, step):  # chunked: V can be several GB
-        b = min(D, a + step)
-        V[a:b] = rng.standard_normal((b - a, K), dtype=np.float32) * np.float32(0.01)
+    chunks = _row_chunks(D)
+    streams = rng.spawn(len(chunks))
+
+    def work(t):
+        (a, b), g = chunks[t], streams[t]
+        step = max(1, (1 << 22) // max(K, 1))
+        for c in range(a, b, step):  # chunked: V can be several GB
+            d = min(b, c + step)
+            V[c:d] = g.standard_normal((d - c, K), dtype=np.float32) * np.float32(0.01)
+
+    with ThreadPoolExecutor(max_workers=_THREADS) as ex:
+        list(ex.map(work, range(len(chunks))))
     return w0, w, V
 
 

@@ -8,6 +8,7 @@ from oracle import fm_oracle as O
 from paper_2004_13940_amd.workloads import make_config, random_csr
 
 from helpers import REL_TOL, assert_close, dev_params, oracle_kw, to_dev
+from helpers import run_full_epochs as _run_full_epochs, run_stratified_epochs as _run_stratified_epochs
 
 pytestmark = pytest.mark.gpu
 
@@ -210,76 +211,6 @@ def test_empty_rows_empty_columns_and_zero_entries():
 
 
 # ------------------------------------------------------------ full epochs ----
-
-def _run_full_epochs(B, wl, epochs, m=None):
-    """epochs of fm_sgd_epoch vs the oracle's full_epoch; returns final states."""
-    import torch
-    X = O.make_matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
-    if m is None:
-        m = B.Matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
-        m.fm_build_csc()
-    p = B.make_params(wl.K, wl.loss, wl.lambda_w, wl.lambda_v, wl.eta, wl.loss_scale, wl.update_w0)
-    d_w0, d_w, d_V = dev_params(wl.w0, wl.w, wl.V)
-    d_y = to_dev(wl.y)
-    w0, w, V = float(wl.w0), wl.w.astype(np.float64), wl.V.astype(np.float64)
-    kw = oracle_kw(wl)
-    for ep in range(epochs):
-        obj = m.fm_sgd_epoch(p, d_y, d_w0, d_w, d_V, want_objective=True)
-        w0, w, V, wobj = O.full_epoch(X, wl.y, w0, w, V, update_w0=bool(wl.update_w0), **kw)
-        torch.cuda.synchronize()
-        _say(f"  epoch {ep}: objective gpu {obj[0] + obj[1]:.8f} oracle {wobj[0] + wobj[1]:.8f}")
-        assert abs(obj[0] - wobj[0]) <= REL_TOL * abs(wobj[0]), f"data term, epoch {ep}"
-        assert abs(obj[1] - wobj[1]) <= REL_TOL * abs(wobj[1]) + 1e-12, f"regulariser, epoch {ep}"
-        assert_close(d_w.cpu().numpy(), w, f"w after epoch {ep}")
-        assert_close(d_V.cpu().numpy().reshape(wl.D, wl.K), V, f"V after epoch {ep}")
-        assert abs(d_w0.item() - w0) <= REL_TOL * max(abs(w0), 1e-3), f"w0 after epoch {ep}"
-    return m, p, X, (d_w0, d_w, d_V, d_y), (w0, w, V)
-
-
-def _run_stratified_epochs(B, wl, m, p, X, dev, host, epochs, check_strata=False, **flags):
-    import torch
-    d_w0, d_w, d_V, d_y = dev
-    w0, w, V = host
-    for k, v in flags.items():
-        setattr(p, k, int(v))
-    kw = oracle_kw(wl)
-    okw = dict(reg_share=not flags.get("reg_full_per_cell", False), refresh_all_rows=flags.get("refresh_all_rows", False),
-               stale_aux=flags.get("stale_aux", False))
-    for ep in range(epochs):
-        if check_strata:
-            # step through the strata on both sides and compare the live aggregates
-            snaps = []
-            O.stratified_epoch(X, wl.y, w0, w, V, P=m.P, update_w0=bool(wl.update_w0), final_objective=False,
-                               on_stratum=lambda s, st: snaps.append({k: st[k].copy() for k in ("a", "G", "q", "r", "w", "V")}),
-                               **kw, **okw)
-            m.fm_stratified_begin(p, d_y, d_w0, d_w, d_V)
-            a, G, q, r = (torch.empty(n, device="cuda") for n in (wl.N, wl.N * wl.K, wl.N, wl.N))
-            for s in range(m.P):
-                m.fm_stratified_step(p, s, d_y, d_w0, d_w, d_V)
-                m.fm_get_aux(wl.K, a, G, q, r)
-                torch.cuda.synchronize()
-                for name, t in (("a", a), ("G", G), ("q", q), ("w", d_w), ("V", d_V)):
-                    assert_close(t.cpu().numpy(), snaps[s][name], f"{name} after stratum {s} of epoch {ep}")
-                # the library keeps r current with the refreshed aggregates; the oracle recomputes it
-                # at the start of the next cell step: same function of the same aggregates
-                want_r = O.multiplier_from_aux(wl.loss, wl.loss_scale, w0, snaps[s]["a"], snaps[s]["G"],
-                                               snaps[s]["q"], wl.y)
-                assert_close(r.cpu().numpy(), want_r, f"r after stratum {s} of epoch {ep}")
-            m.fm_stratified_end(p, d_w0)
-            obj = None
-        else:
-            obj = m.fm_stratified_epoch(p, d_y, d_w0, d_w, d_V, want_objective=True)
-        w0, w, V, wobj, _ = O.stratified_epoch(X, wl.y, w0, w, V, P=m.P, update_w0=bool(wl.update_w0), **kw, **okw)
-        torch.cuda.synchronize()
-        if obj is not None:
-            _say(f"  stratified epoch {ep}: objective gpu {obj[0] + obj[1]:.8f} oracle {wobj[0] + wobj[1]:.8f}")
-            assert abs(obj[0] - wobj[0]) <= REL_TOL * abs(wobj[0]), f"data term, stratified epoch {ep}"
-            assert abs(obj[1] - wobj[1]) <= REL_TOL * abs(wobj[1]) + 1e-12
-        assert_close(d_w.cpu().numpy(), w, f"w after stratified epoch {ep}")
-        assert_close(d_V.cpu().numpy().reshape(wl.D, wl.K), V, f"V after stratified epoch {ep}")
-        assert abs(d_w0.item() - w0) <= REL_TOL * max(abs(w0), 1e-3)
-    return (w0, w, V)
-
 
 def test_config1_ten_full_then_ten_stratified_epochs():
     B = _B()
