@@ -65,7 +65,7 @@ ProfScope::~ProfScope()
 }
 
 static const char* const kKernelNames[FMK_COUNT] = {
-    "rows_forward", "rows_refresh", "cols", "cols_long", "cols_tile", "cols_panel", "cols_finish", "reduce", "bias"};
+    "rows_forward", "rows_refresh", "cols", "cols_long", "cols_tile", "cols_finish", "reduce", "bias"};
 
 extern "C" int fm_profile_enable(fm_matrix* m, int32_t on)
 {
@@ -356,9 +356,8 @@ static int ensure_ws(fm_matrix* m, int32_t K)
     if (m->wsK == K) return FM_OK;
     fm_drop_workspace(m);
     if (m->has_csc) {  // the LDS tiles of the dense-ish columns are shaped for K
-        int shape[4];
+        int shape[3];
         fm_tile_shape(m->N, K, &shape[0], &shape[1], &shape[2]);
-        shape[3] = fm_panel_rows(m->N, K);
         if (memcmp(shape, m->lfull_shape, sizeof(shape)) != 0) {
             FM_HIP(m, hipDeviceSynchronize());
             FM_TRY(fm_build_full_index(m, K, nullptr));
@@ -409,20 +408,6 @@ static void fill_long(ColArgs& A, const LongIndex& li, int32_t s, bool strat)
     A.vlong = strat ? nullptr : li.vlong;
     A.nvlong = strat ? 0 : li.nvlong;
     A.vlong_items = fm_tune().vlong;
-    const PanelIndex& pi = li.panel;
-    const bool with_panel = !strat && pi.rec != nullptr;
-    A.p_rec = with_panel ? pi.rec : nullptr;
-    A.p_gptr = pi.gptr;
-    A.p_gitem = pi.gitem;
-    A.p_rows = pi.rows;
-    A.p_npx = pi.npx;
-    A.p_nitems = with_panel ? pi.nitems : 0;
-    A.p_ngroups = pi.ngroups;
-    A.p_smax = pi.smax;
-    A.p_wgs = fm_tune().ppanel_wgs;
-    A.p_done = pi.done;
-    A.p_lag = fm_tune().ppanel_lag;
-    A.p_spin = 1 << 12;
     const int64_t s0 = strat ? li.h_short_off[s] : 0, s1 = strat ? li.h_short_off[s + 1] : li.nshort;
     A.short_col = li.short_col != nullptr ? li.short_col + s0 : nullptr;
     A.nshort = s1 - s0;

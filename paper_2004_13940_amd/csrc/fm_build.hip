@@ -375,15 +375,6 @@ __device__ __forceinline__ int64_t first_row_at_least(const int32_t* __restrict_
     return lo;
 }
 
-// Sub-columns of a column with cnt entries for the walk with accumulators in LDS: about `unit`
-// entries per panel of `rows` rows each (the same formula on the host and on the device).
-__host__ __device__ inline int64_t fm_panel_subs(int64_t cnt, int64_t N, int64_t rows, int64_t unit)
-{
-    const int64_t per_panel = (cnt * rows + N - 1) / N;  // cnt <= N < 2^31, rows <= 2^16
-    const int64_t S = (per_panel + unit - 1) / unit;
-    return S < 1 ? 1 : S;
-}
-
 // Items of every long column of the full matrix.  A column with fewer than heavy_min
 // entries is cut into consecutive segments of `seg` entries.  A heavy column is first
 // cut at the boundaries of the row panels [b*panel, (b+1)*panel) and every piece then
@@ -398,8 +389,7 @@ __host__ __device__ inline int64_t fm_panel_subs(int64_t cnt, int64_t N, int64_t
 __global__ __launch_bounds__(256) void k_full_items(const int64_t* __restrict__ colptr, const int32_t* __restrict__ crow,
                                                     const int32_t* __restrict__ long_col, int64_t N, int seg,
                                                     int64_t panel, int64_t heavy_min, int64_t maxpos, int64_t tile,
-                                                    int64_t tile_min, int tseg, int64_t pp_min, int64_t pp_max, int64_t pp_rows,
-                                                    int64_t pp_unit, uint32_t pp_key, int pass,
+                                                    int64_t tile_min, int tseg, int pass,
                                                     int64_t* __restrict__ nitems, const int64_t* __restrict__ long_first,
                                                     int32_t* __restrict__ item_col, int64_t* __restrict__ item_beg,
                                                     int32_t* __restrict__ item_len, uint32_t* __restrict__ item_key)
@@ -409,23 +399,6 @@ __global__ __launch_bounds__(256) void k_full_items(const int64_t* __restrict__ 
     const int32_t j = long_col[lc];
     const int64_t beg = colptr[j], end = colptr[j + 1], cnt = end - beg;
     const int64_t first = pass ? long_first[lc] : 0;
-    if (cnt >= pp_min && cnt < pp_max) {
-        // walked panel by panel with the accumulators in LDS: one partial row per sub-column and XCD,
-        // written by k_cols_panel; the item records only reserve the ids and sort behind everything else
-        const int64_t nit = FM_XCDS * fm_panel_subs(cnt, N, pp_rows, pp_unit);
-        if (!pass) {
-            if (threadIdx.x == 0) nitems[lc] = nit;
-            return;
-        }
-        for (int64_t k = threadIdx.x; k < nit; k += blockDim.x) {
-            const int64_t slot = first + k;
-            item_col[slot] = j;
-            item_beg[slot] = beg;
-            item_len[slot] = 0;
-            item_key[slot] = pp_key;
-        }
-        return;
-    }
     const bool tiled = cnt >= tile_min;
     if (!tiled && cnt < heavy_min) {
         const int64_t nit = (cnt + seg - 1) / seg;
@@ -521,77 +494,6 @@ __global__ void k_list_offsets(const uint32_t* __restrict__ keys, int64_t n, int
         if ((int64_t)keys[mid] < bound) lo = mid + 1; else hi = mid;
     }
     list_off[x] = lo;
-}
-
-__global__ void k_long_counts(const int64_t* __restrict__ colptr, const int32_t* __restrict__ long_col, int64_t nlong,
-                              int64_t* __restrict__ cnt)
-{
-    const int64_t lc = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (lc < nlong) cnt[lc] = colptr[long_col[lc] + 1] - colptr[long_col[lc]];
-}
-
-// Runs of the panel walk.  Instance i = (column, sub-column) lives in slot inst_slot[i] of group
-// inst_group[i] of every XCD; its run in panel b holds the column's entries with rows in sub-range
-// inst_sub[i] of inst_S[i] of that panel.  Runs are numbered in reading order:
-//   R = ((x * I + goff[g]) * npx) + pi * nslots(g) + slot,   x = b % FM_XCDS, pi = b / FM_XCDS.
-struct PanelInst {
-    const int32_t *col, *sub, *S, *group, *slot;
-    const int32_t* goff;  // [ngroups + 1] instances before each group
-    int64_t I, npx, rows;
-};
-
-__device__ __forceinline__ int64_t panel_run_id(const PanelInst& P, int64_t i, int64_t b)
-{
-    const int64_t x = b % FM_XCDS, pi = b / FM_XCDS;
-    const int32_t g = P.group[i];
-    const int64_t ns = P.goff[g + 1] - P.goff[g];
-    return (x * P.I + P.goff[g]) * P.npx + pi * ns + P.slot[i];
-}
-
-__global__ void k_panel_runs(const PanelInst P, const int64_t* __restrict__ colptr, const int32_t* __restrict__ crow,
-                             int64_t* __restrict__ run_len, int64_t* __restrict__ run_src)
-{
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t nb = P.npx * FM_XCDS;
-    if (t >= P.I * nb) return;
-    const int64_t i = t / nb, b = t % nb;
-    const int64_t j = P.col[i];
-    const int64_t cb = colptr[j], ce = colptr[j + 1];
-    const int64_t S = P.S[i], sb = P.sub[i];
-    const int64_t r0 = b * P.rows + (sb * P.rows) / S, r1 = b * P.rows + ((sb + 1) * P.rows) / S;
-    const int64_t lo = first_row_at_least(crow, cb, ce, r0);
-    const int64_t hi = first_row_at_least(crow, lo, ce, r1);
-    const int64_t R = panel_run_id(P, i, b);
-    run_len[R] = hi - lo;
-    run_src[R] = lo;
-}
-
-__global__ void k_panel_fill(const PanelInst P, const int32_t* __restrict__ crow, const float* __restrict__ cval,
-                             const int64_t* __restrict__ run_start, const int64_t* __restrict__ run_src,
-                             uint2* __restrict__ rec)
-{
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t nb = P.npx * FM_XCDS;
-    if (t >= P.I * nb) return;
-    const int64_t i = t / nb, b = t % nb;
-    const int64_t R = panel_run_id(P, i, b);
-    const int64_t dst = run_start[R], len = run_start[R + 1] - dst, src = run_src[R];
-    const uint32_t tag = (uint32_t)P.slot[i] << 28;
-    for (int64_t e = 0; e < len; ++e)
-        rec[dst + e] = make_uint2((uint32_t)crow[src + e] | tag, __float_as_uint(cval[src + e]));
-}
-
-// gptr[(x * ngroups + g) * (npx + 1) + pi] = first record of panel pi of group g on XCD x (pi = npx: the end)
-__global__ void k_panel_gptr(const int32_t* __restrict__ goff, int64_t I, int64_t npx, int32_t ngroups,
-                             const int64_t* __restrict__ run_start, int64_t* __restrict__ gptr)
-{
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t per = npx + 1;
-    if (t >= (int64_t)FM_XCDS * ngroups * per) return;
-    const int64_t pi = t % per, xg = t / per;
-    const int64_t g = xg % ngroups, x = xg / ngroups;
-    const int64_t ns = goff[g + 1] - goff[g];
-    gptr[t] = run_start[(x * I + goff[g]) * npx + pi * ns];
 }
 
 inline unsigned blocks_for(int64_t n, int t) { return (unsigned)((n + t - 1) / t); }
@@ -803,10 +705,7 @@ static FmTune& tune_mut()
     static FmTune t = {env_int("FM_SEG", 256, 16, 1 << 20), env_int("FM_PANEL", 32768, 64, 1 << 30),
                        env_int("FM_HEAVY_PER_PANEL", 16, 1, 1 << 20), env_int("FM_VLONG", 512, 1, 1 << 30),
                        env_int("FM_MIN_PANELS", 8 * FM_XCDS, 1, 1 << 30), env_int("FM_TILE", 0, 0, 1 << 20),
-                       env_int("FM_TILE_MIN", -1, -1, 1 << 20), env_int("FM_TILE_SEG", 0, 0, 1 << 20), 0,
-                       env_int("FM_PPANEL", 8192, 0, 65536), env_int("FM_PPANEL_MIN", 4, 1, 1 << 20),
-                       env_int("FM_PPANEL_UNIT", 64, 8, 1 << 16), env_int("FM_PPANEL_WGS", 64, 1, 4096),
-                       env_int("FM_PPANEL_LAG", 1, 1, 64)};
+                       env_int("FM_TILE_MIN", -1, -1, 1 << 20), env_int("FM_TILE_SEG", 0, 0, 1 << 20), 0};
     static const bool once = [] {
         t.seg_strat = env_int("FM_SEG_STRAT", 0, 0, 1 << 20);  // 0: chosen per matrix
         return true;
@@ -844,8 +743,6 @@ static void free_long_index(fm_matrix* m, LongIndex* li)
                     (void*)li->item_len, (void*)li->short_col, (void*)li->order, (void*)li->ord_beg,
                     (void*)li->ord_len, (void*)li->tile_ptr, (void*)li->vlong})
         if (p != nullptr) fm_dev_free(m, p);
-    for (void* p : {(void*)li->panel.rec, (void*)li->panel.gptr, (void*)li->panel.gitem, (void*)li->panel.done})
-        if (p != nullptr) fm_dev_free(m, p);
     *li = LongIndex();
 }
 
@@ -870,136 +767,6 @@ void fm_tile_shape(int64_t N, int32_t K, int* tile_rows, int* tile_min, int* til
     *tile_seg = T.tile_seg > 0 ? T.tile_seg : seg;
 }
 
-// Rows per panel of the walk with accumulators in LDS: only for aggregates kept as packed rows (the
-// kernel reads a row with one request per entry), and only when every XCD gets at least 8 panels;
-// the panel shrinks (down to 1024 rows) for matrices of moderate height.
-int fm_panel_rows(int64_t N, int32_t K)
-{
-    const FmTune& T = fm_tune();
-    if (T.ppanel <= 0 || K <= 0 || fm_cols_packed_mode(K) != FM_PACKED_LANE || N >= (int64_t(1) << 28)) return 0;
-    int64_t rows = T.ppanel;
-    while (rows > 1024 && N / rows < 8 * FM_XCDS) rows /= 2;
-    return N / rows >= 8 * FM_XCDS ? (int)rows : 0;
-}
-
-namespace {
-constexpr int PANEL_NG = FM_BLOCK / 8;  // lane groups of 8 per workgroup of k_cols_panel
-// accumulator slots per group, at most 16 (LDS: 32 groups x slots x (K+4) doubles)
-static int panel_smax() { static const int v = env_int("FM_PPANEL_SMAX", 12, 1, 16); return v; }
-#define PANEL_SMAX panel_smax()
-
-// The panel walk of the columns with at least min_cnt entries: sub-columns, their assignment to the
-// lane groups of an XCD (largest first onto the least loaded group that has a free slot, so that the
-// groups of an XCD walk the panels at the same pace), the entries copied into reading order.
-int build_panel_index(fm_matrix* m, LongIndex* out, const std::vector<int32_t>& h_lcol,
-                      const std::vector<int64_t>& h_cnt, const std::vector<int64_t>& h_first, int64_t rows,
-                      int64_t min_cnt, int64_t max_cnt, int64_t unit, hipStream_t st)
-{
-    PanelIndex& P = out->panel;
-    struct Inst {
-        int32_t col, sub, S;
-        int64_t item0;  // first item id of the column
-        double weight;
-    };
-    std::vector<Inst> inst;
-    for (size_t lc = 0; lc < h_lcol.size(); ++lc) {
-        if (h_cnt[lc] < min_cnt || h_cnt[lc] >= max_cnt) continue;
-        const int64_t S = fm_panel_subs(h_cnt[lc], m->N, rows, unit);
-        for (int64_t sb = 0; sb < S; ++sb)
-            inst.push_back({h_lcol[lc], (int32_t)sb, (int32_t)S, h_first[lc], (double)h_cnt[lc] / (double)S});
-    }
-    const int64_t I = (int64_t)inst.size();
-    if (I == 0) return FM_OK;
-    int64_t ngroups = (int64_t)fm_tune().ppanel_wgs * PANEL_NG;
-    if (I * 2 > ngroups * PANEL_SMAX) ngroups = (I * 2 / PANEL_SMAX + PANEL_NG) / PANEL_NG * PANEL_NG;
-    // assignment: instances by decreasing weight; a binary heap of (load, group) over the groups with a free slot
-    std::vector<int64_t> by(I);
-    for (int64_t i = 0; i < I; ++i) by[i] = i;
-    std::stable_sort(by.begin(), by.end(), [&](int64_t a, int64_t b) { return inst[a].weight > inst[b].weight; });
-    std::vector<std::pair<double, int32_t>> heap;
-    for (int32_t g = 0; g < ngroups; ++g) heap.push_back({0.0, g});
-    auto cmp = [](const std::pair<double, int32_t>& a, const std::pair<double, int32_t>& b) {
-        return a.first > b.first || (a.first == b.first && a.second > b.second);
-    };
-    std::make_heap(heap.begin(), heap.end(), cmp);
-    std::vector<int32_t> h_group(I), h_slot(I), h_ns(ngroups, 0);
-    for (int64_t k = 0; k < I; ++k) {
-        std::pop_heap(heap.begin(), heap.end(), cmp);
-        std::pair<double, int32_t> top = heap.back();
-        heap.pop_back();
-        const int64_t i = by[k];
-        h_group[i] = top.second;
-        h_slot[i] = h_ns[top.second]++;
-        top.first += inst[i].weight;
-        if (h_ns[top.second] < PANEL_SMAX) {
-            heap.push_back(top);
-            std::push_heap(heap.begin(), heap.end(), cmp);
-        }
-    }
-    std::vector<int32_t> h_goff(ngroups + 1, 0);
-    for (int64_t g = 0; g < ngroups; ++g) h_goff[g + 1] = h_goff[g] + h_ns[g];
-    const int64_t npanels = (m->N + rows - 1) / rows;
-    const int64_t npx = (npanels + FM_XCDS - 1) / FM_XCDS;
-    std::vector<int32_t> h_col(I), h_sub(I), h_S(I);
-    std::vector<int32_t> h_gitem((size_t)FM_XCDS * ngroups * PANEL_SMAX, -1);
-    for (int64_t i = 0; i < I; ++i) {
-        h_col[i] = inst[i].col;
-        h_sub[i] = inst[i].sub;
-        h_S[i] = inst[i].S;
-        for (int x = 0; x < FM_XCDS; ++x)
-            h_gitem[((size_t)x * ngroups + h_group[i]) * PANEL_SMAX + h_slot[i]] =
-                (int32_t)(inst[i].item0 + (int64_t)inst[i].sub * FM_XCDS + x);
-    }
-    int32_t *d_col = nullptr, *d_sub = nullptr, *d_S = nullptr, *d_group = nullptr, *d_slot = nullptr, *d_goff = nullptr;
-    auto up = [&](int32_t** d, const std::vector<int32_t>& h) -> int {
-        FM_TRY(fm_dev_alloc(m, (void**)d, h.size() * sizeof(int32_t)));
-        FM_HIP(m, hipMemcpyAsync(*d, h.data(), h.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
-        return FM_OK;
-    };
-    FM_TRY(up(&d_col, h_col));
-    FM_TRY(up(&d_sub, h_sub));
-    FM_TRY(up(&d_S, h_S));
-    FM_TRY(up(&d_group, h_group));
-    FM_TRY(up(&d_slot, h_slot));
-    FM_TRY(up(&d_goff, h_goff));
-    FM_TRY(up(&P.gitem, h_gitem));
-    const PanelInst pin = {d_col, d_sub, d_S, d_group, d_slot, d_goff, I, npx, rows};
-    const int64_t nruns = I * npx * FM_XCDS;
-    int64_t *run_len = nullptr, *run_src = nullptr;
-    FM_TRY(fm_dev_alloc(m, (void**)&run_len, (size_t)(nruns + 1) * sizeof(int64_t)));
-    FM_TRY(fm_dev_alloc(m, (void**)&run_src, (size_t)nruns * sizeof(int64_t)));
-    FM_HIP(m, hipMemsetAsync(run_len + nruns, 0, sizeof(int64_t), st));
-    hipLaunchKernelGGL(k_panel_runs, dim3(blocks_for(nruns, 256)), dim3(256), 0, st, pin, (const int64_t*)m->colptr,
-                       (const int32_t*)m->crow, run_len, run_src);
-    FM_HIP(m, hipGetLastError());
-    FM_TRY(fm_scan_exclusive_i64(m, run_len, nruns + 1, st));
-    int64_t nent = 0;
-    FM_HIP(m, hipMemcpyAsync(&nent, run_len + nruns, sizeof(int64_t), hipMemcpyDeviceToHost, st));
-    FM_HIP(m, hipStreamSynchronize(st));
-    FM_TRY(fm_dev_alloc(m, (void**)&P.rec, (size_t)std::max<int64_t>(nent, 1) * sizeof(uint2)));
-    hipLaunchKernelGGL(k_panel_fill, dim3(blocks_for(nruns, 256)), dim3(256), 0, st, pin, (const int32_t*)m->crow,
-                       (const float*)m->cval, (const int64_t*)run_len, (const int64_t*)run_src, P.rec);
-    FM_HIP(m, hipGetLastError());
-    const int64_t ngp = (int64_t)FM_XCDS * ngroups * (npx + 1);
-    FM_TRY(fm_dev_alloc(m, (void**)&P.gptr, (size_t)ngp * sizeof(int64_t)));
-    hipLaunchKernelGGL(k_panel_gptr, dim3(blocks_for(ngp, 256)), dim3(256), 0, st, (const int32_t*)d_goff, I, npx,
-                       (int32_t)ngroups, (const int64_t*)run_len, P.gptr);
-    FM_HIP(m, hipGetLastError());
-    FM_TRY(fm_dev_alloc(m, (void**)&P.done, (size_t)FM_XCDS * npx * sizeof(int32_t)));
-    FM_HIP(m, hipStreamSynchronize(st));
-    for (void* q : {(void*)d_col, (void*)d_sub, (void*)d_S, (void*)d_group, (void*)d_slot, (void*)d_goff,
-                    (void*)run_len, (void*)run_src})
-        fm_dev_free(m, q);
-    P.rows = rows;
-    P.npx = npx;
-    P.ngroups = (int32_t)ngroups;
-    P.smax = PANEL_SMAX;
-    P.nentries = nent;
-    P.nitems = I * FM_XCDS;
-    return FM_OK;
-}
-}  // namespace
-
 int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st)
 {
     LongIndex* out = &m->lfull;
@@ -1009,8 +776,6 @@ int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st)
     m->lfull_shape[0] = T.tile;
     m->lfull_shape[1] = T.tile_min;
     m->lfull_shape[2] = T.tile_seg;
-    const int64_t pp_rows = fm_panel_rows(m->N, K);
-    m->lfull_shape[3] = (int)pp_rows;
     FM_TRY(build_short_list(m, m->colptr, m->D, m->D, 1, fm_tune().seg, out, st));
     out->nlong = out->nitems = 0;
     out->h_long_off.assign(2, 0);
@@ -1064,19 +829,10 @@ int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st)
                                  : INT64_MAX;
     const int64_t key_tiles = (int64_t)FM_XCDS * (maxpos + 1);
     if (key_tiles + nrtiles >= (1LL << 32)) return fm_fail(m, FM_ERANGE, "too many row tiles");
-    // columns dense enough for the panel walk with accumulators in LDS take that path before any other
-    const uint32_t pp_key = (uint32_t)(key_tiles + nrtiles);  // sorts behind every other item
-    const int64_t pp_unit = T.ppanel_unit;
-    const int64_t pp_min =
-        pp_rows > 0 ? std::max<int64_t>(((int64_t)T.ppanel_min * m->N + pp_rows - 1) / pp_rows, (int64_t)T.seg + 1)
-                    : INT64_MAX;
-    // denser columns stay with the LDS-staged kernel unless FM_PPANEL_ALL=1
-    static const bool pp_all = env_int("FM_PPANEL_ALL", 0, 0, 1) != 0;
-    const int64_t pp_max = pp_all ? INT64_MAX : tile_min;
     FM_HIP(m, hipMemsetAsync(out->long_first, 0, (size_t)(nlong + 1) * sizeof(int64_t), st));
     hipLaunchKernelGGL(k_full_items, dim3((unsigned)nlong), dim3(256), 0, st, (const int64_t*)m->colptr,
                        (const int32_t*)m->crow, (const int32_t*)out->long_col, m->N, T.seg, panel, heavy_min,
-                       maxpos, tile, tile_min, T.tile_seg, pp_min, pp_max, pp_rows, pp_unit, pp_key, 0, out->long_first, (const int64_t*)nullptr, (int32_t*)nullptr, (int64_t*)nullptr,
+                       maxpos, tile, tile_min, T.tile_seg, 0, out->long_first, (const int64_t*)nullptr, (int32_t*)nullptr, (int64_t*)nullptr,
                        (int32_t*)nullptr, (uint32_t*)nullptr);
     FM_HIP(m, hipGetLastError());
     FM_TRY(fm_scan_exclusive_i64(m, out->long_first, nlong + 1, st));
@@ -1096,7 +852,7 @@ int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st)
     FM_TRY(fm_dev_alloc(m, (void**)&i1, (size_t)nitems * 4));
     hipLaunchKernelGGL(k_full_items, dim3((unsigned)nlong), dim3(256), 0, st, (const int64_t*)m->colptr,
                        (const int32_t*)m->crow, (const int32_t*)out->long_col, m->N, T.seg, panel, heavy_min,
-                       maxpos, tile, tile_min, T.tile_seg, pp_min, pp_max, pp_rows, pp_unit, pp_key, 1, (int64_t*)nullptr, (const int64_t*)out->long_first, out->item_col, out->item_beg,
+                       maxpos, tile, tile_min, T.tile_seg, 1, (int64_t*)nullptr, (const int64_t*)out->long_first, out->item_col, out->item_beg,
                        out->item_len, k0);
     FM_HIP(m, hipGetLastError());
     // 3. processing order: stable sort of the item ids by (XCD list, panel position)
@@ -1113,26 +869,9 @@ int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st)
     FM_HIP(m, hipStreamSynchronize(st));
     for (int x = 0; x <= FM_XCDS; ++x) out->list_off[x] = h_off[x];
     for (int x = 0; x < FM_XCDS; ++x) out->list_mid[x] = h_off[FM_XCDS + 1 + x];
-    // the panel walk: which long columns take it, and how many items that reserves at the end of the order
-    std::vector<int32_t> h_lcol((size_t)nlong);
-    std::vector<int64_t> h_cnt((size_t)nlong);
-    int64_t npanel_items = 0;
-    if (pp_rows > 0) {
-        int64_t* d_cnt = nullptr;
-        FM_TRY(fm_dev_alloc(m, (void**)&d_cnt, (size_t)nlong * sizeof(int64_t)));
-        hipLaunchKernelGGL(k_long_counts, dim3(blocks_for(nlong, 256)), dim3(256), 0, st, (const int64_t*)m->colptr,
-                           (const int32_t*)out->long_col, nlong, d_cnt);
-        FM_HIP(m, hipGetLastError());
-        FM_HIP(m, hipMemcpyAsync(h_cnt.data(), d_cnt, (size_t)nlong * sizeof(int64_t), hipMemcpyDeviceToHost, st));
-        FM_HIP(m, hipMemcpyAsync(h_lcol.data(), out->long_col, (size_t)nlong * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-        FM_HIP(m, hipStreamSynchronize(st));
-        fm_dev_free(m, d_cnt);
-        for (int64_t lc = 0; lc < nlong; ++lc)
-            if (h_cnt[(size_t)lc] >= pp_min && h_cnt[(size_t)lc] < pp_max) npanel_items += h_first[(size_t)lc + 1] - h_first[(size_t)lc];
-    }
     out->tile_rows = tile;
     out->ntiles = 0;
-    if (out->list_off[FM_XCDS] < nitems - npanel_items) {  // there are tile items
+    if (out->list_off[FM_XCDS] < nitems) {  // there are tile items
         out->ntiles = nrtiles;
         FM_TRY(fm_dev_alloc(m, (void**)&out->tile_ptr, (size_t)(nrtiles + 1) * sizeof(int64_t)));
         hipLaunchKernelGGL(k_tile_ptr, dim3(blocks_for(nrtiles + 1, 256)), dim3(256), 0, st,
@@ -1152,11 +891,6 @@ int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st)
     fm_dev_free(m, k0);
     fm_dev_free(m, k1);
     fm_dev_free(m, d_off);
-    if (npanel_items > 0) {
-        if (nitems >= (1LL << 31)) return fm_fail(m, FM_ERANGE, "too many column items for the panel walk");
-        FM_TRY(build_panel_index(m, out, h_lcol, h_cnt, h_first, pp_rows, pp_min, pp_max, pp_unit, st));
-        if (out->panel.nitems != npanel_items) return fm_fail(m, FM_EHIP, "panel items do not add up");
-    }
     // 4. columns with very many items get a workgroup each in the finish step
     std::vector<int32_t> h_vlong;
     for (int64_t lc = 0; lc < nlong; ++lc)

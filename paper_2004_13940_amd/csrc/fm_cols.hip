@@ -13,9 +13,6 @@
 // in a fixed order, so results are bit-reproducible from run to run.  Items of heavy
 // columns are cut at row-panel boundaries and handed out panel by panel, one panel at a
 // time per XCD, so that the gathered rows of G stay in that XCD's L2.
-#include <stdio.h>
-#include <stdlib.h>
-
 #include "fm_device.h"
 #include "fm_internal.h"
 
@@ -479,136 +476,6 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_tile(const ColArgs A)
     }
 }
 
-// Heavy columns walked panel by panel with the accumulators in LDS (see PanelIndex).  Workgroup b runs
-// on XCD b % FM_XCDS and its lane groups walk the panels of that XCD in ascending order, all at about
-// the same pace (the builder balances the entries per panel over the groups), so that a panel's
-// aggregate rows are fetched into that XCD's L2 once and then hit.  A group owns up to p_smax
-// sub-columns: their sums over all panels of the XCD live in its private part of LDS (fp64; a run of
-// one sub-column inside one panel is summed in fp32 registers first), so nothing is written per panel
-// and panels can be small.  At the end every sub-column's sums go out as one partial row, added to the
-// other XCDs' and sub-columns' rows of the same column by the finish kernels in a fixed order.
-// Packed aggregate rows only: 8 lanes per group, lane rl = K/4 reads the multiplier.
-template <int RL>
-__global__ __launch_bounds__(FM_BLOCK) void k_cols_panel(const ColArgs A)
-{
-    constexpr int L = 8, VEC = 4, NG = FM_BLOCK / L, S = 16, U = S / L;
-    constexpr int FLUSH_EVERY = 8;  // chunks: an fp32 sum never runs over more than 128 entries
-    extern __shared__ double pacc[];
-    const int sub = threadIdx.x & (L - 1);
-    const int grp = threadIdx.x / L;
-    const int x = blockIdx.x % FM_XCDS;
-    const int nwg = gridDim.x / FM_XCDS;  // workgroups per XCD
-    const int64_t g = (int64_t)(blockIdx.x / FM_XCDS) * NG + grp;  // < p_ngroups: the grid is p_ngroups / NG per XCD
-    constexpr int rl = RL;  // = K / VEC: the lane that reads the multiplier
-    const int PW = A.K + 4;  // doubles per slot: K latent sums, then gw, s2 and two unused
-    double* __restrict__ lacc = pacc + (size_t)grp * A.p_smax * PW;
-    for (int t = sub; t < A.p_smax * PW; t += L) lacc[t] = 0.0;
-    const float scalar_lane = sub == rl ? 1.f : 0.f;
-    const int64_t* __restrict__ gp = A.p_gptr + ((int64_t)x * A.p_ngroups + g) * (A.p_npx + 1);
-    int* __restrict__ done = A.p_done + (int64_t)x * A.p_npx;
-    const int last = (int)A.gs - VEC;
-    const int kb = sub * VEC < last ? sub * VEC : last;  // lanes past the scalars re-read the row's last floats
-    const float* __restrict__ src = A.G + kb;
-    float acc[VEC] = {0.f, 0.f, 0.f, 0.f};
-    float gw = 0.f, s2 = 0.f;
-    int cur = 0;
-    auto flush = [&]() {
-        double* d = lacc + cur * PW + sub * VEC;
-        if (sub < rl) {
-#pragma unroll
-            for (int z = 0; z < VEC; ++z) d[z] += (double)acc[z];
-        } else if (sub == rl) {
-            d[0] += (double)gw;
-            d[1] += (double)s2;
-        }
-#pragma unroll
-        for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
-        gw = s2 = 0.f;
-    };
-    int64_t beg = gp[0];
-    int spin_left = A.p_spin;  // polls this workgroup may spend waiting, over the whole launch (thread 0)
-    for (int64_t pi = 0; pi < A.p_npx; ++pi) {
-        const int64_t end = gp[pi + 1];
-        auto load_records = [&](int64_t e, uint2 (&rc)[U]) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t my = e + u * L + sub;
-                const bool has = my < end;
-                rc[u] = A.p_rec[has ? my : end - 1];
-                if (!has) rc[u].y = 0u;  // value 0: adds nothing to the slot of the last record
-            }
-        };
-        uint2 rc[U], nx[U];
-        if (beg < end) load_records(beg, rc);
-        int since = 0;
-        for (int64_t e = beg; e < end; e += S) {
-            float gv[S][VEC];
-            float xt[S];
-            int sl[S];
-            fm_static_for<0, S>([&](auto sc) {
-                constexpr int s = decltype(sc)::value;
-                constexpr int u = s / L, T = s % L;
-                const uint32_t tag = (uint32_t)fm_bcast_i<L, T>((int)rc[u].x);
-                xt[s] = fm_bcast_f<L, T>(__uint_as_float(rc[u].y));
-                sl[s] = (int)(tag >> 28);
-                fm_load_vec<VEC>(src + (int64_t)(tag & 0x0fffffffu) * A.gs, gv[s]);
-            });
-            // the next chunk's records travel while this chunk's rows arrive
-            if (e + S < end) load_records(e + S, nx);
-#pragma unroll
-            for (int s = 0; s < S; ++s) {
-                if (sl[s] != cur) {  // uniform inside a group
-                    flush();
-                    cur = sl[s];
-                }
-                const float r = fm_bcast_f<L, RL>(gv[s][0]);
-                const float mm = xt[s] * r;
-#pragma unroll
-                for (int z = 0; z < VEC; ++z) acc[z] += mm * gv[s][z];
-                const float ms = scalar_lane * mm;  // only the scalar lane keeps gw, s2
-                gw += ms;
-                s2 += xt[s] * ms;
-            }
-            if (++since == FLUSH_EVERY) {
-                flush();
-                since = 0;
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) rc[u] = nx[u];
-        }
-        flush();
-        beg = end;
-        // Pacing, not correctness: no workgroup of this XCD starts panel pi + p_lag before all of them
-        // have finished panel pi, so that the rows of the panels in flight stay in the XCD's L2.  The
-        // wait is bounded: if some workgroup is not resident the others go on after p_spin polls.
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            __hip_atomic_fetch_add(&done[pi], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int64_t need = pi + 1 - A.p_lag;
-            if (need >= 0 && pi + 1 < A.p_npx && spin_left > 0) {
-                while (__hip_atomic_load(&done[need], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nwg) {
-                    if (--spin_left == 0) break;  // some workgroup is not running: no more waiting in this launch
-                    __builtin_amdgcn_s_sleep(8);
-                }
-            }
-        }
-        __syncthreads();
-    }
-    const int32_t* __restrict__ items = A.p_gitem + ((int64_t)x * A.p_ngroups + g) * A.p_smax;
-    for (int t = 0; t < A.p_smax; ++t) {
-        const int32_t it = items[t];
-        if (it < 0) continue;
-        float* __restrict__ row = A.part + (int64_t)it * A.ps;
-        const double* __restrict__ d = lacc + t * PW;
-        for (int o = sub * VEC; o < A.ps; o += L * VEC) {  // the whole 128-byte row, padding included
-            float z[VEC];
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) z[c] = (o + c < A.K + 2) ? (float)d[o + c] : 0.f;
-            fm_store_vec<VEC>(row + o, z);
-        }
-    }
-}
-
 // Sum of the partials first, first+step, ... < last of one column, in fp64 and in that
 // order; eight loads are issued before the first add so that the loop is not one memory
 // round trip per item.
@@ -845,10 +712,9 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     // The three accumulation kernels touch disjoint columns.  When there are LDS-staged items,
     // k_cols and k_cols_tile go to two side streams so that the LDS-bound kernel overlaps the
     // memory-bound ones; the finish kernels wait for all three.
-    const int64_t ntile_items = A.order != nullptr ? A.nitems - A.list_off[FM_XCDS] - A.p_nitems : 0;
+    const int64_t ntile_items = A.order != nullptr ? A.nitems - A.list_off[FM_XCDS] : 0;
     // (not while per-kernel timing is on: each kernel is then timed alone on the launch stream)
-    const bool with_panel = A.p_rec != nullptr && A.p_nitems > 0;
-    const bool side = (ntile_items > 0 || with_panel || (A.nitems > 0 && A.nshort > 0)) && !m->prof && fm_side_streams(m);
+    const bool side = (ntile_items > 0 || (A.nitems > 0 && A.nshort > 0)) && !m->prof && fm_side_streams(m);
     hipStream_t s_cols = st, s_tile = st;
     if (side) {
         FM_HIP(m, hipEventRecord(m->ev_fork, st));
@@ -856,43 +722,6 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
         FM_HIP(m, hipStreamWaitEvent(m->side2, m->ev_fork, 0));
         s_tile = m->side1;
         s_cols = m->side2;
-    }
-    if (with_panel) {  // first, so that all its workgroups start together
-        if constexpr (PACKED != FM_PACKED_LANE || VEC != 4) {
-            return fm_fail(m, FM_ESTATE, "panel items need packed aggregate rows");
-        } else {
-            FM_TRY(fm_fill_i32(m, A.p_done, (int64_t)FM_XCDS * A.p_npx, 0, s_tile));
-            ProfScope ps(m, s_tile, FMK_COLS_PANEL);
-            const int64_t wgs = A.p_ngroups / (FM_BLOCK / 8);  // p_ngroups is a multiple of the groups per workgroup
-            const size_t lds = (size_t)(FM_BLOCK / 8) * A.p_smax * (A.K + 4) * sizeof(double);
-            void (*kern)(const ColArgs) = nullptr;
-            switch (A.K / 4) {
-                case 1: kern = k_cols_panel<1>; break;
-                case 2: kern = k_cols_panel<2>; break;
-                case 3: kern = k_cols_panel<3>; break;
-                case 4: kern = k_cols_panel<4>; break;
-                case 5: kern = k_cols_panel<5>; break;
-                case 6: kern = k_cols_panel<6>; break;
-                case 7: kern = k_cols_panel<7>; break;
-                default: return fm_fail(m, FM_ESTATE, "panel items need K <= 28");
-            }
-            if (lds > 48 * 1024)  // opt in to more than the default amount of dynamic LDS
-                FM_HIP(m, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            // the pacing only makes sense (and only costs nothing) when every workgroup is resident at once
-            ColArgs B = A;
-            int per_cu = 0, dev = 0;
-            hipDeviceProp_t prop;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, FM_BLOCK, lds) != hipSuccess ||
-                hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess ||
-                wgs * FM_XCDS > (int64_t)per_cu * prop.multiProcessorCount) {
-                (void)hipGetLastError();
-                B.p_spin = 0;
-            }
-            if (getenv("FM_DEBUG")) fprintf(stderr, "[panel] wgs/xcd %lld lds %zu per_cu %d spin %d npx %lld ngroups %d items %lld\n", (long long)wgs, lds, per_cu, B.p_spin, (long long)A.p_npx, A.p_ngroups, (long long)A.p_nitems);
-            hipLaunchKernelGGL(kern, dim3((unsigned)(wgs * FM_XCDS)), dim3(FM_BLOCK), lds, s_tile, B);
-            FM_HIP(m, hipGetLastError());
-        }
     }
     if (ntile_items > 0) {  // items of dense-ish columns, sorted by row tile
         ProfScope ps(m, s_tile, FMK_COLS_TILE);

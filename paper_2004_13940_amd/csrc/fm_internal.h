@@ -30,11 +30,6 @@ struct FmTune {
     int tile_min;         // a column is dense-ish if it averages this many entries per tile (0: none)
     int tile_seg;         // entries per item inside a tile
     int seg_strat;        // `seg` of the per-stratum matrices (FM_SEG_STRAT; fm_set_tuning sets both); 0: automatic
-    int ppanel;           // rows per panel of the walk with accumulators in LDS (k_cols_panel); 0: path off
-    int ppanel_min;       // a column takes that path if it averages at least this many entries per such panel
-    int ppanel_unit;      // entries per panel above which a column is split into sub-columns
-    int ppanel_wgs;       // workgroups per XCD of that kernel
-    int ppanel_lag;       // panels a workgroup of that kernel may run ahead of the slowest one of its XCD
 };
 const FmTune& fm_tune();
 
@@ -61,29 +56,10 @@ enum fm_kernel_id {
     FMK_COLS,
     FMK_COLS_LONG,
     FMK_COLS_TILE,
-    FMK_COLS_PANEL,
     FMK_COLS_FINISH,
     FMK_REDUCE,
     FMK_BIAS,
     FMK_COUNT
-};
-
-// Heavy columns walked panel by panel with their accumulators in LDS (k_cols_panel).  Panel b (rows
-// [b*rows, (b+1)*rows)) belongs to XCD b % FM_XCDS.  A column is cut into `S` sub-columns (sub-ranges of
-// the rows of every panel) so that one sub-column has about `unit` entries per panel; a sub-column on an
-// XCD is one accumulator slot of one lane group of that XCD, and one partial row at the end.  The
-// entries are copied into the order the groups read them: group by group, panel by panel, slot by slot.
-struct PanelIndex {
-    int64_t rows = 0;          // rows per panel (at most 65536)
-    int64_t npx = 0;           // panels per XCD
-    int32_t ngroups = 0;       // lane groups per XCD
-    int32_t smax = 0;          // accumulator slots per group
-    int64_t nentries = 0;
-    uint2* rec = nullptr;      // [nentries] (row - first row of the panel) | slot << 16, bits of the value
-    int64_t* gptr = nullptr;   // [FM_XCDS * ngroups * (npx + 1)] offsets into rec: start of every panel of a group
-    int32_t* gitem = nullptr;  // [FM_XCDS * ngroups * smax] item id of every slot's partial row, -1: unused slot
-    int32_t* done = nullptr;   // [FM_XCDS * npx] pacing counters of the kernel
-    int64_t nitems = 0;        // partial rows this path writes: the last ids of the item numbering
 };
 
 // Work items for columns longer than `seg` entries (of one matrix, or of all strata
@@ -113,7 +89,6 @@ struct LongIndex {
     int64_t* tile_ptr = nullptr;    // [ntiles+1] positions in `order`
     int32_t* vlong = nullptr;       // [nvlong] indices into long_col of columns with > vlong items
     int64_t nvlong = 0;
-    PanelIndex panel;               // full matrix only
 };
 
 struct ProfRec {
@@ -133,8 +108,7 @@ struct fm_matrix {
     int32_t* crow = nullptr;
     float* cval = nullptr;
     LongIndex lfull;
-    int lfull_shape[4] = {0, 0, 0, 0};  // tile rows, entries per tile that make a column dense-ish, item length in a tile,
-                                        // rows per panel of the LDS-accumulator walk (0: off)
+    int lfull_shape[3] = {0, 0, 0};  // tile rows, entries per tile that make a column dense-ish, item length in a tile
     // double partition and per-stratum matrices
     int32_t P = 0;
     std::vector<int64_t> h_rb, h_cb, h_cell_nnz, h_strat_nnz_off;  // bounds, P*P table, P+1 offsets
@@ -235,7 +209,6 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
 // lfull, with the panel order of heavy columns and the LDS tiles shaped for latent size K (0: unknown)
 int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st);
 void fm_tile_shape(int64_t N, int32_t K, int* tile_rows, int* tile_min, int* tile_seg);
-int fm_panel_rows(int64_t N, int32_t K);  // rows per panel of k_cols_panel for this shape, 0: path not used
 int fm_ensure_lazy(fm_matrix* m);  // allocates lazy_last on first use
 
 // ---- pass kernels (fm_rows.hip / fm_cols.hip / fm_reduce.hip) ----
@@ -321,14 +294,6 @@ struct ColArgs {
     int32_t vlong_items;           // threshold that defines vlong
     float* part;                    // rows [acc | gw | s2 | pad] of ps floats, indexed by absolute item id
     int64_t ps;
-    // k_cols_panel (see PanelIndex); p_rec == nullptr: no such items
-    const uint2* p_rec;
-    const int64_t* p_gptr;
-    const int32_t* p_gitem;
-    int64_t p_rows, p_npx, p_nitems;
-    int32_t p_ngroups, p_smax, p_wgs;
-    int32_t* p_done;      // [FM_XCDS * p_npx] workgroups of XCD x that have finished panel pi (zero at launch)
-    int32_t p_lag, p_spin;  // pacing: panels a workgroup may run ahead of the slowest one, and the bound of the wait
 };
 int fm_launch_cols(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st);
 // takes the postponed regulariser steps of every column up to stratum A.s (exclusive)

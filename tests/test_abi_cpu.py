@@ -73,7 +73,7 @@ def test_null_and_oversized_arguments(lib):
                           ctypes.c_void_p(None), ctypes.byref(h))
     assert rc == -4
     assert lib.fm_destroy(ctypes.c_void_p(None)) == 0
-    assert lib.fm_profile_kernels() == 9
+    assert lib.fm_profile_kernels() == 8
 
 
 def test_binding_refuses_to_run_without_a_gpu():
