@@ -156,7 +156,8 @@ def main():
     # size of the aggregates, measured here; beside it the lines per second the dominant kernel moves
     # according to the committed counter summary
     try:
-        line_peak = B.fm_probe_gather(max(1 << 20, min(wl.N * 128, 8 << 30)), 128)
+        from paper_2004_13940_amd import bench_probe
+        line_peak = bench_probe.gather_rate(max(1 << 20, min(wl.N * 128, 8 << 30)), 128)
     except Exception as e:  # a failed calibration must not lose the measurement
         print(f"[bench] gather calibration failed: {e}", file=sys.stderr, flush=True)
         line_peak = None

@@ -221,8 +221,23 @@ int fm_profile_kernels(void);
 const char* fm_profile_kernel_name(int32_t k);
 int fm_profile_read(fm_matrix* m, int64_t* launches /*HOST nk*/, double* total_ms /*HOST nk*/);
 
-/* Work-decomposition knobs of the column side, for callers that tune or test them; they
- * apply to matrices whose CSC is built afterwards.  A value <= 0 keeps the current one.
+/* Switches between code paths that compute the same thing, per handle; tests run every one of them
+ * against the oracle.  Results do not depend on them beyond fp32 rounding.
+ *   FM_OPT_AUX_PLANAR    1: the handle keeps the aggregates planar (G [N x K], then r, a, q) for every
+ *                        K; 0 (default): as packed rows [G | r | a | q | pad] when [G | r] fits one
+ *                        128-byte line (K % 4 == 0, K <= 28).  Changing it drops the aggregates held.
+ *   FM_OPT_SIDE_STREAMS  1 (default): column kernels that touch disjoint columns overlap on two
+ *                        internal streams; 0: everything on the caller's stream.
+ *   FM_OPT_LAZY_REG      1 (default): fm_stratified_epoch and fm_minibatch_epoch postpone the
+ *                        regulariser-only steps of columns without entries in a cell or batch; 0: every
+ *                        column takes its step in every stratum or batch.
+ *   FM_OPT_GRAPH         fm_stratified_epoch replayed from a captured HIP graph: 0 never, 1 (default)
+ *                        when the strata are small enough for the launches to dominate, 2 always. */
+typedef enum { FM_OPT_AUX_PLANAR = 0, FM_OPT_SIDE_STREAMS = 1, FM_OPT_LAZY_REG = 2, FM_OPT_GRAPH = 3 } fm_option;
+int fm_set_option(fm_matrix* m, int32_t option /*fm_option*/, int32_t value);
+
+/* Work-decomposition knobs of the column side, per handle, for callers that tune or test them; they
+ * must be set before fm_build_csc (FM_ESTATE afterwards).  A value <= 0 keeps the current one.
  *   seg              entries per work item of a long column                      (default 256; the
  *                    per-stratum and per-batch matrices use 256 or 128, chosen per matrix, unless set here)
  *   panel            rows per panel of the L2-blocked traversal of heavy columns (default 32768)
@@ -230,7 +245,8 @@ int fm_profile_read(fm_matrix* m, int64_t* launches /*HOST nk*/, double* total_m
  *   vlong            columns with more items are summed by a whole workgroup      (default 512)
  *   min_panels       matrices with fewer panels use plain segments only           (default 64)
  * Results do not depend on these values beyond fp32 rounding. */
-int fm_set_tuning(int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t vlong, int32_t min_panels);
+int fm_set_tuning(fm_matrix* m, int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t vlong,
+                  int32_t min_panels);
 /*   tile_rows     rows of aggregates staged in LDS by the kernel for dense-ish columns
  *   min_per_tile  a column is dense-ish if it averages this many entries per tile; 0 = none
  *   tile_seg      entries per work item inside a tile
@@ -239,13 +255,7 @@ int fm_set_tuning(int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t v
  * 4, K <= 16); 128 / 2 / 128 and 256 / 4 / 256 for matrices of fewer than 2^17 and 2^18 rows; else
  * 512 / 8 / 256.
  * min_per_tile < 0 keeps the current value. */
-int fm_set_tile_tuning(int32_t tile_rows, int32_t min_per_tile, int32_t tile_seg);
-
-/* Calibration for benchmarks, not part of the method: rows of row_bytes (64 or 128) read per second
- * from pseudo-random places of a zeroed device buffer of buffer_bytes (1 MiB .. 64 GiB) that the call
- * allocates and frees.  This is the traffic the pass kernels are bound by (gathers of V rows and of
- * aggregate rows).  rows_per_s is HOST 1; the call waits for the stream. */
-int fm_probe_gather(int64_t buffer_bytes, int32_t row_bytes, double* rows_per_s, void* hip_stream);
+int fm_set_tile_tuning(fm_matrix* m, int32_t tile_rows, int32_t min_per_tile, int32_t tile_seg);
 
 int fm_destroy(fm_matrix* m);
 const char* fm_last_error(const fm_matrix* m); /* m may be NULL: last build error of this thread */

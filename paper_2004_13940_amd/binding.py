@@ -38,7 +38,9 @@ EXPORTS = ["fm_build_csr", "fm_build_csc", "fm_partition", "fm_get_csc", "fm_get
            "fm_get_batch_csc", "fm_forward", "fm_forward_noalloc", "fm_evaluate", "fm_gradient",
            "fm_sgd_epoch", "fm_minibatch_epoch", "fm_stratified_epoch", "fm_stratified_begin", "fm_stratified_step",
            "fm_stratified_end", "fm_get_aux", "fm_profile_enable", "fm_profile_kernels",
-           "fm_profile_kernel_name", "fm_profile_read", "fm_set_tuning", "fm_set_tile_tuning", "fm_probe_gather", "fm_destroy", "fm_last_error"]
+           "fm_profile_kernel_name", "fm_profile_read", "fm_set_option", "fm_set_tuning", "fm_set_tile_tuning", "fm_destroy",
+           "fm_last_error"]
+FM_OPT_AUX_PLANAR, FM_OPT_SIDE_STREAMS, FM_OPT_LAZY_REG, FM_OPT_GRAPH = 0, 1, 2, 3
 
 _lib = None
 
@@ -95,24 +97,6 @@ def make_params(K, loss, lambda_w, lambda_v, eta, loss_scale=1.0, update_w0=1, r
                      int(update_w0), int(reg_full_per_cell), int(refresh_all_rows), int(stale_aux))
 
 
-def fm_probe_gather(buffer_bytes, row_bytes=128, stream=None):
-    """Rows of ``row_bytes`` read per second from random places of a buffer of ``buffer_bytes``."""
-    out = ctypes.c_double(0.0)
-    rc = load().fm_probe_gather(ctypes.c_int64(int(buffer_bytes)), ctypes.c_int32(int(row_bytes)), ctypes.byref(out),
-                                _stream(stream))
-    if rc != FM_OK:
-        raise FMError(rc, "fm_probe_gather failed")
-    return out.value
-
-
-def fm_set_tuning(seg=0, panel=0, heavy_per_panel=0, vlong=0, min_panels=0):
-    load().fm_set_tuning(*(ctypes.c_int32(int(v)) for v in (seg, panel, heavy_per_panel, vlong, min_panels)))
-
-
-def fm_set_tile_tuning(tile_rows=0, min_per_tile=-1, tile_seg=0):
-    load().fm_set_tile_tuning(*(ctypes.c_int32(int(v)) for v in (tile_rows, min_per_tile, tile_seg)))
-
-
 class Matrix:
     """Owner of an ``fm_matrix`` handle; methods mirror the C entry points."""
 
@@ -151,6 +135,18 @@ class Matrix:
             self.close()
         except Exception:
             pass
+
+    # -- settings
+    def fm_set_option(self, option, value):
+        self._check(load().fm_set_option(self._h, ctypes.c_int32(int(option)), ctypes.c_int32(int(value))))
+
+    def fm_set_tuning(self, seg=0, panel=0, heavy_per_panel=0, vlong=0, min_panels=0):
+        self._check(load().fm_set_tuning(self._h, *(ctypes.c_int32(int(v)) for v in (seg, panel, heavy_per_panel, vlong,
+                                                                                     min_panels))))
+
+    def fm_set_tile_tuning(self, tile_rows=0, min_per_tile=-1, tile_seg=0):
+        self._check(load().fm_set_tile_tuning(self._h, *(ctypes.c_int32(int(v)) for v in (tile_rows, min_per_tile,
+                                                                                          tile_seg))))
 
     # -- structures
     def fm_build_csc(self, stream=None):

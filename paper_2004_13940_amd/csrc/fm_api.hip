@@ -272,30 +272,23 @@ static int check_params(fm_matrix* m, const fm_params* p)
 
 // Packed rows are used when [G | r] of a row fits one 128-byte line (a whole number of float4,
 // K <= 28): a column-side gather is then a single request.  For larger K a row of G is one or
-// more whole lines by itself and the planar layout gathers fewer of them.  FM_AUX_PACKED=0
+// more whole lines by itself and the planar layout gathers fewer of them.  The option aux_planar
 // selects the planar layout always.
-bool fm_aux_packed(int32_t K)
-{
-    static const bool allow = [] {
-        const char* e = getenv("FM_AUX_PACKED");
-        return !(e != nullptr && *e == '0');
-    }();
-    return allow && K % 4 == 0 && K + 1 <= 32;
-}
+bool fm_aux_packed(const fm_matrix* m, int32_t K) { return !m->opt.aux_planar && K % 4 == 0 && K + 1 <= 32; }
 
 static int64_t packed_stride(int32_t K) { return ((int64_t)K + 3 + 15) / 16 * 16; }
 
-int fm_cols_packed_mode(int32_t K)
-{
-    return fm_aux_packed(K) ? FM_PACKED_LANE : FM_PLANAR;
-}
+int fm_cols_packed_mode(const fm_matrix* m, int32_t K) { return fm_aux_packed(m, K) ? FM_PACKED_LANE : FM_PLANAR; }
 
-int64_t fm_aux_floats(int64_t N, int32_t K) { return fm_aux_packed(K) ? N * packed_stride(K) : N * ((int64_t)K + 3); }
+int64_t fm_aux_floats(const fm_matrix* m, int32_t K)
+{
+    return fm_aux_packed(m, K) ? m->N * packed_stride(K) : m->N * ((int64_t)K + 3);
+}
 
 FmAux fm_aux_layout(const fm_matrix* m, int32_t K)
 {
     FmAux x;
-    if (fm_aux_packed(K)) {
+    if (fm_aux_packed(m, K)) {
         x.gs = x.ss = packed_stride(K);
         x.G = m->aux;
         x.r = m->aux + K;
@@ -314,11 +307,10 @@ FmAux fm_aux_layout(const fm_matrix* m, int32_t K)
 
 bool fm_side_streams(fm_matrix* m)
 {
+    if (!m->opt.side_streams) return false;
     if (m->side_state == 0) {
-        const char* e = getenv("FM_SIDE_STREAMS");
         m->side_state = -1;
-        if (!(e != nullptr && *e == '0') &&
-            hipStreamCreateWithFlags(&m->side1, hipStreamNonBlocking) == hipSuccess &&
+        if (hipStreamCreateWithFlags(&m->side1, hipStreamNonBlocking) == hipSuccess &&
             hipStreamCreateWithFlags(&m->side2, hipStreamNonBlocking) == hipSuccess &&
             hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) == hipSuccess &&
             hipEventCreateWithFlags(&m->ev_join1, hipEventDisableTiming) == hipSuccess &&
@@ -357,7 +349,7 @@ static int ensure_ws(fm_matrix* m, int32_t K)
     fm_drop_workspace(m);
     if (m->has_csc) {  // the LDS tiles of the dense-ish columns are shaped for K
         int shape[3];
-        fm_tile_shape(m->N, K, &shape[0], &shape[1], &shape[2]);
+        fm_tile_shape(m, K, &shape[0], &shape[1], &shape[2]);
         if (memcmp(shape, m->lfull_shape, sizeof(shape)) != 0) {
             FM_HIP(m, hipDeviceSynchronize());
             FM_TRY(fm_build_full_index(m, K, nullptr));
@@ -365,7 +357,7 @@ static int ensure_ws(fm_matrix* m, int32_t K)
         }
     }
     const size_t D = (size_t)m->D;
-    FM_TRY(fm_dev_alloc(m, (void**)&m->aux, (size_t)std::max<int64_t>(fm_aux_floats(m->N, K), 1) * sizeof(float)));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->aux, (size_t)std::max<int64_t>(fm_aux_floats(m, K), 1) * sizeof(float)));
     const int64_t items = std::max<int64_t>(std::max<int64_t>(m->lfull.nitems, m->lstrat.nitems), m->lbatch.nitems);
     FM_TRY(fm_dev_alloc(m, (void**)&m->part,
                         (size_t)std::max<int64_t>(items, 1) * (size_t)fm_part_stride(K) * sizeof(float)));
@@ -383,7 +375,7 @@ static int ensure_strat_ws(fm_matrix* m, int32_t K)
     return ensure_ws(m, K);  // fm_partition dropped any older workspace, so dV/dwn are there
 }
 
-static void fill_long(ColArgs& A, const LongIndex& li, int32_t s, bool strat)
+static void fill_long(const fm_matrix* m, ColArgs& A, const LongIndex& li, int32_t s, bool strat)
 {
     const int64_t l0 = strat ? li.h_long_off[s] : 0, l1 = strat ? li.h_long_off[s + 1] : li.nlong;
     const int64_t i0 = strat ? li.h_item_off[s] : 0, i1 = strat ? li.h_item_off[s + 1] : li.nitems;
@@ -407,27 +399,17 @@ static void fill_long(ColArgs& A, const LongIndex& li, int32_t s, bool strat)
     A.lin_mode = 0;
     A.vlong = strat ? nullptr : li.vlong;
     A.nvlong = strat ? 0 : li.nvlong;
-    A.vlong_items = fm_tune().vlong;
+    A.vlong_items = m->tune.vlong;
     const int64_t s0 = strat ? li.h_short_off[s] : 0, s1 = strat ? li.h_short_off[s + 1] : li.nshort;
     A.short_col = li.short_col != nullptr ? li.short_col + s0 : nullptr;
     A.nshort = s1 - s0;
-}
-
-// FM_WHOLE_ROWS=0: the forward writes only the fields of a packed row that the epoch reads
-static bool fm_whole_rows()
-{
-    static const bool on = [] {
-        const char* e = getenv("FM_WHOLE_ROWS");
-        return !(e != nullptr && e[0] == '0');
-    }();
-    return on;
 }
 
 // RowArgs outputs pointing into the handle's aggregate rows [G | r | a | q | pad]
 static void aux_outputs(fm_matrix* m, int32_t K, RowArgs& A, bool with_aq)
 {
     const FmAux x = fm_aux_layout(m, K);
-    A.whole_rows = (fm_aux_packed(K) && A.y != nullptr && fm_whole_rows()) ? 1 : 0;
+    A.whole_rows = (fm_aux_packed(m, K) && A.y != nullptr) ? 1 : 0;  // never leave a line partly written
     A.G = x.G;
     A.gs = x.gs;
     A.ss = x.ss;
@@ -576,7 +558,7 @@ extern "C" int fm_gradient(fm_matrix* m, const fm_params* p, const float* r, con
     A.ptr = m->colptr;
     A.row = m->crow;
     A.val = m->cval;
-    if (fm_aux_packed(p->K)) {
+    if (fm_aux_packed(m, p->K)) {
         // one streaming pass puts r and G into packed aggregate rows, so that every gather of the
         // column pass is one request (and dense-ish columns can be staged through LDS)
         FM_TRY(fm_pack_aux(m, r, G, st));
@@ -587,7 +569,7 @@ extern "C" int fm_gradient(fm_matrix* m, const fm_params* p, const float* r, con
         A.G = x.G;
         A.gs = x.gs;
         A.rs = x.ss;
-        A.packed = fm_cols_packed_mode(p->K);
+        A.packed = fm_cols_packed_mode(m, p->K);
     } else {
         A.r = r;
         A.G = G;
@@ -598,7 +580,7 @@ extern "C" int fm_gradient(fm_matrix* m, const fm_params* p, const float* r, con
     A.V = const_cast<float*>(V);
     A.grad_w = grad_w;
     A.grad_V = grad_V;
-    fill_long(A, m->lfull, 0, false);
+    fill_long(m, A, m->lfull, 0, false);
     return fm_launch_cols(m, A, false, st);
 }
 
@@ -636,10 +618,10 @@ extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, fl
     A.G = x.G;
     A.gs = x.gs;
     A.rs = x.ss;
-    A.packed = fm_cols_packed_mode(p->K);
+    A.packed = fm_cols_packed_mode(m, p->K);
     A.w = w;
     A.V = V;
-    fill_long(A, m->lfull, 0, false);
+    fill_long(m, A, m->lfull, 0, false);
     FM_TRY(fm_launch_cols(m, A, true, st));
     if (p->update_w0) FM_TRY(fm_bias_step(m, w0, m->scal + 1, p->eta, nullptr, st));
     if (objective != nullptr) {
@@ -652,16 +634,6 @@ extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, fl
 }
 
 // ------------------------------------------------------- stratified epoch ----
-
-// FM_LAZY_REG=0 makes fm_stratified_epoch take every column's step in every stratum.
-static bool fm_lazy_enabled()
-{
-    static const bool on = [] {
-        const char* e = getenv("FM_LAZY_REG");
-        return !(e != nullptr && e[0] == '0');
-    }();
-    return on;
-}
 
 extern "C" int fm_stratified_begin(fm_matrix* m, const fm_params* p, const float* y, const float* w0,
                                    const float* w, const float* V, void* hip_stream)
@@ -716,12 +688,12 @@ static int stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const fl
     A.G = x.G;
     A.gs = x.gs;
     A.rs = x.ss;
-    A.packed = fm_cols_packed_mode(p->K);
+    A.packed = fm_cols_packed_mode(m, p->K);
     if (!p->stale_aux) {  // the changes are only recorded for the refresh
         A.dV = m->dV;
         A.dwn = m->dwn;
     }
-    fill_long(A, m->lstrat, s, true);
+    fill_long(m, A, m->lstrat, s, true);
     FM_TRY(fm_launch_cols(m, A, true, st));
     if (p->stale_aux) return FM_OK;  // Algorithm 1: the aggregates wait for the re-computation
     // phase B: incremental refresh of the aggregates and multipliers
@@ -803,18 +775,6 @@ static int enqueue_stratified_epoch(fm_matrix* m, const fm_params* p, const floa
     return FM_OK;
 }
 
-// FM_GRAPH=0: never replay the stratified epoch from a captured graph.  By default a graph is used
-// for matrices whose strata are small enough for the launches to dominate.
-static int fm_graph_mode()
-{
-    static const int mode = [] {
-        const char* e = getenv("FM_GRAPH");
-        if (e == nullptr || *e == 0) return 1;            // automatic
-        return e[0] == '0' ? 0 : (e[0] == '2' ? 2 : 1);   // 0 off, 2 always
-    }();
-    return mode;
-}
-
 static bool graph_ready(fm_matrix* m)
 {
     if (m->graph_state == 0) {
@@ -885,9 +845,9 @@ extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float
     // The refresh of a stratum reads the change of a column only where the column has entries in
     // its cell, so the regulariser-only steps of the other columns can wait (not when every row
     // is refreshed from every column's change).
-    const bool lazy = (!p->refresh_all_rows || p->stale_aux) && m->lazy_last != nullptr && fm_lazy_enabled();
+    const bool lazy = (!p->refresh_all_rows || p->stale_aux) && m->lazy_last != nullptr && m->opt.lazy_reg;
     // small strata are bound by their launches: replay them from a graph
-    const int gmode = fm_graph_mode();
+    const int gmode = m->opt.graph;  // 0 never, 1 for matrices whose strata are small enough for the launches to dominate, 2 always
     // (worth it from some tens of launches on: below that the two events and the graph launch cost more)
     const bool small = m->nnz / m->P < (int64_t(1) << 20) && m->P >= 16;
     bool done = false;
@@ -930,7 +890,7 @@ extern "C" int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float*
     const FmAux x = fm_aux_layout(m, p->K);
     // a column without entries in a batch only takes the regulariser's step there: postponed
     // until the column next has entries, or the epoch ends
-    const bool lazy = fm_lazy_enabled();
+    const bool lazy = m->opt.lazy_reg;
     if (lazy) FM_TRY(fm_fill_i32(m, m->lazy_last, m->D, 0, st));
     auto col_args = [&](int32_t b, ColArgs& A) {
         base_col_args(m, p, A);
@@ -960,7 +920,7 @@ extern "C" int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float*
             R.gs = x.gs;
             R.ss = x.ss;
             R.r = x.r + r0 * x.ss;
-            R.whole_rows = (fm_aux_packed(p->K) && fm_whole_rows()) ? 1 : 0;
+            R.whole_rows = fm_aux_packed(m, p->K) ? 1 : 0;
             R.row_part = p->update_w0 ? m->row_part : nullptr;
             R.loss = p->loss;
             R.s = p->loss_scale;
@@ -978,8 +938,8 @@ extern "C" int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float*
         A.G = x.G;
         A.gs = x.gs;
         A.rs = x.ss;
-        A.packed = fm_cols_packed_mode(p->K);
-        fill_long(A, m->lbatch, b, true);
+        A.packed = fm_cols_packed_mode(m, p->K);
+        fill_long(m, A, m->lbatch, b, true);
         FM_TRY(fm_launch_cols(m, A, true, st));
         if (p->update_w0 && nb > 0) FM_TRY(fm_bias_step(m, w0, m->scal + 1, p->eta, nullptr, st));
     }
@@ -1009,5 +969,59 @@ extern "C" int fm_get_aux(const fm_matrix* m, float* a, float* G, float* q, floa
         return fm_fail(mm, FM_ESTATE, "a and q are only held after a stratified call");
     hipStream_t st = (hipStream_t)hip_stream;
     FM_TRY(fm_unpack_aux(mm, a, G, q, r, st));
+    return FM_OK;
+}
+
+
+// ------------------------------------------------------------- settings ----
+
+extern "C" int fm_set_option(fm_matrix* m, int32_t option, int32_t value)
+{
+    if (m == nullptr) return FM_EINVAL;
+    switch (option) {
+        case FM_OPT_AUX_PLANAR:
+            if (m->opt.aux_planar != (value != 0)) {
+                FM_HIP(m, hipDeviceSynchronize());
+                fm_drop_workspace(m);  // the aggregates change layout
+                m->opt.aux_planar = value != 0;
+            }
+            return FM_OK;
+        case FM_OPT_SIDE_STREAMS:
+            m->opt.side_streams = value != 0;
+            fm_drop_graph(m);
+            return FM_OK;
+        case FM_OPT_LAZY_REG:
+            m->opt.lazy_reg = value != 0;
+            return FM_OK;
+        case FM_OPT_GRAPH:
+            if (value < 0 || value > 2) return fm_fail(m, FM_EINVAL, "graph mode %d outside 0..2", value);
+            m->opt.graph = value;
+            return FM_OK;
+    }
+    return fm_fail(m, FM_EINVAL, "unknown option %d", option);
+}
+
+extern "C" int fm_set_tuning(fm_matrix* m, int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t vlong,
+                             int32_t min_panels)
+{
+    if (m == nullptr) return FM_EINVAL;
+    if (m->has_csc) return fm_fail(m, FM_ESTATE, "fm_set_tuning must come before fm_build_csc");
+    FmTune& t = m->tune;
+    if (seg > 0) t.seg = t.seg_strat = seg < 16 ? 16 : seg;
+    if (panel > 0) t.panel = panel < 64 ? 64 : panel;
+    if (heavy_per_panel > 0) t.heavy_per_panel = heavy_per_panel;
+    if (vlong > 0) t.vlong = vlong;
+    if (min_panels > 0) t.min_panels = min_panels;
+    return FM_OK;
+}
+
+extern "C" int fm_set_tile_tuning(fm_matrix* m, int32_t tile_rows, int32_t min_per_tile, int32_t tile_seg)
+{
+    if (m == nullptr) return FM_EINVAL;
+    if (m->has_csc) return fm_fail(m, FM_ESTATE, "fm_set_tile_tuning must come before fm_build_csc");
+    FmTune& t = m->tune;
+    if (tile_rows > 0) t.tile = tile_rows < 64 ? 64 : tile_rows;
+    if (min_per_tile >= 0) t.tile_min = min_per_tile;
+    if (tile_seg > 0) t.tile_seg = tile_seg < 16 ? 16 : tile_seg;
     return FM_OK;
 }

@@ -2,8 +2,6 @@
 // the per-stratum matrices of the double partition, and the work-item lists for long
 // columns.  Everything here is deterministic (integer atomics are only used for
 // counts, whose totals do not depend on the order of the additions).
-#include <stdlib.h>
-
 #include "fm_device.h"
 #include "fm_internal.h"
 
@@ -632,9 +630,9 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
     // Item length.  The launches of one stratum are small: when full-length items would leave a
     // stratum with too few of them to fill the chip, they are halved (more groups to spread over,
     // at the price of more partial sums); a fixed FM_SEG_STRAT or fm_set_tuning overrides this.
-    int seg = fm_tune().seg_strat;
+    int seg = m->tune.seg_strat;
     if (seg <= 0) {
-        seg = fm_tune().seg;
+        seg = m->tune.seg;
         FM_HIP(m, hipMemsetAsync(ti, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
         FM_HIP(m, hipMemsetAsync(tl, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
         hipLaunchKernelGGL(k_long_count, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, seg, tl, ti);
@@ -692,50 +690,6 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
 
 
 
-static int env_int(const char* name, int dflt, int lo, int hi)
-{
-    const char* e = getenv(name);
-    if (e == nullptr || *e == 0) return dflt;
-    const long v = strtol(e, nullptr, 10);
-    return (int)(v < lo ? lo : v > hi ? hi : v);
-}
-
-static FmTune& tune_mut()
-{
-    static FmTune t = {env_int("FM_SEG", 256, 16, 1 << 20), env_int("FM_PANEL", 32768, 64, 1 << 30),
-                       env_int("FM_HEAVY_PER_PANEL", 16, 1, 1 << 20), env_int("FM_VLONG", 512, 1, 1 << 30),
-                       env_int("FM_MIN_PANELS", 8 * FM_XCDS, 1, 1 << 30), env_int("FM_TILE", 0, 0, 1 << 20),
-                       env_int("FM_TILE_MIN", -1, -1, 1 << 20), env_int("FM_TILE_SEG", 0, 0, 1 << 20), 0};
-    static const bool once = [] {
-        t.seg_strat = env_int("FM_SEG_STRAT", 0, 0, 1 << 20);  // 0: chosen per matrix
-        return true;
-    }();
-    (void)once;
-    return t;
-}
-
-const FmTune& fm_tune() { return tune_mut(); }
-
-extern "C" int fm_set_tile_tuning(int32_t tile_rows, int32_t min_per_tile, int32_t tile_seg)
-{
-    FmTune& t = tune_mut();
-    if (tile_rows > 0) t.tile = tile_rows < 64 ? 64 : tile_rows;
-    if (min_per_tile >= 0) t.tile_min = min_per_tile;
-    if (tile_seg > 0) t.tile_seg = tile_seg < 16 ? 16 : tile_seg;
-    return FM_OK;
-}
-
-extern "C" int fm_set_tuning(int32_t seg, int32_t panel, int32_t heavy_per_panel, int32_t vlong, int32_t min_panels)
-{
-    FmTune& t = tune_mut();
-    if (seg > 0) t.seg = t.seg_strat = seg < 16 ? 16 : seg;
-    if (panel > 0) t.panel = panel < 64 ? 64 : panel;
-    if (heavy_per_panel > 0) t.heavy_per_panel = heavy_per_panel;
-    if (vlong > 0) t.vlong = vlong;
-    if (min_panels > 0) t.min_panels = min_panels;
-    return FM_OK;
-}
-
 // Frees the device arrays of an index and resets it.
 static void free_long_index(fm_matrix* m, LongIndex* li)
 {
@@ -749,9 +703,10 @@ static void free_long_index(fm_matrix* m, LongIndex* li)
 // Shape of the LDS tiles for N rows and latent size K (K = 0: not known yet).  Explicit settings win;
 // else two tiles must fit the LDS of a compute unit (1024 rows only while [G | r] of a row is at most
 // 17 floats) and the tile shrinks with the matrix.  Larger tiles mean fewer items, hence fewer partial sums to write and read back.
-void fm_tile_shape(int64_t N, int32_t K, int* tile_rows, int* tile_min, int* tile_seg)
+void fm_tile_shape(const fm_matrix* m, int32_t K, int* tile_rows, int* tile_min, int* tile_seg)
 {
-    const FmTune& T = fm_tune();
+    const FmTune& T = m->tune;
+    const int64_t N = m->N;
     // one workgroup works on one tile: tall matrices take big tiles (fewer items, hence fewer partial
     // sums), short ones small tiles (enough workgroups to fill the chip)
     int rows = 512, dense = 8, seg = 256;
@@ -771,12 +726,12 @@ int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st)
 {
     LongIndex* out = &m->lfull;
     free_long_index(m, out);
-    FmTune T = fm_tune();
-    fm_tile_shape(m->N, K, &T.tile, &T.tile_min, &T.tile_seg);
+    FmTune T = m->tune;
+    fm_tile_shape(m, K, &T.tile, &T.tile_min, &T.tile_seg);
     m->lfull_shape[0] = T.tile;
     m->lfull_shape[1] = T.tile_min;
     m->lfull_shape[2] = T.tile_seg;
-    FM_TRY(build_short_list(m, m->colptr, m->D, m->D, 1, fm_tune().seg, out, st));
+    FM_TRY(build_short_list(m, m->colptr, m->D, m->D, 1, m->tune.seg, out, st));
     out->nlong = out->nitems = 0;
     out->h_long_off.assign(2, 0);
     out->h_item_off.assign(2, 0);

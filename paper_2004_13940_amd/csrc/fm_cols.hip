@@ -606,16 +606,16 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_finish_block(const ColArgs A)
 // LDS-staged kernel for the tile items; false if the tile does not fit in LDS for this K
 // (the caller then runs the items through k_cols_long).
 template <int L>
-bool launch_tile_l(const ColArgs& A, size_t lds, hipStream_t st)
+bool launch_tile_l(fm_matrix* m, const ColArgs& A, size_t lds, hipStream_t st)
 {
-    static bool attr_set = false;  // opt in once to more than the default 64 KB of dynamic LDS
-    if (!attr_set) {
+    constexpr unsigned bit = 1u << __builtin_ctz((unsigned)L);
+    if (!(m->tile_attr_set & bit)) {  // opt in once per handle to more than the default 64 KB of dynamic LDS
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_cols_tile<L>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) != hipSuccess) {
             (void)hipGetLastError();
             if (lds > 64 * 1024) return false;
         }
-        attr_set = true;
+        m->tile_attr_set |= bit;
     }
     hipLaunchKernelGGL((k_cols_tile<L>), dim3((unsigned)A.ntiles), dim3(FM_BLOCK), lds, st, A);
     return true;
@@ -623,7 +623,6 @@ bool launch_tile_l(const ColArgs& A, size_t lds, hipStream_t st)
 
 inline bool launch_tile(fm_matrix* m, const ColArgs& A, hipStream_t st)
 {
-    (void)m;
     if (A.ntiles <= 0 || A.ntiles > 0x7fffffffLL || A.K % 4 != 0) return false;
     const size_t lds = (size_t)A.tile_rows * (size_t)(A.K + 1) * sizeof(float);
     // at least two workgroups per compute unit, or the copy of one tile cannot overlap the work on another
@@ -631,13 +630,13 @@ inline bool launch_tile(fm_matrix* m, const ColArgs& A, hipStream_t st)
     int need = A.K / 4, l = 1;
     while (l < need) l <<= 1;
     switch (l) {
-        case 1: return launch_tile_l<1>(A, lds, st);
-        case 2: return launch_tile_l<2>(A, lds, st);
-        case 4: return launch_tile_l<4>(A, lds, st);
-        case 8: return launch_tile_l<8>(A, lds, st);
-        case 16: return launch_tile_l<16>(A, lds, st);
-        case 32: return launch_tile_l<32>(A, lds, st);
-        case 64: return launch_tile_l<64>(A, lds, st);
+        case 1: return launch_tile_l<1>(m, A, lds, st);
+        case 2: return launch_tile_l<2>(m, A, lds, st);
+        case 4: return launch_tile_l<4>(m, A, lds, st);
+        case 8: return launch_tile_l<8>(m, A, lds, st);
+        case 16: return launch_tile_l<16>(m, A, lds, st);
+        case 32: return launch_tile_l<32>(m, A, lds, st);
+        case 64: return launch_tile_l<64>(m, A, lds, st);
     }
     return false;
 }

@@ -17,21 +17,27 @@ constexpr int FM_WAVES = FM_BLOCK / FM_WAVE;
 constexpr int FM_MAXP = 4096;
 constexpr int FM_XCDS = 8;                // L2 domains; workgroup b runs on XCD b % 8
 
-// Tunables of the column-side work decomposition (tile, tile_min < 0, tile_seg: 0 or negative = chosen
-// per latent size, see fm_tile_shape; read once from the environment:
-// FM_SEG, FM_SEG_STRAT, FM_PANEL, FM_HEAVY_PER_PANEL, FM_VLONG, FM_MIN_PANELS; or fm_set_tuning).
+// Tunables of the column-side work decomposition, per handle (fm_set_tuning, fm_set_tile_tuning;
+// tile, tile_min < 0, tile_seg: 0 or negative = chosen per latent size, see fm_tile_shape).
 struct FmTune {
-    int seg;              // entries per work item of a long column
-    int panel;            // rows per panel of the L2-blocked traversal of heavy columns
-    int heavy_per_panel;  // a column is heavy if it averages at least this many entries per panel
-    int vlong;            // columns with more items than this are finished by a whole workgroup
-    int min_panels;       // the panel order is used only for matrices with at least this many panels
-    int tile;             // rows per LDS tile of the kernel for dense-ish columns
-    int tile_min;         // a column is dense-ish if it averages this many entries per tile (0: none)
-    int tile_seg;         // entries per item inside a tile
-    int seg_strat;        // `seg` of the per-stratum matrices (FM_SEG_STRAT; fm_set_tuning sets both); 0: automatic
+    int seg = 256;             // entries per work item of a long column
+    int panel = 32768;         // rows per panel of the L2-blocked traversal of heavy columns
+    int heavy_per_panel = 16;  // a column is heavy if it averages at least this many entries per panel
+    int vlong = 512;           // columns with more items than this are finished by a whole workgroup
+    int min_panels = 8 * 8;    // the panel order is used only for matrices with at least this many panels
+    int tile = 0;              // rows per LDS tile of the kernel for dense-ish columns
+    int tile_min = -1;         // a column is dense-ish if it averages this many entries per tile (0: none)
+    int tile_seg = 0;          // entries per item inside a tile
+    int seg_strat = 0;         // `seg` of the per-stratum and per-batch matrices (fm_set_tuning sets both); 0: automatic
 };
-const FmTune& fm_tune();
+
+// Per-handle switches between code paths that compute the same thing (fm_set_option).
+struct FmOptions {
+    bool aux_planar = false;   // planar aggregates for every K (default: packed rows when [G | r] fits one line)
+    bool side_streams = true;  // column kernels that touch disjoint columns overlap on internal side streams
+    bool lazy_reg = true;      // regulariser-only steps of a stratified or mini-batch epoch are postponed
+    int graph = 1;             // stratified epoch from a captured graph: 0 never, 1 when launch-bound, 2 always
+};
 
 // Where the handle keeps the aggregates.  Packed (when [G | r] fits one 128-byte line: K % 4 == 0,
 // K <= 28): one row [G_0..G_{K-1}, r, a, q, pad] per example with a stride that is a multiple of
@@ -40,14 +46,14 @@ struct FmAux {
     float *G, *r, *a, *q;
     int64_t gs, ss;
 };
-bool fm_aux_packed(int32_t K);
+struct fm_matrix;
+bool fm_aux_packed(const fm_matrix* m, int32_t K);
 // floats per row of partial sums [acc_0..acc_{K-1} | gw | s2 | pad]: a multiple of 32 (128 bytes)
 inline int64_t fm_part_stride(int32_t K) { return ((int64_t)K + 2 + 31) / 32 * 32; }
 // How the column kernels read the aggregate rows (ColArgs::packed).
 enum { FM_PLANAR = 0, FM_PACKED_LANE = 1 };
-int fm_cols_packed_mode(int32_t K);
-int64_t fm_aux_floats(int64_t N, int32_t K);
-struct fm_matrix;
+int fm_cols_packed_mode(const fm_matrix* m, int32_t K);
+int64_t fm_aux_floats(const fm_matrix* m, int32_t K);
 FmAux fm_aux_layout(const fm_matrix* m, int32_t K);
 
 enum fm_kernel_id {
@@ -98,6 +104,9 @@ struct ProfRec {
 
 struct fm_matrix {
     int64_t N = 0, D = 0, nnz = 0;
+    FmTune tune;
+    FmOptions opt;
+    unsigned tile_attr_set = 0;  // bit log2(L): k_cols_tile<L> has been given its dynamic-LDS limit
     // CSR
     int64_t* rowptr = nullptr;
     int32_t* col = nullptr;
@@ -176,7 +185,7 @@ int fm_dev_alloc(fm_matrix* m, void** p, size_t bytes);
 void fm_dev_free(fm_matrix* m, void* p);
 void fm_drop_workspace(fm_matrix* m);  // forces reallocation after the structures changed
 void fm_drop_graph(fm_matrix* m);      // a captured epoch holds pointers into the workspace and the structures
-bool fm_side_streams(fm_matrix* m);    // creates them on first use; false if disabled (FM_SIDE_STREAMS=0)
+bool fm_side_streams(fm_matrix* m);    // creates them on first use; false if switched off or unavailable
 
 #define FM_HIP(m, expr)                                                                  \
     do {                                                                                 \
@@ -208,7 +217,7 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
                         LongIndex* out, hipStream_t st);
 // lfull, with the panel order of heavy columns and the LDS tiles shaped for latent size K (0: unknown)
 int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st);
-void fm_tile_shape(int64_t N, int32_t K, int* tile_rows, int* tile_min, int* tile_seg);
+void fm_tile_shape(const fm_matrix* m, int32_t K, int* tile_rows, int* tile_min, int* tile_seg);
 int fm_ensure_lazy(fm_matrix* m);  // allocates lazy_last on first use
 
 // ---- pass kernels (fm_rows.hip / fm_cols.hip / fm_reduce.hip) ----

@@ -95,12 +95,15 @@ def _say(*a):
 
 # ---- epoch runners shared by the parity tests: the library and the oracle side by side ----
 
-def run_full_epochs(B, wl, epochs, m=None):
-    """epochs of fm_sgd_epoch vs the oracle's full_epoch; returns final states."""
+def run_full_epochs(B, wl, epochs, m=None, setup=None):
+    """epochs of fm_sgd_epoch vs the oracle's full_epoch; returns final states.  ``setup(m)`` runs on the
+    new handle before its CSC is built (tuning and options)."""
     import torch
     X = O.make_matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
     if m is None:
         m = B.Matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
+        if setup is not None:
+            setup(m)
         m.fm_build_csc()
     p = B.make_params(wl.K, wl.loss, wl.lambda_w, wl.lambda_v, wl.eta, wl.loss_scale, wl.update_w0)
     d_w0, d_w, d_V = dev_params(wl.w0, wl.w, wl.V)

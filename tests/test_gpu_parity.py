@@ -362,10 +362,12 @@ def test_batch_csc_is_bit_exact(N, D, B, density):
     m.close()
 
 
-def _run_minibatch_epochs(Bm, wl, nb, epochs, full_reg=False, update_w0=True):
+def _run_minibatch_epochs(Bm, wl, nb, epochs, full_reg=False, update_w0=True, setup=None):
     import torch
     X = O.make_matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
     m = Bm.Matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
+    if setup is not None:
+        setup(m)
     m.fm_build_csc()
     m.fm_partition_batches(nb)
     p = Bm.make_params(wl.K, wl.loss, wl.lambda_w, wl.lambda_v, wl.eta, wl.loss_scale, int(update_w0),
@@ -530,9 +532,12 @@ def test_heavy_columns_through_the_panel_order_and_workgroup_finish():
     short columns, and columns summed by a whole workgroup."""
     import torch
     B = _B()
-    B.fm_set_tuning(seg=16, panel=64, heavy_per_panel=2, vlong=8, min_panels=4)
-    B.fm_set_tile_tuning(tile_rows=64, min_per_tile=12, tile_seg=16)
-    try:
+
+    def small_knobs(m):
+        m.fm_set_tuning(seg=16, panel=64, heavy_per_panel=2, vlong=8, min_panels=4)
+        m.fm_set_tile_tuning(tile_rows=64, min_per_tile=12, tile_seg=16)
+
+    if True:
         for K, loss in [(16, O.LOSS_LOGISTIC), (8, O.LOSS_SQUARED), (3, O.LOSS_LOGISTIC), (32, O.LOSS_SQUARED)]:
             N, D = 5000, 300
             rng = np.random.default_rng(40 + K)
@@ -549,11 +554,11 @@ def test_heavy_columns_through_the_panel_order_and_workgroup_finish():
             wl = Workload("panels", N, D, K, rowptr, col, val, y, np.float32(0.05), w, V, loss, 1e-3, 2e-3, 0.3,
                           1.0 / N, 3, 4, 1)
             _say("panel path", K, loss, len(col))
-            m, p, X, dev, host = _run_full_epochs(B, wl, 3)
+            m, p, X, dev, host = _run_full_epochs(B, wl, 3, setup=small_knobs)
+            with pytest.raises(B.FMError) as e:  # the decomposition is fixed once the CSC is built
+                m.fm_set_tuning(seg=32)
+            assert e.value.code == -5
             m.close()
-    finally:
-        B.fm_set_tuning(seg=256, panel=32768, heavy_per_panel=16, vlong=512, min_panels=64)
-        B.fm_set_tile_tuning(tile_rows=512, min_per_tile=8, tile_seg=256)
 
 
 # ------------------------------------------------------------ error paths ----
@@ -593,14 +598,56 @@ def test_state_and_argument_errors_are_reported():
     m.close()
 
 
-def test_gather_probe_reports_a_plausible_rate_and_rejects_bad_arguments():
-    B = _B()
-    rate = B.fm_probe_gather(64 << 20, 128)
+def test_bench_probes_report_plausible_figures_and_reject_bad_arguments():
+    """The calibration probes of bench.py live in a library of their own (not in the product ABI)."""
+    import torch
+    from paper_2004_13940_amd import bench_probe as P
+    rate = P.gather_rate(64 << 20, 128)
     assert 1e9 < rate < 1e12
+    with pytest.raises(RuntimeError):
+        P.gather_rate(64 << 20, 96)
+    with pytest.raises(RuntimeError):
+        P.gather_rate(1000, 64)
+    src = torch.arange(1 << 20, dtype=torch.float32, device="cuda")
+    dst = torch.zeros_like(src)
+    P.copy(src, dst, reps=2)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    assert not hasattr(_B().load(), "fm_probe_gather")
+
+
+@pytest.mark.parametrize("options", [
+    {"FM_OPT_AUX_PLANAR": 1},
+    {"FM_OPT_SIDE_STREAMS": 0},
+    {"FM_OPT_LAZY_REG": 0},
+    {"FM_OPT_GRAPH": 2},
+    {"FM_OPT_GRAPH": 0},
+    {"FM_OPT_AUX_PLANAR": 1, "FM_OPT_SIDE_STREAMS": 0, "FM_OPT_LAZY_REG": 0, "FM_OPT_GRAPH": 2},
+])
+@pytest.mark.parametrize("idx,scale", [(3, 0.1), (4, 0.002)])
+def test_every_option_gives_the_oracle_result(options, idx, scale):
+    """Each per-handle switch (planar aggregates at K=16, one stream only, immediate regulariser steps,
+    stratified epoch always or never from a graph) through full-gradient, stratified and mini-batch epochs."""
+    B = _B()
+    wl = make_config(idx, scale=scale)
+    _say("options", options, wl.name, wl.N, wl.D, wl.nnz)
+
+    def setup(m):
+        for name, value in options.items():
+            m.fm_set_option(getattr(B, name), value)
+
+    m, p, X, dev, host = _run_full_epochs(B, wl, 2, setup=setup)
+    m.fm_partition(wl.P)
+    host = _run_stratified_epochs(B, wl, m, p, X, dev, host, 2)
+    # switching the aggregate layout on a live handle: the next pass allocates the other layout
+    if "FM_OPT_AUX_PLANAR" in options:
+        m.fm_set_option(B.FM_OPT_AUX_PLANAR, 0)
+        host = _run_stratified_epochs(B, wl, m, p, X, dev, host, 1)
+    m.close()
+    m2, _, _ = _run_minibatch_epochs(B, wl, 5, 1, update_w0=bool(wl.update_w0), setup=setup)
+    m2.close()
     with pytest.raises(B.FMError):
-        B.fm_probe_gather(64 << 20, 96)
-    with pytest.raises(B.FMError):
-        B.fm_probe_gather(1000, 64)
+        B.Matrix(1, 1, np.array([0, 0]), np.array([], np.int32), np.array([], np.float32)).fm_set_option(99, 1)
 
 
 def test_random_shapes_through_every_epoch_kind():
