@@ -210,6 +210,68 @@ void oracle_cell_update(int32_t K, int32_t loss, double s, double eta, double rh
     free(gV);
 }
 
+/* The same cell step for a set of columns that need not be contiguous: the columns cols[0..ncols) that
+ * a worker holds in one round of Algorithm 1 when every column is handed from worker to worker on its
+ * own (Section 4.3: the parameter tuples circulate one by one; the initial placement is random).  The
+ * step of one column is the step of oracle_cell_update restricted to that column. */
+void oracle_cell_update_cols(int32_t K, int32_t loss, double s, double eta, double rho,
+                             double lambda_w, double lambda_v,
+                             int64_t i_lo, int64_t i_hi, int64_t ncols, const int32_t *cols,
+                             const int64_t *colptr, const int32_t *row, const double *cval,
+                             const double *y, double w0, const double *a, const double *G,
+                             const double *q, double *r, double *w, double *V,
+                             double *dw, double *dV, double *dn)
+{
+    for (int64_t i = i_lo; i < i_hi; ++i) {
+        double l;
+        loss_one(loss, s, yhat_from_aux(w0, a[i], G + i * K, q[i], K), y[i], &l, &r[i]);
+    }
+    double *gV = (double *)malloc((size_t)K * sizeof(double));
+    for (int64_t t = 0; t < ncols; ++t) {
+        const int64_t j = cols[t];
+        double g = 0.0, s2 = 0.0;
+        for (int32_t k = 0; k < K; ++k) gV[k] = 0.0;
+        for (int64_t e = colptr[j]; e < colptr[j + 1]; ++e) {
+            const int64_t i = row[e];
+            if (i < i_lo || i >= i_hi) continue; /* entry belongs to another worker's rows */
+            const double x = cval[e];
+            g += r[i] * x;
+            s2 += r[i] * x * x;
+            for (int32_t k = 0; k < K; ++k) gV[k] += r[i] * x * G[i * K + k];
+        }
+        double n_old = 0.0, n_new = 0.0;
+        dw[j] = -eta * (g + rho * lambda_w * w[j]);
+        w[j] += dw[j];
+        for (int32_t k = 0; k < K; ++k) {
+            const double v = V[j * K + k];
+            const double d = -eta * (gV[k] - s2 * v + rho * lambda_v * v);
+            dV[j * K + k] = d;
+            V[j * K + k] = v + d;
+            n_old += v * v;
+            n_new += (v + d) * (v + d);
+        }
+        dn[j] = n_new - n_old;
+    }
+    free(gV);
+}
+
+/* Phase B for such a set: the rows [i_lo,i_hi) take the changes of the columns with inset[j] != 0. */
+void oracle_refresh_cols(int32_t K, int64_t i_lo, int64_t i_hi, const uint8_t *inset,
+                         const int64_t *rowptr, const int32_t *col, const double *val,
+                         const double *dw, const double *dV, const double *dn,
+                         double *a, double *G, double *q)
+{
+    for (int64_t i = i_lo; i < i_hi; ++i)
+        for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+            const int64_t j = col[e];
+            if (!inset[j]) continue;
+            const double x = val[e];
+            a[i] += x * dw[j];
+            q[i] += x * x * dn[j];
+            for (int32_t k = 0; k < K; ++k) G[i * K + k] += x * dV[j * K + k];
+        }
+}
+
 /* Phase B, the incremental refresh (Section 4.2, "incremental synchronization"):
  * for rows [i_lo,i_hi) and their entries in columns [j_lo,j_hi):
  *   a_i += sum x_ij dw_j,  G_ik += sum x_ij dV_jk,  q_i += sum x_ij^2 dn_j. */

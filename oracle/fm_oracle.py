@@ -11,8 +11,8 @@ products for V=0, central finite differences of the objective, the ridge
 solution, dense transposes and brute-force cell masks.
 
 Parity unpinned (conventions with no external check): the share ``rho`` of the
-regulariser a cell step applies, and the moment the bias is updated in a
-stratified epoch.
+regulariser a cell step applies, the moment the bias is updated in a stratified
+epoch, and the direction in which a column is handed from worker to worker.
 """
 from __future__ import annotations
 
@@ -203,6 +203,68 @@ def refresh(X: Matrix, a, G, q, rows, cols, dw, dV, dn):
     K = G.shape[1]
     _L().oracle_refresh(_i32(K), _i64(rows[0]), _i64(rows[1]), _i64(cols[0]), _i64(cols[1]), _p(X.rowptr), _p(X.col),
                         _p(X.val), _p(dw), _p(dV), _p(dn), _p(a), _p(G), _p(q))
+
+
+def placed_epoch(X: Matrix, y, w0, w, V, *, P, place, loss, s, lambda_w, lambda_v, eta,
+                 update_w0=True, reg_share=True, stale_aux=True, on_round=None, final_objective=True):
+    """One epoch of the schedule of Algorithm 1 with every column handed on individually (Section 4.3).
+
+    Worker p owns the rows of row block p for good.  Column j (its w_j and v_j) starts at worker
+    ``place[j]`` (the paper places the parameters at random) and is handed on to the next worker after
+    every round, against the numbering of the workers, so that in round t it is at worker
+    (place[j] - t) mod P and after P rounds it has met every row block once; with
+    place[j] = column block of j this is the ring of ``stratified_epoch``.
+
+      aux (a,G,q) <- forward from scratch                        (the re-computation loop)
+      for round t = 0..P-1, for every worker p with the columns J it holds in this round:
+          r_I from aux; block gradient of the columns of J over the rows of p; step on w_J, V_J
+          (``stale_aux``: nothing else, the update phase of Algorithm 1 reads stale aggregates;
+           otherwise worker p refreshes its own rows with the changes of J, as in Section 4.2)
+      bias step from the aux as it stands; objective from a fresh forward.
+
+    ``on_round(t, state)`` is called after every round; state["held"][p] lists the columns worker p held.
+    """
+    y = _c(y, np.float64)
+    w, V = _c(w, np.float64).copy(), _c(V, np.float64).copy()
+    place = _c(place, np.int64)
+    K = V.shape[1]
+    N, D = X.N, X.D
+    if place.shape != (D,) or (D and (place.min() < 0 or place.max() >= P)):
+        raise ValueError("place must hold one worker in [0, P) per column")
+    rb = block_bounds(N, P)
+    a, G, q, _ = forward(X, w0, w, V)
+    r = np.zeros(N)
+    dw, dV, dn = np.zeros(D), np.zeros((D, K)), np.zeros(D)
+    L = _L()
+    for t in range(P):
+        at = (place - t) % P  # the worker every column is at in this round
+        held = [np.flatnonzero(at == p).astype(np.int32) for p in range(P)]
+        for p in range(P):
+            rho = (rb[p + 1] - rb[p]) / N if reg_share else 1.0
+            L.oracle_cell_update_cols(_i32(K), _i32(loss), _f64(s), _f64(eta), _f64(rho), _f64(lambda_w),
+                                      _f64(lambda_v), _i64(rb[p]), _i64(rb[p + 1]), _i64(len(held[p])),
+                                      _p(held[p]), _p(X.colptr), _p(X.row), _p(X.cval), _p(y), _f64(w0), _p(a),
+                                      _p(G), _p(q), _p(r), _p(w), _p(V), _p(dw), _p(dV), _p(dn))
+        if not stale_aux:
+            for p in range(P):
+                inset = (at == p).astype(np.uint8)
+                L.oracle_refresh_cols(_i32(K), _i64(rb[p]), _i64(rb[p + 1]), _p(inset), _p(X.rowptr), _p(X.col),
+                                      _p(X.val), _p(dw), _p(dV), _p(dn), _p(a), _p(G), _p(q))
+        if on_round is not None:
+            on_round(t, dict(a=a, G=G, q=q, r=r, w=w, V=V, held=held))
+    if update_w0:
+        L.oracle_multiplier_from_aux(_i64(N), _i32(K), _i32(loss), _f64(s), _f64(w0), _p(a), _p(G),
+                                     _p(q), _p(y), _p(r))
+        w0 = float(w0) - eta * float(np.sum(r))
+    obj = objective(loss, s, lambda_w, lambda_v, X, y, w0, w, V) if final_objective else None
+    return float(w0), w, V, obj, dict(a=a, G=G, q=q, r=r)
+
+
+def block_placement(D, P):
+    """place[j] = column block of j in the contiguous floor split: the placement that turns
+    ``placed_epoch`` into the ring of ``stratified_epoch``."""
+    cb = block_bounds(D, P)
+    return (np.searchsorted(cb, np.arange(D), side="right") - 1).astype(np.int32)
 
 
 def stratified_epoch(X: Matrix, y, w0, w, V, *, P, loss, s, lambda_w, lambda_v, eta,

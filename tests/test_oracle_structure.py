@@ -377,3 +377,115 @@ def test_batch_csc_keeps_each_entry_in_exactly_one_batch():
         np.testing.assert_array_equal(sub, want)
         total += len(row)
     assert total == len(X.col)
+
+
+# ---- Algorithm 1 with every column handed on individually (placed_epoch) ----
+
+@pytest.mark.parametrize("stale", [True, False])
+@pytest.mark.parametrize("P", [1, 3, 5])
+def test_block_placement_reproduces_the_ring(P, stale):
+    """With place[j] = column block of j the per-column schedule is the ring of stratified_epoch:
+    same cells in the same rounds, so every number agrees bit for bit (stale and refreshed)."""
+    rng, X, Xs, y, w, V = _rand_problem(51, 70, 23, 3, 0.3)
+    kw = dict(P=P, loss=O.LOSS_LOGISTIC, s=1.0 / 70, lambda_w=2e-2, lambda_v=1e-2, eta=0.4)
+    a = O.stratified_epoch(X, y, 0.1, w, V, stale_aux=stale, **kw)
+    b = O.placed_epoch(X, y, 0.1, w, V, place=O.block_placement(X.D, P), stale_aux=stale, **kw)
+    assert a[0] == b[0]
+    np.testing.assert_array_equal(a[1], b[1])
+    np.testing.assert_array_equal(a[2], b[2])
+    for k in ("a", "G", "q", "r"):
+        np.testing.assert_array_equal(a[4][k], b[4][k])
+
+
+def test_every_column_meets_every_row_block_once_whatever_the_placement():
+    rng, X, Xs, y, w, V = _rand_problem(52, 40, 17, 2, 0.3)
+    P = 6
+    place = rng.integers(0, P, X.D)
+    seen = np.zeros((P, X.D), int)
+
+    def on_round(t, st):
+        held = st["held"]
+        assert sorted(np.concatenate(held).tolist()) == list(range(X.D))  # every column is somewhere, once
+        for p in range(P):
+            seen[p, held[p]] += 1
+        if t == 0:
+            for p in range(P):
+                assert set(held[p].tolist()) == set(np.flatnonzero(place == p).tolist())  # the initial placement
+
+    O.placed_epoch(X, y, 0.0, w, V, P=P, place=place, loss=O.LOSS_LOGISTIC, s=1.0, lambda_w=0.0, lambda_v=0.0,
+                   eta=0.1, on_round=on_round)
+    assert (seen == 1).all()
+
+
+@pytest.mark.parametrize("loss", [O.LOSS_SQUARED, O.LOSS_LOGISTIC])
+def test_stale_placed_epoch_without_regulariser_matches_the_closed_form(loss):
+    """lambda = 0, stale aggregates: the multipliers never change, so w and w0 take exactly one
+    full-gradient step whatever the placement, and v_j follows the affine maps
+    v <- v - eta (gV_p - s2_p v) over the row blocks in the order column j meets them,
+    place[j], place[j]-1, ... (mod P), with gV_p, s2_p from the frozen r and G (dense products here)."""
+    rng, X, Xs, y, w, V = _rand_problem(53, 60, 19, 4, 0.35)
+    N, D = Xs.shape
+    P = 5
+    place = rng.integers(0, P, D)
+    kw = dict(loss=loss, s=1.0 / N, lambda_w=0.0, lambda_v=0.0, eta=0.09)
+    w0a, wa, _, _ = O.full_epoch(X, y, 0.2, w, V, **kw)
+    _, G0, _, yh = O.forward(X, 0.2, w, V)
+    _, r0 = O.loss_multiplier(loss, kw["s"], yh, y)
+    w0b, wb, Vb, _, aux = O.placed_epoch(X, y, 0.2, w, V, P=P, place=place, stale_aux=True, **kw)
+    np.testing.assert_allclose(wb, wa, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(w0b, w0a, rtol=1e-12)
+    rb = O.block_bounds(N, P)
+    Xd = Xs.toarray()
+    want = V.copy()
+    for j in range(D):
+        for t in range(P):
+            pb = (place[j] - t) % P
+            I = slice(rb[pb], rb[pb + 1])
+            x = Xd[I, j]
+            gV = (x * r0[I]) @ G0[I]
+            s2 = (x * x) @ r0[I]
+            want[j] = want[j] - kw["eta"] * (gV - s2 * want[j])
+    np.testing.assert_allclose(Vb, want, rtol=1e-11, atol=1e-15)
+    np.testing.assert_allclose(aux["G"], Xs @ V, rtol=1e-12, atol=1e-14)  # never refreshed
+
+
+def test_stale_placed_epoch_without_data_shrinks_every_column_by_all_shares():
+    """r = 0 (squared loss at y = yhat): every column meets every row block once, so it is multiplied by
+    prod_p (1 - eta rho_p lambda) whatever the placement."""
+    rng, X, Xs, y, w, V = _rand_problem(54, 50, 18, 3, 0.3)
+    _, _, _, yh = O.forward(X, 0.0, w, V)
+    P, eta, lw, lv = 4, 0.3, 0.2, 0.1
+    place = rng.integers(0, P, X.D)
+    _, wb, Vb, _, _ = O.placed_epoch(X, yh, 0.0, w, V, P=P, place=place, stale_aux=True, loss=O.LOSS_SQUARED, s=1.0,
+                                     lambda_w=lw, lambda_v=lv, eta=eta)
+    rb = O.block_bounds(X.N, P)
+    fw = np.prod([1 - eta * lw * (rb[p + 1] - rb[p]) / X.N for p in range(P)])
+    fv = np.prod([1 - eta * lv * (rb[p + 1] - rb[p]) / X.N for p in range(P)])
+    np.testing.assert_allclose(wb, w * fw, rtol=1e-12)
+    np.testing.assert_allclose(Vb, V * fv, rtol=1e-12)
+
+
+def test_refreshed_placed_epoch_keeps_own_deltas_and_differs_from_the_stale_one():
+    """With the incremental refresh a worker's aggregates hold exactly the changes it applied itself:
+    G_I = X_I V0 + sum over the rounds of X_{I,J_t} dV_{J_t}; and the result differs from the stale epoch."""
+    rng, X, Xs, y, w, V = _rand_problem(55, 48, 20, 3, 0.3)
+    P = 4
+    place = rng.integers(0, P, X.D)
+    kw = dict(P=P, place=place, loss=O.LOSS_LOGISTIC, s=1.0, lambda_w=1e-3, lambda_v=1e-3, eta=0.05)
+    rb = O.block_bounds(X.N, P)
+    Xd = Xs.toarray()
+    want = Xd @ V
+    prev = {"V": V.copy()}
+
+    def on_round(t, st):
+        dV = st["V"] - prev["V"]
+        for p in range(P):
+            I = slice(rb[p], rb[p + 1])
+            J = st["held"][p]
+            want[I] += Xd[I][:, J] @ dV[J]
+        prev["V"] = st["V"].copy()
+        np.testing.assert_allclose(st["G"], want, rtol=1e-11, atol=1e-13)
+
+    a = O.placed_epoch(X, y, 0.0, w, V, stale_aux=False, on_round=on_round, **kw)
+    b = O.placed_epoch(X, y, 0.0, w, V, stale_aux=True, **kw)
+    assert np.abs(a[2] - b[2]).max() > 1e-6
