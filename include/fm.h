@@ -86,6 +86,18 @@ int fm_build_csc(fm_matrix* m, void* hip_stream);
  * Needs fm_build_csc.  1 <= P <= 4096. */
 int fm_partition(fm_matrix* m, int32_t P, void* hip_stream);
 
+/* The same with every column handed from worker to worker on its own (Algorithm 1; Section 4.3: the
+ * parameter tuples circulate one by one, initial placement at random).  Rows are split into P floor-split
+ * row blocks as above; column j starts at worker place[j] in [0,P) (HOST, D entries, e.g. drawn from a
+ * seeded generator) and is handed on after every round against the numbering of the workers: in round
+ * s it is at worker (place[j] - s) mod P, and after P rounds it has met every row block once.  Round s
+ * takes the place of stratum s in every stratified call (fm_stratified_epoch with stale_aux = 1 is
+ * Algorithm 1's update phase followed, at the next epoch's start, by its re-computation loop; without
+ * stale_aux a worker refreshes its own rows after every round).  place[j] = column block of j gives
+ * fm_partition.  In fm_get_block_index cell_nnz[p*P + c] then counts the entries of row block p in the
+ * columns placed at worker c, and col_bounds must be NULL. */
+int fm_partition_placed(fm_matrix* m, int32_t P, const int32_t* place /*HOST D*/, void* hip_stream);
+
 /* Copies for bit-exact checks (HOST outputs, sized by the caller). */
 int fm_get_csc(const fm_matrix* m, int64_t* colptr /*D+1*/, int32_t* row /*nnz*/, float* val /*nnz*/);
 int fm_get_block_index(const fm_matrix* m, int64_t* row_bounds /*P+1*/, int64_t* col_bounds /*P+1*/,

@@ -394,40 +394,41 @@ def batch_csc(X: Matrix, B, b):
     return colptr, X.row[keep], X.cval[keep]
 
 
-def stratum_of_entries(N, D, P, rows, cols):
-    """Stratum (q - p) mod P of entries given by their row and column indices."""
+def stratum_of_entries(N, D, P, rows, cols, place=None):
+    """Stratum (q - p) mod P of entries given by their row and column indices; q is the column block,
+    or place[column] when the columns are placed one by one (then the stratum is the round)."""
     rb, cb = block_bounds(N, P), block_bounds(D, P)
     p = np.searchsorted(rb, rows, side="right") - 1
     # empty blocks repeat a boundary: searchsorted(right)-1 lands on the last of
     # the repeated boundaries, which is the one non-empty block holding the index
-    q = np.searchsorted(cb, cols, side="right") - 1
+    q = np.searchsorted(cb, cols, side="right") - 1 if place is None else np.asarray(place, np.int64)[cols]
     return ((q - p) % P).astype(np.int64), p, q
 
 
-def cell_nnz(X: Matrix, P):
+def cell_nnz(X: Matrix, P, place=None):
     """P x P table of stored entries per cell."""
     rows = np.repeat(np.arange(X.N, dtype=np.int64), np.diff(X.rowptr))
-    _, p, q = stratum_of_entries(X.N, X.D, P, rows, X.col.astype(np.int64))
+    _, p, q = stratum_of_entries(X.N, X.D, P, rows, X.col.astype(np.int64), place)
     out = np.zeros((P, P), np.int64)
     np.add.at(out, (p, q), 1)
     return out
 
 
-def stratum_csr(X: Matrix, P, s):
+def stratum_csr(X: Matrix, P, s, place=None):
     """CSR (rowptr over all N rows, col, val) of the matrix that keeps only the
     entries lying in the cells of stratum s."""
     rows = np.repeat(np.arange(X.N, dtype=np.int64), np.diff(X.rowptr))
-    st, _, _ = stratum_of_entries(X.N, X.D, P, rows, X.col.astype(np.int64))
+    st, _, _ = stratum_of_entries(X.N, X.D, P, rows, X.col.astype(np.int64), place)
     keep = st == s
     rowptr = np.zeros(X.N + 1, np.int64)
     np.cumsum(np.bincount(rows[keep], minlength=X.N), out=rowptr[1:])
     return rowptr, X.col[keep], X.val[keep]
 
 
-def stratum_csc(X: Matrix, P, s):
+def stratum_csc(X: Matrix, P, s, place=None):
     """CSC (colptr over all D columns, row, val) of the same per-stratum matrix."""
     cols = np.repeat(np.arange(X.D, dtype=np.int64), np.diff(X.colptr))
-    st, _, _ = stratum_of_entries(X.N, X.D, P, X.row.astype(np.int64), cols)
+    st, _, _ = stratum_of_entries(X.N, X.D, P, X.row.astype(np.int64), cols, place)
     keep = st == s
     colptr = np.zeros(X.D + 1, np.int64)
     np.cumsum(np.bincount(cols[keep], minlength=X.D), out=colptr[1:])

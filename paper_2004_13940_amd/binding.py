@@ -33,7 +33,7 @@ class FMError(RuntimeError):
         self.code = code
 
 
-EXPORTS = ["fm_build_csr", "fm_build_csc", "fm_partition", "fm_get_csc", "fm_get_block_index",
+EXPORTS = ["fm_build_csr", "fm_build_csc", "fm_partition", "fm_partition_placed", "fm_get_csc", "fm_get_block_index",
            "fm_get_stratum_nnz", "fm_get_stratum_csr", "fm_get_stratum_csc", "fm_partition_batches",
            "fm_get_batch_csc", "fm_forward", "fm_forward_noalloc", "fm_evaluate", "fm_gradient",
            "fm_sgd_epoch", "fm_minibatch_epoch", "fm_stratified_epoch", "fm_stratified_begin", "fm_stratified_step",
@@ -156,6 +156,14 @@ class Matrix:
         self._check(load().fm_partition(self._h, ctypes.c_int32(P), _stream(stream)))
         self.P = int(P)
 
+    def fm_partition_placed(self, P, place, stream=None):
+        place = np.ascontiguousarray(place, dtype=np.int32)
+        if place.shape != (self.D,):
+            raise ValueError("place must have D entries")
+        self._check(load().fm_partition_placed(self._h, ctypes.c_int32(P), _vp(place), _stream(stream)))
+        self.P = int(P)
+        self.placed = True
+
     def fm_get_csc(self):
         colptr = np.empty(self.D + 1, np.int64)
         row = np.empty(self.nnz, np.int32)
@@ -165,7 +173,7 @@ class Matrix:
 
     def fm_get_block_index(self):
         rb = np.empty(self.P + 1, np.int64)
-        cb = np.empty(self.P + 1, np.int64)
+        cb = None if getattr(self, "placed", False) else np.empty(self.P + 1, np.int64)
         cells = np.empty((self.P, self.P), np.int64)
         self._check(load().fm_get_block_index(self._h, _vp(rb), _vp(cb), _vp(cells)))
         return rb, cb, cells

@@ -192,6 +192,8 @@ extern "C" int fm_get_block_index(const fm_matrix* m, int64_t* row_bounds, int64
     if (m == nullptr) return FM_EINVAL;
     fm_matrix* mm = const_cast<fm_matrix*>(m);
     if (m->P == 0) return fm_fail(mm, FM_ESTATE, "matrix not partitioned");
+    if (col_bounds != nullptr && m->d_place != nullptr)
+        return fm_fail(mm, FM_ESTATE, "the columns were placed one by one (fm_partition_placed): there are no column blocks");
     if (row_bounds) memcpy(row_bounds, m->h_rb.data(), (size_t)(m->P + 1) * sizeof(int64_t));
     if (col_bounds) memcpy(col_bounds, m->h_cb.data(), (size_t)(m->P + 1) * sizeof(int64_t));
     if (cell_nnz) memcpy(cell_nnz, m->h_cell_nnz.data(), (size_t)m->P * m->P * sizeof(int64_t));
@@ -669,6 +671,7 @@ static void strat_col_args(fm_matrix* m, const fm_params* p, int32_t s, float* w
     A.P = m->P;
     A.s = s;
     if (!p->reg_full_per_cell) set_shares(A, m->d_rho, m->d_rb, m->N, m->P);
+    A.place = m->d_place;
     if (lazy) A.lazy_last = m->lazy_last;
 }
 

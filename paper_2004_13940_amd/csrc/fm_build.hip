@@ -187,7 +187,7 @@ __global__ void k_ptr_from_sorted(const uint32_t* __restrict__ keys, int64_t n, 
 // being processed (rowptr for CSR, colptr for CSC) and `minor` its index array.
 __global__ void k_stratum_keys(const int64_t* __restrict__ major, int64_t nmajor, const int32_t* __restrict__ minor,
                                int64_t n, int64_t N, int64_t D, int32_t P, int by_rows,
-                               uint32_t* __restrict__ keys, uint32_t* __restrict__ idx,
+                               const int32_t* __restrict__ place, uint32_t* __restrict__ keys, uint32_t* __restrict__ idx,
                                unsigned long long* __restrict__ cnt)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -201,7 +201,7 @@ __global__ void k_stratum_keys(const int64_t* __restrict__ major, int64_t nmajor
     if (by_rows == 2) {  // row batches: the key is the row block alone
         s = p;
     } else {
-        const int32_t q = fm_block_of(j, D, P);
+        const int32_t q = place != nullptr ? place[j] : fm_block_of(j, D, P);
         s = (q - p) % P;
         if (s < 0) s += P;
     }
@@ -220,6 +220,16 @@ __global__ void k_gather_pairs(const uint32_t* __restrict__ perm, const int32_t*
         ind_out[i] = ind[e];
         val_out[i] = val[e];
     }
+}
+
+// cell[p*P + c] += 1 for every stored entry in row block p whose column was placed at worker c
+__global__ void k_cell_count(const int64_t* __restrict__ rowptr, int64_t N, const int32_t* __restrict__ col, int64_t n,
+                             const int32_t* __restrict__ place, int32_t P, unsigned long long* __restrict__ cell)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n) return;
+    const int32_t p = fm_block_of(owner_of(rowptr, N, e), N, P);
+    atomicAdd(&cell[(int64_t)p * P + place[col[e]]], 1ull);
 }
 
 // out[s*(P+1)+q] = s_colptr[s*D + cb[q]]
@@ -929,7 +939,8 @@ static int build_strata_side(fm_matrix* m, bool by_rows, hipStream_t st, int64_t
     FM_TRY(fm_dev_alloc(m, (void**)&k1, (size_t)n * 4));
     FM_TRY(fm_dev_alloc(m, (void**)&i1, (size_t)n * 4));
     hipLaunchKernelGGL(k_stratum_keys, dim3(blocks_for(n, 256)), dim3(256), 0, st, major, nmajor, minor, n, m->N,
-                       m->D, P, batches ? 2 : (by_rows ? 1 : 0), k0, i0, (unsigned long long*)*sptr_out);
+                       m->D, P, batches ? 2 : (by_rows ? 1 : 0), batches ? nullptr : (const int32_t*)m->d_place, k0, i0,
+                       (unsigned long long*)*sptr_out);
     FM_HIP(m, hipGetLastError());
     FM_TRY(fm_scan_exclusive_i64(m, *sptr_out, (int64_t)np, st));
     bool alt = false;
@@ -946,10 +957,26 @@ static int build_strata_side(fm_matrix* m, bool by_rows, hipStream_t st, int64_t
     return FM_OK;
 }
 
+static int partition_impl(fm_matrix* m, int32_t P, const int32_t* place, hipStream_t st);
+
 extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
 {
     if (m == nullptr) return FM_EINVAL;
-    hipStream_t st = (hipStream_t)hip_stream;
+    return partition_impl(m, P, nullptr, (hipStream_t)hip_stream);
+}
+
+extern "C" int fm_partition_placed(fm_matrix* m, int32_t P, const int32_t* place, void* hip_stream)
+{
+    if (m == nullptr) return FM_EINVAL;
+    if (place == nullptr) return fm_fail(m, FM_EINVAL, "place is NULL");
+    for (int64_t j = 0; j < m->D; ++j)
+        if (place[j] < 0 || place[j] >= P)
+            return fm_fail(m, FM_ERANGE, "place[%lld] = %d outside [0,%d)", (long long)j, place[j], P);
+    return partition_impl(m, P, place, (hipStream_t)hip_stream);
+}
+
+static int partition_impl(fm_matrix* m, int32_t P, const int32_t* place, hipStream_t st)
+{
     if (!m->has_csc) return fm_fail(m, FM_ESTATE, "fm_partition needs fm_build_csc first");
     if (P < 1 || P > FM_MAXP) return fm_fail(m, FM_EINVAL, "P=%d outside 1..%d", P, FM_MAXP);
     if (m->P != 0) return fm_fail(m, FM_ESTATE, "matrix is already partitioned (P=%d)", m->P);
@@ -970,7 +997,13 @@ extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
     FM_TRY(fm_dev_alloc(m, (void**)&m->d_rb, (size_t)(P + 1) * sizeof(int64_t)));
     FM_HIP(m, hipMemcpy(m->d_rb, m->h_rb.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
     FM_TRY(fm_ensure_lazy(m));
-    FM_HIP(m, hipMemcpy(d_cb, m->h_cb.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
+    std::vector<int64_t> h_cbk = m->h_cb;  // column bounds at which the cell table is read off the per-stratum CSC
+    if (place != nullptr) {
+        FM_TRY(fm_dev_alloc(m, (void**)&m->d_place, (size_t)m->D * sizeof(int32_t)));
+        FM_HIP(m, hipMemcpy(m->d_place, place, (size_t)m->D * sizeof(int32_t), hipMemcpyHostToDevice));
+        for (int32_t b = 1; b <= P; ++b) h_cbk[b] = m->D;  // only the start of every stratum is read this way
+    }
+    FM_HIP(m, hipMemcpy(d_cb, h_cbk.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
 
     FM_TRY(build_strata_side(m, true, st, &m->s_rowptr, &m->s_col, &m->s_val, P));
     FM_TRY(build_strata_side(m, false, st, &m->s_colptr, &m->s_row, &m->s_cval, P));
@@ -995,6 +1028,19 @@ extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
         }
     }
     m->h_strat_nnz_off[P] = m->nnz;
+    if (place != nullptr) {  // cells (row block, worker the column started at): counted entry by entry
+        unsigned long long* d_cell = nullptr;
+        FM_TRY(fm_dev_alloc(m, (void**)&d_cell, (size_t)P * P * sizeof(unsigned long long)));
+        FM_HIP(m, hipMemsetAsync(d_cell, 0, (size_t)P * P * sizeof(unsigned long long), st));
+        if (m->nnz > 0) {
+            hipLaunchKernelGGL(k_cell_count, dim3(blocks_for(m->nnz, 256)), dim3(256), 0, st, (const int64_t*)m->rowptr,
+                               m->N, (const int32_t*)m->col, m->nnz, (const int32_t*)m->d_place, P, d_cell);
+            FM_HIP(m, hipGetLastError());
+        }
+        FM_HIP(m, hipMemcpyAsync(m->h_cell_nnz.data(), d_cell, (size_t)P * P * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+        FM_HIP(m, hipStreamSynchronize(st));
+        fm_dev_free(m, d_cell);
+    }
     fm_dev_free(m, d_starts);
     fm_dev_free(m, d_cb);
     FM_TRY(fm_build_long_index(m, m->s_colptr, (int64_t)P * m->D, m->D, P, &m->lstrat, st));

@@ -43,7 +43,15 @@ __device__ __forceinline__ void accumulate_entries(const ColArgs& A, int64_t beg
     }
 }
 
-// Share of the regulariser that the step of stratum t applies to column block qb.
+// The class of column j that decides which row block it meets in which stratum: its column block in
+// the ring of Section 4.2, or the worker it was placed at when columns travel one by one (Section 4.3).
+__device__ __forceinline__ int32_t column_class(const ColArgs& A, int64_t j)
+{
+    if (A.rho == nullptr || A.batch) return 0;
+    return A.place != nullptr ? A.place[j] : fm_block_of(j, A.D, A.P);
+}
+
+// Share of the regulariser that the step of stratum t applies to a column of class qb.
 __device__ __forceinline__ float reg_share(const ColArgs& A, int32_t qb, int32_t t)
 {
     if (A.rho == nullptr) return 1.f;
@@ -137,7 +145,7 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
                                               const float (&acc)[VEC], float gw, float s2, ColState<VEC> c)
 {
     const int K = A.K;
-    const int32_t qb = (A.rho != nullptr && !A.batch) ? fm_block_of(j, A.D, A.P) : 0;
+    const int32_t qb = column_class(A, j);
     const float rho = reg_share(A, qb, A.s);
     float fv = 1.f, fw = 1.f;
     if (c.t0 < A.s) catch_up_factors(A, qb, c.t0, A.s, fv, fw);  // postponed regulariser-only steps
@@ -240,7 +248,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_empty(const ColArgs A)
         finish_column<VEC, LE, false>(A, j, sub, kbase, kact, acc, 0.f, 0.f,
                                       load_column<VEC, false>(A, j, sub, kbase, kact));
     } else {
-        const int32_t qb = (A.rho != nullptr && !A.batch) ? fm_block_of(j, A.D, A.P) : 0;
+        const int32_t qb = column_class(A, j);
         const float rho = reg_share(A, qb, A.s);
         float dn = 0.f;
         if (kact) {
@@ -280,7 +288,7 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_flush(const ColArgs A)
     if (j >= A.D) return;  // whole groups leave together
     const int32_t t0 = A.lazy_last[j];
     if (t0 >= A.s) return;
-    const int32_t qb = (A.rho != nullptr && !A.batch) ? fm_block_of(j, A.D, A.P) : 0;
+    const int32_t qb = column_class(A, j);
     float fv, fw;
     catch_up_factors(A, qb, t0, A.s, fv, fw);
     const int kbase = sub * VEC;

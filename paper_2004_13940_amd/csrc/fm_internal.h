@@ -121,6 +121,7 @@ struct fm_matrix {
     // double partition and per-stratum matrices
     int32_t P = 0;
     std::vector<int64_t> h_rb, h_cb, h_cell_nnz, h_strat_nnz_off;  // bounds, P*P table, P+1 offsets
+    int32_t* d_place = nullptr;    // [D] worker every column starts at (fm_partition_placed), nullptr: its column block
     float* d_rho = nullptr;        // [P] share |I_p|/N of the regulariser that a step on row block p applies
     int64_t* d_rb = nullptr;       // [P+1] row block bounds
     int64_t* d_bb = nullptr;       // [B+1] batch bounds
@@ -269,7 +270,9 @@ struct ColArgs {
     const int32_t* short_col;  // list of the short non-empty columns of this launch
     int64_t nshort;
     float lambda_w, lambda_v, eta;
-    // regulariser share: rho = 1 when rho == nullptr, else rho[p] = |I_p|/N with p = (colblock(j) - s) mod P
+    // regulariser share: rho = 1 when rho == nullptr, else rho[p] = |I_p|/N with p = (c(j) - s) mod P, where
+    // c(j) = place[j], or the column block of j when place == nullptr
+    const int32_t* place;
     const float* rho;
     const int64_t* rb;           // with rho: [P+1] bounds of the row blocks (strata) or batches
     float rho_small, rho_big;    // with rho: the shares of a block of floor(N/P) rows and of one more

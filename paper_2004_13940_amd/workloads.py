@@ -341,6 +341,12 @@ def make_config(index: int, seed: int | None = None, scale: float = 1.0) -> Work
     return wl
 
 
+def random_placement(D: int, P: int, seed: int) -> np.ndarray:
+    """Seeded initial placement of the D columns on P workers, uniform at random (Algorithm 1 places
+    the parameters at random before the first round)."""
+    return np.random.Generator(np.random.PCG64(seed)).integers(0, P, D).astype(np.int32)
+
+
 def random_csr(rng: np.random.Generator, N: int, D: int, density: float,
                empty_rows: bool = True) -> tuple[np.ndarray, np.ndarray, np.ndarray]:
     """Small random CSR matrix with N(0,1) values for unit tests (rows may be

@@ -561,6 +561,90 @@ def test_heavy_columns_through_the_panel_order_and_workgroup_finish():
             m.close()
 
 
+# ----------------------------------------- columns handed on one by one ----
+
+def _run_placed_epochs(B, wl, P, place, epochs, stale):
+    """fm_partition_placed + fm_stratified_epoch against the oracle's placed_epoch."""
+    import torch
+    m, p, X, dev, host = _run_full_epochs(B, wl, 0)
+    m.fm_partition_placed(P, place)
+    p.stale_aux = int(stale)
+    d_w0, d_w, d_V, d_y = dev
+    w0, w, V = host
+    for ep in range(epochs):
+        obj = m.fm_stratified_epoch(p, d_y, d_w0, d_w, d_V, want_objective=True)
+        w0, w, V, wobj, _ = O.placed_epoch(X, wl.y, w0, w, V, P=P, place=place, stale_aux=stale,
+                                           update_w0=bool(wl.update_w0), **oracle_kw(wl))
+        torch.cuda.synchronize()
+        _say(f"  placed epoch {ep} (stale={stale}): objective gpu {sum(obj):.8f} oracle {sum(wobj):.8f}")
+        assert abs(obj[0] - wobj[0]) <= REL_TOL * abs(wobj[0])
+        assert abs(obj[1] - wobj[1]) <= REL_TOL * abs(wobj[1]) + 1e-12
+        assert_close(d_w.cpu().numpy(), w, f"w after placed epoch {ep}")
+        assert_close(d_V.cpu().numpy().reshape(wl.D, wl.K), V, f"V after placed epoch {ep}")
+        assert abs(d_w0.item() - w0) <= REL_TOL * max(abs(w0), 1e-3)
+    return m, X
+
+
+@pytest.mark.parametrize("stale", [True, False])
+@pytest.mark.parametrize("N,D,P,K", [(300, 40, 4, 8), (97, 23, 7, 3), (2300, 50, 64, 16), (50, 9, 1, 4)])
+def test_columns_placed_one_by_one_match_the_oracle(N, D, P, K, stale):
+    """Algorithm 1's schedule with a seeded random initial placement of every column: structures bit for bit,
+    then two epochs (update phase on stale aggregates, or with the own-row refresh) against the oracle."""
+    from paper_2004_13940_amd.workloads import Workload, random_placement
+    B = _B()
+    rowptr, col, val, y, w0, w, V = _problem(1300 + P + K, N, D, K, 0.15, O.LOSS_LOGISTIC, dense_cols=(2,))
+    wl = Workload("placed", N, D, K, rowptr, col, val, y, w0, w, V, O.LOSS_LOGISTIC, 1e-2, 2e-2, 0.5, 1.0 / N, 1, P, 1)
+    place = random_placement(D, P, seed=77 + P)
+    _say("placed", N, D, P, K, stale, len(col))
+    m, X = _run_placed_epochs(B, wl, P, place, 2, stale)
+    rb, cb, cells = m.fm_get_block_index()
+    assert cb is None
+    np.testing.assert_array_equal(rb, O.block_bounds(N, P))
+    np.testing.assert_array_equal(cells, O.cell_nnz(X, P, place))
+    for s in sorted({0, 1 % P, P - 1}):
+        for got, want in ((m.fm_get_stratum_csr(s), O.stratum_csr(X, P, s, place)),
+                          (m.fm_get_stratum_csc(s), O.stratum_csc(X, P, s, place))):
+            np.testing.assert_array_equal(got[0], want[0])
+            np.testing.assert_array_equal(got[1], want[1])
+            np.testing.assert_array_equal(got[2], want[2].astype(np.float32))
+    m.close()
+
+
+def test_block_placement_is_the_ring_on_the_gpu_and_a_scaled_workload_runs_placed():
+    """place[j] = column block of j must give bit for bit what fm_partition gives; then the text-like
+    workload at a tenth of its size with a random placement on P = 32 workers, stale and refreshed."""
+    import torch
+    from paper_2004_13940_amd.workloads import random_placement
+    B = _B()
+    wl = make_config(3, scale=0.1)
+    outs = []
+    for placed in (False, True):
+        m, p, X, dev, host = _run_full_epochs(B, wl, 0)
+        if placed:
+            m.fm_partition_placed(wl.P, O.block_placement(wl.D, wl.P))
+        else:
+            m.fm_partition(wl.P)
+        d_w0, d_w, d_V, d_y = dev
+        for stale in (1, 0):
+            p.stale_aux = stale
+            m.fm_stratified_epoch(p, d_y, d_w0, d_w, d_V)
+        torch.cuda.synchronize()
+        outs.append((d_w0.clone(), d_w.clone(), d_V.clone()))
+        m.close()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    place = random_placement(wl.D, wl.P, seed=5)
+    for stale in (True, False):
+        m, _ = _run_placed_epochs(B, wl, wl.P, place, 2, stale)
+        m.close()
+    m = B.Matrix(wl.N, wl.D, wl.rowptr, wl.col, wl.val)
+    m.fm_build_csc()
+    with pytest.raises(B.FMError) as e:
+        m.fm_partition_placed(4, np.full(wl.D, 4, np.int32))  # worker 4 of 4 does not exist
+    assert e.value.code == -4
+    m.close()
+
+
 # ------------------------------------------------------------ error paths ----
 
 def test_state_and_argument_errors_are_reported():
