@@ -219,6 +219,14 @@ def time_config(torch, B, wl, reps, oracle_rows):
     out["forward"] = entry(ms, b_fwd)
     ms, _ = T.run(grad, reps)
     out["gradient"] = entry(ms, b_grad)
+    if K % 4 == 0:  # the same forward and epoch with the V rows gathered from the half-precision copy (not the headline)
+        ph = B.make_params(wl.K, wl.loss, wl.lambda_w, wl.lambda_v, wl.eta, wl.loss_scale, wl.update_w0, half_gather=1)
+        fwd_h = lambda: m.fm_forward(ph, y, w0, w, V, yhat=yhat, a=a, G=G, q=q, r=r)
+        fwd_h()
+        ms, _ = T.run(fwd_h, reps)
+        out["forward_half_gather"] = entry(ms, None)
+        ms, _ = T.run(lambda: m.fm_sgd_epoch(ph, y, w0, w, V), reps, before=restore)
+        out["epoch_half_gather"] = entry(ms, None)
     del yhat, a, q, r, G, gw, gV
     torch.cuda.empty_cache()
     t0 = time.perf_counter()

@@ -63,6 +63,13 @@ typedef struct {
                                   the epoch reads the aggregates computed at its start (no refresh between
                                   strata; Section 4.2, staleness), and the next fm_stratified_begin
                                   recomputes them.  Overrides refresh_all_rows. */
+    int32_t half_gather;       /* 1 = the passes that gather rows of V (fm_forward, fm_evaluate, the forward of
+                                  fm_sgd_epoch and of every batch of fm_minibatch_epoch) read them from a
+                                  half-precision copy (IEEE binary16, round to nearest even) that the call
+                                  refreshes from V first: the score is that of the model with rounded factors,
+                                  sums in fp32; gradient and step use the fp32 V.  Halves the bytes of every
+                                  gathered row.  K % 4 == 0.  Beyond the paper (it fixes no precision); the
+                                  stratified calls and fm_forward_noalloc return FM_EINVAL with it. */
 } fm_params;
 
 /* ---- building the data structures (Section 3: X is read by rows for the score,

@@ -24,7 +24,8 @@ class fm_params(ctypes.Structure):
                 ("lambda_w", ctypes.c_float), ("lambda_v", ctypes.c_float),
                 ("eta", ctypes.c_float), ("loss_scale", ctypes.c_float),
                 ("update_w0", ctypes.c_int32), ("reg_full_per_cell", ctypes.c_int32),
-                ("refresh_all_rows", ctypes.c_int32), ("stale_aux", ctypes.c_int32)]
+                ("refresh_all_rows", ctypes.c_int32), ("stale_aux", ctypes.c_int32),
+                ("half_gather", ctypes.c_int32)]
 
 
 class FMError(RuntimeError):
@@ -92,9 +93,9 @@ def _dev(t, n, what):
 
 
 def make_params(K, loss, lambda_w, lambda_v, eta, loss_scale=1.0, update_w0=1, reg_full_per_cell=0,
-                refresh_all_rows=0, stale_aux=0) -> fm_params:
+                refresh_all_rows=0, stale_aux=0, half_gather=0) -> fm_params:
     return fm_params(int(K), int(loss), float(lambda_w), float(lambda_v), float(eta), float(loss_scale),
-                     int(update_w0), int(reg_full_per_cell), int(refresh_all_rows), int(stale_aux))
+                     int(update_w0), int(reg_full_per_cell), int(refresh_all_rows), int(stale_aux), int(half_gather))
 
 
 class Matrix:

@@ -269,6 +269,15 @@ static int check_params(fm_matrix* m, const fm_params* p)
     if (!fm_shape_for_K(p->K, &vec, &lanes))
         return fm_fail(m, FM_EINVAL, "K=%d unsupported (1..64, or a multiple of 4 up to 256)", p->K);
     if (p->loss != FM_LOSS_SQUARED && p->loss != FM_LOSS_LOGISTIC) return fm_fail(m, FM_EINVAL, "unknown loss %d", p->loss);
+    if (p->half_gather && p->K % 4 != 0) return fm_fail(m, FM_EINVAL, "half_gather needs K to be a multiple of 4");
+    return FM_OK;
+}
+
+// stratified calls keep fp32 gathers: their incremental refresh adds fp32 changes to aggregates that
+// would have been formed from rounded factors
+static int no_half(fm_matrix* m, const fm_params* p)
+{
+    if (p->half_gather) return fm_fail(m, FM_EINVAL, "half_gather applies to fm_forward, fm_evaluate, fm_sgd_epoch and fm_minibatch_epoch");
     return FM_OK;
 }
 
@@ -422,6 +431,26 @@ static void aux_outputs(fm_matrix* m, int32_t K, RowArgs& A, bool with_aq)
 
 // ---------------------------------------------------------------- forward ----
 
+// With half_gather: refresh the handle's half-precision copy of V (one streaming pass) and hand it to the row kernel.
+static int half_copy(fm_matrix* m, const fm_params* p, const float* V, const _Float16** out, hipStream_t st)
+{
+    *out = nullptr;
+    if (!p->half_gather) return FM_OK;
+    const int64_t n = m->D * (int64_t)p->K;
+    if (m->Vh == nullptr || m->VhK != p->K) {
+        if (m->Vh != nullptr) {
+            FM_HIP(m, hipDeviceSynchronize());
+            fm_dev_free(m, m->Vh);
+            m->Vh = nullptr;
+        }
+        FM_TRY(fm_dev_alloc(m, (void**)&m->Vh, (size_t)std::max<int64_t>(n, 1) * sizeof(_Float16)));
+        m->VhK = p->K;
+    }
+    FM_TRY(fm_to_half(m, V, m->Vh, n, st));
+    *out = m->Vh;
+    return FM_OK;
+}
+
 // mode 0: caller arrays (dense); 1: handle's aggregate rows, G and r; 2: handle's rows, G r a q
 static int run_forward(fm_matrix* m, const fm_params* p, const float* y, const float* w0, const float* w,
                        const float* V, float* yhat, float* a, float* G, float* q, float* r, int mode, bool want_sums,
@@ -453,6 +482,7 @@ static int run_forward(fm_matrix* m, const fm_params* p, const float* y, const f
     A.row_part = (want_sums && y != nullptr) ? m->row_part : nullptr;
     A.loss = p->loss;
     A.s = p->loss_scale;
+    FM_TRY(half_copy(m, p, V, &A.Vh, st));
     FM_TRY(fm_launch_rows(m, A, false, st));
     if (A.row_part != nullptr) FM_TRY(fm_reduce_pairs(m, m->row_part, fm_rows_grid(m->N, p->K), m->scal + 0, st));
     return FM_OK;
@@ -512,6 +542,7 @@ extern "C" int fm_evaluate(fm_matrix* m, const fm_params* p, const float* y, con
     A.row_part = m->row_part;
     A.loss = p->loss;
     A.s = 1.f;
+    FM_TRY(half_copy(m, p, V, &A.Vh, st));
     FM_TRY(fm_launch_rows(m, A, false, st));
     FM_TRY(fm_reduce_pairs(m, m->row_part, fm_rows_grid(m->N, p->K), m->scal + 0, st));
     FM_TRY(fm_reduce_eval(m, m->aux, y, m->N, 0, m->scal + 4, st));
@@ -642,6 +673,7 @@ extern "C" int fm_stratified_begin(fm_matrix* m, const fm_params* p, const float
 {
     if (m == nullptr) return FM_EINVAL;
     FM_TRY(check_params(m, p));
+    FM_TRY(no_half(m, p));
     if (m->P == 0) return fm_fail(m, FM_ESTATE, "stratified calls need fm_partition first");
     if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
         return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
@@ -735,6 +767,7 @@ extern "C" int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, c
 {
     if (m == nullptr) return FM_EINVAL;
     FM_TRY(check_params(m, p));
+    FM_TRY(no_half(m, p));
     if (m->P == 0) return fm_fail(m, FM_ESTATE, "stratified calls need fm_partition first");
     if (s < 0 || s >= m->P) return fm_fail(m, FM_EINVAL, "stratum %d outside [0,%d)", s, m->P);
     if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
@@ -840,6 +873,7 @@ extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float
 {
     if (m == nullptr) return FM_EINVAL;
     FM_TRY(check_params(m, p));
+    FM_TRY(no_half(m, p));
     if (m->P == 0) return fm_fail(m, FM_ESTATE, "stratified calls need fm_partition first");
     if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
         return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
@@ -927,6 +961,7 @@ extern "C" int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float*
             R.row_part = p->update_w0 ? m->row_part : nullptr;
             R.loss = p->loss;
             R.s = p->loss_scale;
+            FM_TRY(half_copy(m, p, V, &R.Vh, st));  // the factors as they stand
             FM_TRY(fm_launch_rows(m, R, false, st));
             if (R.row_part != nullptr)
                 FM_TRY(fm_reduce_pairs(m, m->row_part, fm_rows_grid(nb, p->K), m->scal + 0, st));

@@ -20,6 +20,24 @@ __device__ __forceinline__ void fm_load_vec(const float* __restrict__ p, float (
     }
 }
 
+// The same from a row stored as IEEE half precision (the internal copy of V that a pass with
+// fm_params.half_gather reads): half the bytes per gathered row, widened to fp32 on arrival.
+typedef _Float16 fm_h4 __attribute__((ext_vector_type(4)));
+typedef _Float16 fm_h2 __attribute__((ext_vector_type(2)));
+template <int VEC>
+__device__ __forceinline__ void fm_load_vec(const _Float16* __restrict__ p, float (&v)[VEC])
+{
+    if constexpr (VEC == 4) {
+        const fm_h4 t = *reinterpret_cast<const fm_h4*>(p);
+        v[0] = (float)t.x; v[1] = (float)t.y; v[2] = (float)t.z; v[3] = (float)t.w;
+    } else if constexpr (VEC == 2) {
+        const fm_h2 t = *reinterpret_cast<const fm_h2*>(p);
+        v[0] = (float)t.x; v[1] = (float)t.y;
+    } else {
+        v[0] = (float)*p;
+    }
+}
+
 // Same load with the non-temporal hint: the line is not kept in L2 ahead of lines that
 // were loaded normally.  Used on the column side for rows that will not be gathered again
 // soon, so that they do not push a panel's rows out of the 4 MB L2 of the XCD.
@@ -127,8 +145,8 @@ struct FmChunk {
 // S entry slots (slot s = entry s%L of lane-slot s/L): broadcast each entry's index and
 // multiplier inside the group, gather the rows with at most 16 loads in flight, then
 // accumulate.
-template <int VEC, int L, bool SQ, int S, class IX, class MU>
-__device__ __forceinline__ void fm_gather_slots(const IX& ix, const MU& mu, const float* __restrict__ src,
+template <int VEC, int L, bool SQ, int S, class IX, class MU, class SRC>
+__device__ __forceinline__ void fm_gather_slots(const IX& ix, const MU& mu, const SRC* __restrict__ src,
                                                 int64_t stride, int kb, float (&acc)[VEC], float& sq)
 {
     constexpr int B = S < 16 ? S : 16;
@@ -165,9 +183,9 @@ __device__ __forceinline__ void fm_gather_slots(const IX& ix, const MU& mu, cons
 // Full chunks of L*CH entries run without masking; the tail runs in L-entry slots whose
 // missing entries repeat the last entry with value 0.  `kb` must be a valid offset for
 // every lane (idle lanes pass 0 and discard acc).
-template <int VEC, int L, bool SQ, int CH = FmChunk<L>::CH, class Own>
+template <int VEC, int L, bool SQ, int CH = FmChunk<L>::CH, class Own, class SRC = float>
 __device__ __forceinline__ void fm_gather_accumulate(const int32_t* __restrict__ idx, const float* __restrict__ val,
-                                                     int64_t beg, int64_t end, const float* __restrict__ src,
+                                                     int64_t beg, int64_t end, const SRC* __restrict__ src,
                                                      int64_t stride, int sub, int kb, float (&acc)[VEC], float& sq,
                                                      Own&& own)
 {

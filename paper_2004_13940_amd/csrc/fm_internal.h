@@ -148,6 +148,8 @@ struct fm_matrix {
     // workspace, sized for wsK
     int32_t wsK = 0;
     float* aux = nullptr;   // aggregates, see fm_aux_layout
+    _Float16* Vh = nullptr; // [D*K] half-precision copy of V for passes with half_gather (allocated on first use)
+    int32_t VhK = 0;        // the K it was sized for
     float* dV = nullptr;    // [D*K] last step's change of V
     float2* dwn = nullptr;  // [D] (change of w_j, change of |v_j|^2)
     float* part = nullptr;      // [max items * part_stride(K)] partial sums of the items, see fm_part_stride
@@ -231,6 +233,7 @@ struct RowArgs {
     const float* w0;    // device scalar
     const float* w;     // forward: weights
     const float* V;     // forward: factors ; refresh: dV
+    const _Float16* Vh; // forward, nullable: gather the rows of V from this half-precision copy instead
     const float2* dwn;  // refresh: (dw_j, dn_j)
     const float* y;     // nullable
     float *yhat, *a, *G, *q, *r;  // forward: nullable outputs ; refresh: in/out aggregates
@@ -249,6 +252,7 @@ int64_t fm_rows_grid(int64_t N, int32_t K);
 // fm_forward_noalloc (fm_noalloc.hip); called when a handle is created
 int fm_noalloc_init_device(fm_matrix* m);
 int fm_pack_aux(fm_matrix* m, const float* r, const float* G, hipStream_t st);  // packed layout only
+int fm_to_half(fm_matrix* m, const float* x, _Float16* out, int64_t n, hipStream_t st);  // round to nearest even
 int fm_unpack_aux(fm_matrix* m, float* a, float* G, float* q, float* r, hipStream_t st);
 
 struct ColArgs {

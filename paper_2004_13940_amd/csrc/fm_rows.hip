@@ -11,7 +11,7 @@
 
 namespace {
 
-enum { MODE_FORWARD = 0, MODE_REFRESH = 1 };
+enum { MODE_FORWARD = 0, MODE_REFRESH = 1, MODE_FORWARD_HALF = 2 };  // the last: V rows from the half-precision copy
 
 // Loss value and multiplier for one example (cases after eq. updates_v; the loss
 // constants make the printed multiplier the exact derivative).  expf only ever sees
@@ -78,6 +78,13 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
                                                a_acc += w[c] * x;
                                                return x;
                                            });
+    } else if constexpr (MODE == MODE_FORWARD_HALF) {
+        const float* __restrict__ w = A.w;
+        fm_gather_accumulate<VEC, L, true>(A.col, A.val, beg, end, A.Vh, K, sub, kb, acc, q_acc,
+                                           [&](int c, float x) {
+                                               a_acc += w[c] * x;
+                                               return x;
+                                           });
     } else {
         // rows that have no entry in this stratum keep their aggregates untouched
         touched = valid && beg < end;  // uniform inside a group
@@ -103,11 +110,11 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
     if (!kact) {  // idle lanes of a group wider than K/VEC worked on a valid but foreign slice
 #pragma unroll
         for (int u = 0; u < VEC; ++u) acc[u] = 0.f;
-        if constexpr (MODE == MODE_FORWARD) q_acc = 0.f;
+        if constexpr (MODE != MODE_REFRESH) q_acc = 0.f;
     }
 
     float l_i = 0.f, r_i = 0.f;
-    if constexpr (MODE == MODE_FORWARD) {
+    if constexpr (MODE != MODE_REFRESH) {
         float pair = 0.f;
 #pragma unroll
         for (int z = 0; z < VEC; ++z) pair += acc[z] * acc[z];
@@ -202,10 +209,16 @@ int launch_rows_t(fm_matrix* m, const RowArgs& A, bool refresh, hipStream_t st)
     if (grid <= 0) return FM_OK;
     if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "row grid too large");
     ProfScope ps(m, st, refresh ? FMK_ROWS_REFRESH : FMK_ROWS_FORWARD);
-    if (refresh)
+    if (refresh) {
         hipLaunchKernelGGL((k_rows<VEC, L, MODE_REFRESH>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
-    else
+    } else if (A.Vh != nullptr) {
+        if constexpr (VEC == 4)
+            hipLaunchKernelGGL((k_rows<VEC, L, MODE_FORWARD_HALF>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
+        else
+            return fm_fail(m, FM_EINVAL, "half_gather needs K to be a multiple of 4");
+    } else {
         hipLaunchKernelGGL((k_rows<VEC, L, MODE_FORWARD>), dim3((unsigned)grid), dim3(FM_BLOCK), 0, st, A);
+    }
     FM_HIP(m, hipGetLastError());
     return FM_OK;
 }
@@ -266,6 +279,34 @@ __global__ void k_pack_aux(const FmAux x, int64_t N, int32_t K, const float* __r
     fm_store_vec<4>(x.G + i * x.gs + o, z);
 }
 }  // namespace
+
+namespace {
+__global__ void k_to_half(const float4* __restrict__ x, fm_h4* __restrict__ out, int64_t n4)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n4) return;
+    const float4 v = x[i];
+    fm_h4 h;
+    h.x = (_Float16)v.x;
+    h.y = (_Float16)v.y;
+    h.z = (_Float16)v.z;
+    h.w = (_Float16)v.w;
+    out[i] = h;
+}
+}  // namespace
+
+// n a multiple of 4; conversion rounds to nearest even (subnormal halves kept)
+int fm_to_half(fm_matrix* m, const float* x, _Float16* out, int64_t n, hipStream_t st)
+{
+    const int64_t n4 = n / 4;
+    if (n4 <= 0) return FM_OK;
+    const int64_t grid = (n4 + 255) / 256;
+    if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "conversion too large");
+    hipLaunchKernelGGL(k_to_half, dim3((unsigned)grid), dim3(256), 0, st, reinterpret_cast<const float4*>(x),
+                       reinterpret_cast<fm_h4*>(out), n4);
+    FM_HIP(m, hipGetLastError());
+    return FM_OK;
+}
 
 int fm_pack_aux(fm_matrix* m, const float* r, const float* G, hipStream_t st)
 {

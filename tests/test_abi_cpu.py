@@ -31,10 +31,10 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_params_struct_layout_matches_header():
     from paper_2004_13940_amd import binding
-    assert ctypes.sizeof(binding.fm_params) == 10 * 4
+    assert ctypes.sizeof(binding.fm_params) == 11 * 4
     assert [f[0] for f in binding.fm_params._fields_] == [
         "K", "loss", "lambda_w", "lambda_v", "eta", "loss_scale", "update_w0", "reg_full_per_cell",
-        "refresh_all_rows", "stale_aux"]
+        "refresh_all_rows", "stale_aux", "half_gather"]
 
 
 def _try_build(lib, N, D, rowptr, col, val):

@@ -183,6 +183,31 @@ def test_full_size_forward_and_full_gradient_epoch(full):
         assert abs(d_w0.item() - w0) <= REL_TOL * max(abs(w0), 1e-3)
 
 
+def test_full_size_epoch_with_half_precision_gathers(full):
+    """half_gather at the benchmarked shape: the forward on V rounded to binary16 on both sides, gradient and step on
+    the fp32 factors; the deviation of the scores from the unrounded model is printed for information."""
+    import torch
+    wl, m, X, B = full
+    p = _params(B, wl)
+    p.half_gather = 1
+    d_w0, d_w, d_V = dev_params(wl.w0, wl.w, wl.V)
+    d_y = to_dev(wl.y)
+    yhat = torch.empty(wl.N, device="cuda")
+    m.fm_forward(p, d_y, d_w0, d_w, d_V, yhat=yhat)
+    V16 = wl.V.astype(np.float16).astype(np.float64)
+    a, G, q, yh = O.forward(X, float(wl.w0), wl.w, V16)
+    assert_close(yhat.cpu().numpy(), yh, "yhat with rounded factors at full size")
+    _, _, _, yh_full = O.forward(X, float(wl.w0), wl.w, wl.V)
+    _say(f"scores deviate from the unrounded model by {np.abs(yh - yh_full).max() / np.abs(yh_full).max():.2e} of the largest")
+    del a, q, yh_full
+    l, r = O.loss_multiplier(wl.loss, wl.loss_scale, yh, wl.y)
+    gw0, gw, gV = O.gradient(X, r, G, wl.w, wl.V, wl.lambda_w, wl.lambda_v)
+    obj = m.fm_sgd_epoch(p, d_y, d_w0, d_w, d_V, want_objective=True)
+    assert abs(obj[0] - wl.loss_scale * l.sum()) <= REL_TOL * wl.loss_scale * l.sum()
+    assert_close(d_w.cpu().numpy(), wl.w - wl.eta * gw, "w after an epoch with half gathers")
+    assert_close(d_V.cpu().numpy().reshape(wl.D, wl.K), wl.V - wl.eta * gV, "V after an epoch with half gathers")
+
+
 def test_full_size_first_step_element_by_element(full):
     wl, m, X, B = full
     _check_first_epoch_elementwise(B, wl, m, X)

@@ -820,3 +820,92 @@ def test_replayed_stratified_epochs_stay_correct_between_other_work():
     assert_close(e_V.cpu().numpy().reshape(wl.D, wl.K), Vb, "V with new arrays")
     m.close()
     mo.close()
+
+
+# ------------------------------------- half-precision copy of V for the gathers ----
+
+def _round16(V):
+    """What the library's copy holds: the fp32 factors rounded to IEEE half precision (nearest even)."""
+    return np.asarray(V, np.float32).astype(np.float16).astype(np.float64)
+
+
+@pytest.mark.parametrize("K,loss", [(4, O.LOSS_SQUARED), (16, O.LOSS_LOGISTIC), (64, O.LOSS_LOGISTIC), (128, O.LOSS_SQUARED)])
+def test_half_gather_scores_the_model_with_rounded_factors(K, loss):
+    """half_gather: the forward gathers V rows from a half-precision copy.  Both sides take the rounding in the
+    same precision (binary16, nearest even), so the usual 1e-4 applies; the deviation from the unrounded model
+    is printed for information.  The gradient and the step keep the fp32 factors."""
+    import torch
+    B = _B()
+    N, D = 700, 90
+    rowptr, col, val, y, w0, w, V = _problem(1700 + K, N, D, K, 0.15, loss, dense_cols=(1,))
+    V = (V * (3 if K <= 16 else 0.5)).astype(np.float32)  # a spread of magnitudes, some below the smallest normal half
+    V[::7] *= np.float32(1e-4)
+    X = O.make_matrix(N, D, rowptr, col, val)
+    m = B.Matrix(N, D, rowptr, col, val)
+    m.fm_build_csc()
+    s = 1.0 / N
+    p = B.make_params(K, loss, 1e-2, 2e-2, 0.3, s, 1, half_gather=1)
+    d_w0, d_w, d_V = dev_params(w0, w, V)
+    d_y = to_dev(y)
+    out = {k: torch.empty(n, device="cuda") for k, n in (("yhat", N), ("a", N), ("G", N * K), ("q", N), ("r", N))}
+    got_loss = m.fm_forward(p, d_y, d_w0, d_w, d_V, want_loss=True, **out)
+    a, G, q, yh = O.forward(X, float(w0), w, _round16(V))
+    l, r = O.loss_multiplier(loss, s, yh, y)
+    for k, want in (("yhat", yh), ("a", a), ("G", G), ("q", q), ("r", r)):
+        assert_close(out[k].cpu().numpy().reshape(want.shape), want, f"{k} with rounded factors")
+    assert abs(got_loss - l.sum()) <= REL_TOL * l.sum()
+    _, _, _, yh_full = O.forward(X, float(w0), w, V)
+    _say(f"  K={K}: yhat deviates from the unrounded model by {np.abs(yh - yh_full).max() / np.abs(yh_full).max():.2e} "
+         f"of its largest entry")
+    ev = m.fm_evaluate(p, d_y, d_w0, d_w, d_V)
+    assert abs(ev["mean_loss"] - O.loss_multiplier(loss, 1.0, yh, y)[0].mean()) <= REL_TOL * abs(ev["mean_loss"]) + 1e-12
+    # full-gradient epochs: forward on the rounded copy, gradient and step on the fp32 factors
+    ow0, ow, oV = float(w0), w.astype(np.float64), V.astype(np.float64)
+    for ep in range(3):
+        obj = m.fm_sgd_epoch(p, d_y, d_w0, d_w, d_V, want_objective=True)
+        a, G, q, yh = O.forward(X, ow0, ow, _round16(oV))
+        l, r = O.loss_multiplier(loss, s, yh, y)
+        gw0, gw, gV = O.gradient(X, r, G, ow, oV, 1e-2, 2e-2)
+        assert abs(obj[0] - s * l.sum()) <= REL_TOL * s * l.sum()
+        ow0, ow, oV = ow0 - 0.3 * gw0, ow - 0.3 * gw, oV - 0.3 * gV
+        assert_close(d_w.cpu().numpy(), ow, f"w after epoch {ep} with half gathers")
+        assert_close(d_V.cpu().numpy().reshape(D, K), oV, f"V after epoch {ep} with half gathers")
+        assert abs(d_w0.item() - ow0) <= REL_TOL * max(abs(ow0), 1e-3)
+    # mini-batch epoch: every batch scores its rows with the factors as they stand, rounded
+    nb = 4
+    m.fm_partition_batches(nb)
+    m.fm_minibatch_epoch(p, d_y, d_w0, d_w, d_V)
+    rb = O.block_bounds(N, nb)
+    yd = y.astype(np.float64)
+    rr = np.zeros(N)
+    dw, dV, dn = np.zeros(D), np.zeros((D, K)), np.zeros(D)
+    ow, oV = ow.copy(), oV.copy()
+    for b in range(nb):
+        lo, hi = int(rb[b]), int(rb[b + 1])
+        a, G, q, _ = O.forward(X, ow0, ow, _round16(oV))
+        O.cell_update(X, yd, ow0, ow, oV, a, G, q, rr, (lo, hi), (0, D), loss=loss, s=s, eta=0.3, rho=(hi - lo) / N,
+                      lambda_w=1e-2, lambda_v=2e-2, dw=dw, dV=dV, dn=dn)
+        ow0 = ow0 - 0.3 * float(rr[lo:hi].sum())
+    assert_close(d_w.cpu().numpy(), ow, "w after a mini-batch epoch with half gathers")
+    assert_close(d_V.cpu().numpy().reshape(D, K), oV, "V after a mini-batch epoch with half gathers")
+    # where the mode does not apply
+    m.fm_partition(2)
+    with pytest.raises(B.FMError) as e:
+        m.fm_stratified_epoch(p, d_y, d_w0, d_w, d_V)
+    assert e.value.code == -1
+    with pytest.raises(B.FMError) as e:
+        m.fm_forward_noalloc(p, d_y, d_w0, d_w, d_V, yhat=out["yhat"])
+    assert e.value.code == -1
+    m.close()
+
+
+def test_half_gather_needs_a_latent_size_that_is_a_multiple_of_four():
+    B = _B()
+    rowptr, col, val, y, w0, w, V = _problem(9, 30, 12, 6, 0.3, O.LOSS_SQUARED)
+    m = B.Matrix(30, 12, rowptr, col, val)
+    p = B.make_params(6, O.LOSS_SQUARED, 0.0, 0.0, 0.1, half_gather=1)
+    d_w0, d_w, d_V = dev_params(w0, w, V)
+    with pytest.raises(B.FMError) as e:
+        m.fm_forward(p, to_dev(y), d_w0, d_w, d_V)
+    assert e.value.code == -1
+    m.close()
