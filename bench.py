@@ -230,9 +230,11 @@ def time_config(torch, B, wl, reps, oracle_rows):
     del yhat, a, q, r, G, gw, gV
     torch.cuda.empty_cache()
     t0 = time.perf_counter()
+    free0 = torch.cuda.mem_get_info()[0]
     m.fm_partition(wl.P)
     torch.cuda.synchronize()
     out["partition_s"] = time.perf_counter() - t0
+    out["partition_device_bytes"] = free0 - torch.cuda.mem_get_info()[0]  # the two re-ordered copies are 16 B per entry
     restore()
     m.fm_stratified_epoch(p, y, w0, w, V)
     ms, _ = T.run(lambda: m.fm_stratified_epoch(p, y, w0, w, V), reps, before=restore)

@@ -89,8 +89,10 @@ int fm_build_csc(fm_matrix* m, void* hip_stream);
  * block b of n items = [floor(b n/P), floor((b+1) n/P)) in 64-bit arithmetic, and the
  * ring schedule: stratum s holds the P disjoint cells (p, (p+s) mod P), stratum 0 on
  * the diagonal (Section 4.2, figure of the communication pattern).  Builds, for every
- * stratum, the CSR and the CSC of the matrix restricted to that stratum's cells.
- * Needs fm_build_csc.  1 <= P <= 4096. */
+ * stratum, the CSR and the CSC of the matrix restricted to that stratum's cells: two re-ordered copies of the
+ * entries plus, per stratum, the list of the rows and of the columns that have an entry there (memory
+ * proportional to the entries, not to P (N + D)).
+ * Needs fm_build_csc.  1 <= P <= 2^20; the table of entries per cell is kept for P <= 4096. */
 int fm_partition(fm_matrix* m, int32_t P, void* hip_stream);
 
 /* The same with every column handed from worker to worker on its own (Algorithm 1; Section 4.3: the
@@ -108,7 +110,7 @@ int fm_partition_placed(fm_matrix* m, int32_t P, const int32_t* place /*HOST D*/
 /* Copies for bit-exact checks (HOST outputs, sized by the caller). */
 int fm_get_csc(const fm_matrix* m, int64_t* colptr /*D+1*/, int32_t* row /*nnz*/, float* val /*nnz*/);
 int fm_get_block_index(const fm_matrix* m, int64_t* row_bounds /*P+1*/, int64_t* col_bounds /*P+1*/,
-                       int64_t* cell_nnz /*P*P, [p*P+q]*/);
+                       int64_t* cell_nnz /*P*P, [p*P+q]; FM_ESTATE for P > 4096*/);
 int fm_get_stratum_nnz(const fm_matrix* m, int32_t s, int64_t* nnz_out /*HOST 1*/);
 int fm_get_stratum_csr(const fm_matrix* m, int32_t s, int64_t* rowptr /*N+1, starts at 0*/,
                        int32_t* col, float* val);
@@ -117,7 +119,7 @@ int fm_get_stratum_csc(const fm_matrix* m, int32_t s, int64_t* colptr /*D+1, sta
 
 /* Row batches for fm_minibatch_epoch: B contiguous floor-split row blocks, and for every batch
  * the CSC of the matrix restricted to its rows (rows keep their global numbers, ascending per
- * column).  Needs fm_build_csc.  1 <= B <= 4096.  Independent of fm_partition. */
+ * column).  Needs fm_build_csc.  1 <= B <= 2^20 (B = N is one example per step).  Independent of fm_partition. */
 int fm_partition_batches(fm_matrix* m, int32_t B, void* hip_stream);
 int fm_get_batch_csc(const fm_matrix* m, int32_t b, int64_t* colptr /*HOST D+1, starts at 0*/,
                      int32_t* row /*HOST*/, float* val /*HOST*/);

@@ -196,7 +196,10 @@ extern "C" int fm_get_block_index(const fm_matrix* m, int64_t* row_bounds, int64
         return fm_fail(mm, FM_ESTATE, "the columns were placed one by one (fm_partition_placed): there are no column blocks");
     if (row_bounds) memcpy(row_bounds, m->h_rb.data(), (size_t)(m->P + 1) * sizeof(int64_t));
     if (col_bounds) memcpy(col_bounds, m->h_cb.data(), (size_t)(m->P + 1) * sizeof(int64_t));
-    if (cell_nnz) memcpy(cell_nnz, m->h_cell_nnz.data(), (size_t)m->P * m->P * sizeof(int64_t));
+    if (cell_nnz) {
+        if (m->h_cell_nnz.empty()) return fm_fail(mm, FM_ESTATE, "the cell table is only kept for P <= %d", FM_MAXP_CELLS);
+        memcpy(cell_nnz, m->h_cell_nnz.data(), (size_t)m->P * m->P * sizeof(int64_t));
+    }
     return FM_OK;
 }
 
@@ -210,6 +213,26 @@ extern "C" int fm_get_stratum_nnz(const fm_matrix* m, int32_t s, int64_t* nnz_ou
     return FM_OK;
 }
 
+// Pointer array over all nmaj rows (or columns) of one stratum or batch, expanded on the host from the list
+// of the rows (columns) that have entries there: list positions [l0, l1), entries from ent0 on.
+static int expand_ptr(fm_matrix* mm, const int32_t* nz_major, const int64_t* nz_beg, int64_t l0, int64_t l1,
+                      int64_t ent0, int64_t ent1, int64_t nmaj, int64_t* ptr)
+{
+    const size_t cnt = (size_t)(l1 - l0);
+    std::vector<int32_t> idx(cnt);
+    std::vector<int64_t> beg(cnt);
+    if (cnt > 0) {
+        FM_HIP(mm, hipMemcpy(idx.data(), nz_major + l0, cnt * sizeof(int32_t), hipMemcpyDeviceToHost));
+        FM_HIP(mm, hipMemcpy(beg.data(), nz_beg + l0, cnt * sizeof(int64_t), hipMemcpyDeviceToHost));
+    }
+    int64_t k = 0;
+    for (size_t t = 0; t < cnt; ++t) {
+        for (; k <= idx[t]; ++k) ptr[k] = beg[t] - ent0;  // rows up to and including this one start here
+    }
+    for (; k <= nmaj; ++k) ptr[k] = ent1 - ent0;
+    return FM_OK;
+}
+
 static int get_stratum(const fm_matrix* m, int32_t s, bool by_rows, int64_t* ptr, int32_t* ind, float* val)
 {
     if (m == nullptr) return FM_EINVAL;
@@ -220,9 +243,9 @@ static int get_stratum(const fm_matrix* m, int32_t s, bool by_rows, int64_t* ptr
     const int64_t nmaj = by_rows ? m->N : m->D;
     const int64_t off = m->h_strat_nnz_off[s], cnt = m->h_strat_nnz_off[s + 1] - off;
     if (ptr) {
-        FM_HIP(mm, hipMemcpy(ptr, (by_rows ? m->s_rowptr : m->s_colptr) + (int64_t)s * nmaj,
-                             (size_t)(nmaj + 1) * sizeof(int64_t), hipMemcpyDeviceToHost));
-        for (int64_t k = 0; k <= nmaj; ++k) ptr[k] -= off;
+        const std::vector<int64_t>& lo = by_rows ? m->h_touch_off : m->h_ncol_off;
+        FM_TRY(expand_ptr(mm, by_rows ? m->s_touched : m->s_ncol, by_rows ? m->s_touched_beg : m->s_ncol_beg, lo[s],
+                          lo[s + 1], off, off + cnt, nmaj, ptr));
     }
     if (ind && cnt)
         FM_HIP(mm, hipMemcpy(ind, (by_rows ? m->s_col : m->s_row) + off, (size_t)cnt * sizeof(int32_t),
@@ -250,11 +273,8 @@ extern "C" int fm_get_batch_csc(const fm_matrix* m, int32_t b, int64_t* colptr, 
     if (b < 0 || b >= m->B) return fm_fail(mm, FM_EINVAL, "batch %d outside [0,%d)", b, m->B);
     FM_HIP(mm, hipDeviceSynchronize());
     const int64_t off = m->h_batch_nnz_off[b], cnt = m->h_batch_nnz_off[b + 1] - off;
-    if (colptr) {
-        FM_HIP(mm, hipMemcpy(colptr, m->b_colptr + (int64_t)b * m->D, (size_t)(m->D + 1) * sizeof(int64_t),
-                             hipMemcpyDeviceToHost));
-        for (int64_t k = 0; k <= m->D; ++k) colptr[k] -= off;
-    }
+    if (colptr)
+        FM_TRY(expand_ptr(mm, m->b_ncol, m->b_ncol_beg, m->h_bcol_off[b], m->h_bcol_off[b + 1], off, off + cnt, m->D, colptr));
     if (row && cnt) FM_HIP(mm, hipMemcpy(row, m->b_row + off, (size_t)cnt * sizeof(int32_t), hipMemcpyDeviceToHost));
     if (val && cnt) FM_HIP(mm, hipMemcpy(val, m->b_cval + off, (size_t)cnt * sizeof(float), hipMemcpyDeviceToHost));
     return FM_OK;
@@ -413,6 +433,8 @@ static void fill_long(const fm_matrix* m, ColArgs& A, const LongIndex& li, int32
     A.vlong_items = m->tune.vlong;
     const int64_t s0 = strat ? li.h_short_off[s] : 0, s1 = strat ? li.h_short_off[s + 1] : li.nshort;
     A.short_col = li.short_col != nullptr ? li.short_col + s0 : nullptr;
+    A.short_beg = li.short_beg != nullptr ? li.short_beg + s0 : nullptr;
+    A.short_len = li.short_len != nullptr ? li.short_len + s0 : nullptr;
     A.nshort = s1 - s0;
 }
 
@@ -715,7 +737,8 @@ static int stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const fl
     // phase A: block gradients of the stratum's P cells and the step on every column block
     ColArgs A;
     strat_col_args(m, p, s, w, V, lazy, A);
-    A.ptr = m->s_colptr + (int64_t)s * m->D;
+    A.ptr = nullptr;  // no pointer array per stratum: short columns carry their extent, long ones their items
+    A.mark = lazy ? nullptr : m->col_mark;
     A.row = m->s_row;
     A.val = m->s_cval;
     const FmAux x = fm_aux_layout(m, p->K);
@@ -741,16 +764,12 @@ static int stratified_step(fm_matrix* m, const fm_params* p, int32_t s, const fl
         R.col = m->col;
         R.val = m->val;
     } else {
-        R.rowptr = m->s_rowptr + (int64_t)s * m->N;
         R.col = m->s_col;
         R.val = m->s_val;
-        if (m->s_touched != nullptr) {  // only the rows that have an entry in this stratum
-            R.rows = m->s_touched + m->h_touch_off[s];
-            R.rowptr = m->s_touched_beg + m->h_touch_off[s];
-            R.N = m->h_touch_off[s + 1] - m->h_touch_off[s];
-        } else {
-            R.N = 0;
-        }
+        // only the rows that have an entry in this stratum
+        R.rows = m->s_touched + m->h_touch_off[s];
+        R.rowptr = m->s_touched_beg + m->h_touch_off[s];
+        R.N = m->h_touch_off[s + 1] - m->h_touch_off[s];
     }
     R.w0 = w0;
     R.V = m->dV;
@@ -969,7 +988,8 @@ extern "C" int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float*
         // steps 4-5 over the batch's rows: gradient and step of every column that has entries there
         ColArgs A;
         col_args(b, A);
-        A.ptr = m->b_colptr + (int64_t)b * m->D;
+        A.ptr = nullptr;
+        A.mark = lazy ? nullptr : m->col_mark;
         A.row = m->b_row;
         A.val = m->b_cval;
         A.r = x.r;

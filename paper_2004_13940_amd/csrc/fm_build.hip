@@ -187,8 +187,7 @@ __global__ void k_ptr_from_sorted(const uint32_t* __restrict__ keys, int64_t n, 
 // being processed (rowptr for CSR, colptr for CSC) and `minor` its index array.
 __global__ void k_stratum_keys(const int64_t* __restrict__ major, int64_t nmajor, const int32_t* __restrict__ minor,
                                int64_t n, int64_t N, int64_t D, int32_t P, int by_rows,
-                               const int32_t* __restrict__ place, uint32_t* __restrict__ keys, uint32_t* __restrict__ idx,
-                               unsigned long long* __restrict__ cnt)
+                               const int32_t* __restrict__ place, uint32_t* __restrict__ keys, uint32_t* __restrict__ idx)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= n) return;
@@ -207,7 +206,56 @@ __global__ void k_stratum_keys(const int64_t* __restrict__ major, int64_t nmajor
     }
     keys[e] = (uint32_t)s;
     idx[e] = (uint32_t)e;
-    atomicAdd(&cnt[(int64_t)s * nmajor + mj], 1ull);
+}
+
+// major index (row of a CSR entry, column of a CSC entry) of every entry of a permuted order
+__global__ void k_major_of(const uint32_t* __restrict__ perm, const int64_t* __restrict__ major, int64_t nmajor,
+                           int32_t* __restrict__ out, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = (int32_t)owner_of(major, nmajor, perm[i]);
+}
+
+// flag[i] = 1 where entry i (in stratum order) opens a new (stratum, major) pair
+__global__ void k_head_flags(const uint32_t* __restrict__ keys, const int32_t* __restrict__ maj, int64_t n,
+                             int64_t* __restrict__ flag)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) flag[i] = (i == 0 || keys[i] != keys[i - 1] || maj[i] != maj[i - 1]) ? 1 : 0;
+}
+
+// pos = exclusive scan of the flags: the pairs in order, with their major index and first entry
+__global__ void k_compact_heads(const uint32_t* __restrict__ keys, const int32_t* __restrict__ maj,
+                                const int64_t* __restrict__ pos, int64_t n, int32_t* __restrict__ nz_major,
+                                int64_t* __restrict__ nz_beg)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    if (i == 0 || keys[i] != keys[i - 1] || maj[i] != maj[i - 1]) {
+        nz_major[pos[i]] = maj[i];
+        nz_beg[pos[i]] = i;
+    }
+}
+
+// out[t] = number of elements of the ascending array a[0..n) that are smaller than bound[t]
+__global__ void k_lower_bounds(const int64_t* __restrict__ a, int64_t n, const int64_t* __restrict__ bound, int64_t nb,
+                               int64_t* __restrict__ out)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= nb) return;
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (a[mid] < bound[t]) lo = mid + 1; else hi = mid;
+    }
+    out[t] = lo;
+}
+
+__global__ void k_gather_i64(const int64_t* __restrict__ src, const int64_t* __restrict__ idx, int64_t n,
+                             int64_t* __restrict__ out)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) out[t] = src[idx[t]];
 }
 
 __global__ void k_gather_pairs(const uint32_t* __restrict__ perm, const int32_t* __restrict__ ind,
@@ -222,24 +270,17 @@ __global__ void k_gather_pairs(const uint32_t* __restrict__ perm, const int32_t*
     }
 }
 
-// cell[p*P + c] += 1 for every stored entry in row block p whose column was placed at worker c
+// cell[p*P + c] += 1 for every stored entry in row block p whose column belongs to column block c (or was
+// placed at worker c); integer atomics: the totals do not depend on the order
 __global__ void k_cell_count(const int64_t* __restrict__ rowptr, int64_t N, const int32_t* __restrict__ col, int64_t n,
-                             const int32_t* __restrict__ place, int32_t P, unsigned long long* __restrict__ cell)
+                             int64_t D, const int32_t* __restrict__ place, int32_t P,
+                             unsigned long long* __restrict__ cell)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= n) return;
     const int32_t p = fm_block_of(owner_of(rowptr, N, e), N, P);
-    atomicAdd(&cell[(int64_t)p * P + place[col[e]]], 1ull);
-}
-
-// out[s*(P+1)+q] = s_colptr[s*D + cb[q]]
-__global__ void k_cell_starts(const int64_t* __restrict__ s_colptr, const int64_t* __restrict__ cb, int64_t D,
-                              int32_t P, int64_t* __restrict__ out)
-{
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= (int64_t)P * (P + 1)) return;
-    const int64_t s = t / (P + 1), q = t % (P + 1);
-    out[t] = s_colptr[s * D + cb[q]];
+    const int32_t c = place != nullptr ? place[col[e]] : fm_block_of(col[e], D, P);
+    atomicAdd(&cell[(int64_t)p * P + c], 1ull);
 }
 
 // ------------------------------------------------------------ long index ----
@@ -272,8 +313,8 @@ __global__ __launch_bounds__(LI_T) void k_long_count(const int64_t* __restrict__
     }
 }
 
-__global__ __launch_bounds__(LI_T) void k_long_fill(const int64_t* __restrict__ ptr, int64_t ncols, int64_t D,
-                                                    int seg, int with_items,
+__global__ __launch_bounds__(LI_T) void k_long_fill(const int64_t* __restrict__ ptr, int64_t ncols,
+                                                    const int32_t* __restrict__ ids, int seg, int with_items,
                                                     const int64_t* __restrict__ tile_long,
                                                     const int64_t* __restrict__ tile_items,
                                                     int32_t* __restrict__ long_col, int64_t* __restrict__ long_vcol,
@@ -300,7 +341,7 @@ __global__ __launch_bounds__(LI_T) void k_long_fill(const int64_t* __restrict__ 
         if (c >= ncols) break;
         const int64_t b = ptr[c], len = ptr[c + 1] - b;
         if (len <= seg) continue;
-        const int32_t j = (int32_t)(c % D);
+        const int32_t j = ids != nullptr ? ids[c] : (int32_t)c;
         long_col[lpos] = j;
         long_vcol[lpos] = c;
         ++lpos;
@@ -319,10 +360,11 @@ __global__ __launch_bounds__(LI_T) void k_long_fill(const int64_t* __restrict__ 
 // -------------------------------------------- short non-empty columns ----
 // Columns with 1..seg entries, in (virtual) column order: k_cols works through this list;
 // empty columns only feel the regulariser and are handled by an elementwise kernel.
-__global__ __launch_bounds__(LI_T) void k_short_list(const int64_t* __restrict__ ptr, int64_t ncols, int64_t D, int seg,
+__global__ __launch_bounds__(LI_T) void k_short_list(const int64_t* __restrict__ ptr, int64_t ncols,
+                                                     const int32_t* __restrict__ ids, int seg,
                                                      int pass, int64_t* __restrict__ tile_cnt,
                                                      int32_t* __restrict__ short_col, int64_t* __restrict__ short_vcol,
-                                                     int64_t* __restrict__ short_beg)
+                                                     int64_t* __restrict__ short_beg, int32_t* __restrict__ short_len)
 {
     __shared__ int64_t sh[2][SCAN_T];
     const int64_t base = (int64_t)blockIdx.x * LI_TILE + (int64_t)threadIdx.x * LI_E;
@@ -346,21 +388,22 @@ __global__ __launch_bounds__(LI_T) void k_short_list(const int64_t* __restrict__
         if (c >= ncols) break;
         const int64_t len = ptr[c + 1] - ptr[c];
         if (len > 0 && len <= seg) {
-            short_col[pos] = (int32_t)(c % D);
+            short_col[pos] = ids != nullptr ? ids[c] : (int32_t)c;
             short_vcol[pos] = c;
             if (short_beg != nullptr) short_beg[pos] = ptr[c];
+            if (short_len != nullptr) short_len[pos] = (int32_t)len;
             ++pos;
         }
     }
 }
 
-// off[s] = number of list entries with virtual column < s*D, s = 0..nstrata
-__global__ void k_stratum_offsets(const int64_t* __restrict__ vcol, int64_t n, int64_t D, int32_t nstrata,
-                                  int64_t* __restrict__ off)
+// off[s] = number of list entries whose position in the column list is < bounds[s], s = 0..nstrata
+__global__ void k_stratum_offsets(const int64_t* __restrict__ vcol, int64_t n, const int64_t* __restrict__ bounds,
+                                  int32_t nstrata, int64_t* __restrict__ off)
 {
     const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (s > nstrata) return;
-    const int64_t bound = s * D;
+    const int64_t bound = bounds[s];
     int64_t lo = 0, hi = n;
     while (lo < hi) {
         const int64_t mid = (lo + hi) >> 1;
@@ -569,63 +612,59 @@ int fm_sort_by_key_u32(fm_matrix* m, uint32_t* keys, uint32_t* idx, uint32_t* ke
 }
 
 
-// List of the non-empty columns (or rows) with at most `seg` entries, per stratum when
-// nstrata > 1: h_off[s] is where stratum s starts in the list.
-static int build_nonempty_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
-                               int seg, int32_t** list_out, int64_t* count_out, std::vector<int64_t>* h_off,
-                               hipStream_t st, int64_t** beg_out = nullptr)
+// List of the non-empty columns with at most `seg` entries.  ptr[c], ptr[c+1] bound the entries of list
+// position c, ids[c] is its column (nullptr: c itself); per stratum when nstrata > 1: h_bounds[s] is the
+// first position of stratum s and h_short_off[s] where it starts in the short list.  with_extent: also
+// the first entry and the length of every listed column (needed when ptr is not indexed by column).
+static int build_short_list(fm_matrix* m, const int64_t* ptr, const int32_t* ids, int64_t ncols_total,
+                            const std::vector<int64_t>& h_bounds, int32_t nstrata, int seg, bool with_extent,
+                            LongIndex* out, hipStream_t st)
 {
-    *count_out = 0;
-    h_off->assign(nstrata + 1, 0);
+    out->nshort = 0;
+    out->h_short_off.assign(nstrata + 1, 0);
     if (ncols_total <= 0) return FM_OK;
     const int64_t ntiles = (ncols_total + LI_TILE - 1) / LI_TILE;
     int64_t* tc = nullptr;
     FM_TRY(fm_dev_alloc(m, (void**)&tc, (size_t)(ntiles + 1) * sizeof(int64_t)));
     FM_HIP(m, hipMemsetAsync(tc, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
-    hipLaunchKernelGGL(k_short_list, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, D, seg, 0, tc,
-                       (int32_t*)nullptr, (int64_t*)nullptr, (int64_t*)nullptr);
+    hipLaunchKernelGGL(k_short_list, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, ids, seg, 0, tc,
+                       (int32_t*)nullptr, (int64_t*)nullptr, (int64_t*)nullptr, (int32_t*)nullptr);
     FM_HIP(m, hipGetLastError());
     FM_TRY(fm_scan_exclusive_i64(m, tc, ntiles + 1, st));
     int64_t n = 0;
     FM_HIP(m, hipMemcpyAsync(&n, tc + ntiles, sizeof(int64_t), hipMemcpyDeviceToHost, st));
     FM_HIP(m, hipStreamSynchronize(st));
     if (n > 0) {
-        int64_t *vcol = nullptr, *d_off = nullptr;
-        FM_TRY(fm_dev_alloc(m, (void**)list_out, (size_t)n * sizeof(int32_t)));
+        int64_t *vcol = nullptr, *d_off = nullptr, *d_bounds = nullptr;
+        FM_TRY(fm_dev_alloc(m, (void**)&out->short_col, (size_t)n * sizeof(int32_t)));
+        if (with_extent) {
+            FM_TRY(fm_dev_alloc(m, (void**)&out->short_beg, (size_t)n * sizeof(int64_t)));
+            FM_TRY(fm_dev_alloc(m, (void**)&out->short_len, (size_t)n * sizeof(int32_t)));
+        }
         FM_TRY(fm_dev_alloc(m, (void**)&vcol, (size_t)n * sizeof(int64_t)));
         FM_TRY(fm_dev_alloc(m, (void**)&d_off, (size_t)(nstrata + 1) * sizeof(int64_t)));
-        int64_t* beg = nullptr;
-        if (beg_out != nullptr) {  // start of every listed column; one more element: the end of all entries
-            FM_TRY(fm_dev_alloc(m, (void**)beg_out, (size_t)(n + 1) * sizeof(int64_t)));
-            beg = *beg_out;
-            FM_HIP(m, hipMemcpyAsync(beg + n, ptr + ncols_total, sizeof(int64_t), hipMemcpyDeviceToDevice, st));
-        }
-        hipLaunchKernelGGL(k_short_list, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, D, seg, 1, tc,
-                           *list_out, vcol, beg);
+        FM_TRY(fm_dev_alloc(m, (void**)&d_bounds, (size_t)(nstrata + 1) * sizeof(int64_t)));
+        FM_HIP(m, hipMemcpyAsync(d_bounds, h_bounds.data(), (size_t)(nstrata + 1) * sizeof(int64_t), hipMemcpyHostToDevice, st));
+        hipLaunchKernelGGL(k_short_list, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, ids, seg, 1, tc,
+                           out->short_col, vcol, out->short_beg, out->short_len);
         FM_HIP(m, hipGetLastError());
         hipLaunchKernelGGL(k_stratum_offsets, dim3(blocks_for(nstrata + 1, 256)), dim3(256), 0, st, (const int64_t*)vcol,
-                           n, D, nstrata, d_off);
+                           n, (const int64_t*)d_bounds, nstrata, d_off);
         FM_HIP(m, hipGetLastError());
-        FM_HIP(m, hipMemcpyAsync(h_off->data(), d_off, (size_t)(nstrata + 1) * sizeof(int64_t),
+        FM_HIP(m, hipMemcpyAsync(out->h_short_off.data(), d_off, (size_t)(nstrata + 1) * sizeof(int64_t),
                                  hipMemcpyDeviceToHost, st));
         FM_HIP(m, hipStreamSynchronize(st));
         fm_dev_free(m, vcol);
         fm_dev_free(m, d_off);
+        fm_dev_free(m, d_bounds);
     }
-    *count_out = n;
+    out->nshort = n;
     fm_dev_free(m, tc);
     return FM_OK;
 }
 
-static int build_short_list(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata, int seg,
-                            LongIndex* out, hipStream_t st)
-{
-    return build_nonempty_list(m, ptr, ncols_total, D, nstrata, seg, &out->short_col, &out->nshort,
-                               &out->h_short_off, st);
-}
-
-int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
-                        LongIndex* out, hipStream_t st)
+int fm_build_long_index(fm_matrix* m, const int64_t* ptr, const int32_t* ids, int64_t ncols_total,
+                        const std::vector<int64_t>& h_bounds, int32_t nstrata, LongIndex* out, hipStream_t st)
 {
     out->nshort = 0;
     out->h_short_off.assign(nstrata + 1, 0);
@@ -639,7 +678,7 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
     FM_TRY(fm_dev_alloc(m, (void**)&ti, (size_t)(ntiles + 1) * sizeof(int64_t)));
     // Item length.  The launches of one stratum are small: when full-length items would leave a
     // stratum with too few of them to fill the chip, they are halved (more groups to spread over,
-    // at the price of more partial sums); a fixed FM_SEG_STRAT or fm_set_tuning overrides this.
+    // at the price of more partial sums); fm_set_tuning overrides this.
     int seg = m->tune.seg_strat;
     if (seg <= 0) {
         seg = m->tune.seg;
@@ -653,7 +692,7 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
         FM_HIP(m, hipStreamSynchronize(st));
         if (n_full / nstrata < 12288 && seg > 128) seg = 128;
     }
-    FM_TRY(build_short_list(m, ptr, ncols_total, D, nstrata, seg, out, st));
+    FM_TRY(build_short_list(m, ptr, ids, ncols_total, h_bounds, nstrata, seg, true, out, st));
     FM_HIP(m, hipMemsetAsync(tl, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
     FM_HIP(m, hipMemsetAsync(ti, 0, (size_t)(ntiles + 1) * sizeof(int64_t), st));
     hipLaunchKernelGGL(k_long_count, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, seg, tl, ti);
@@ -674,7 +713,7 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
         FM_TRY(fm_dev_alloc(m, (void**)&out->item_beg, (size_t)nitems * sizeof(int64_t)));
         FM_TRY(fm_dev_alloc(m, (void**)&out->item_len, (size_t)nitems * sizeof(int32_t)));
         FM_TRY(fm_dev_alloc(m, (void**)&vcol, (size_t)nlong * sizeof(int64_t)));
-        hipLaunchKernelGGL(k_long_fill, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, D, seg, 1,
+        hipLaunchKernelGGL(k_long_fill, dim3((unsigned)ntiles), dim3(LI_T), 0, st, ptr, ncols_total, ids, seg, 1,
                            (const int64_t*)tl, (const int64_t*)ti, out->long_col, vcol, out->long_first,
                            out->item_col, out->item_beg, out->item_len);
         FM_HIP(m, hipGetLastError());
@@ -687,7 +726,7 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
         // per-stratum ranges of the concatenated lists
         int64_t k = 0;
         for (int32_t s = 0; s <= nstrata; ++s) {
-            while (k < nlong && h_vcol[(size_t)k] < (int64_t)s * D) ++k;
+            while (k < nlong && h_vcol[(size_t)k] < h_bounds[(size_t)s]) ++k;
             out->h_long_off[s] = k;
             out->h_item_off[s] = h_first[(size_t)k];
         }
@@ -698,13 +737,11 @@ int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, i
     return FM_OK;
 }
 
-
-
 // Frees the device arrays of an index and resets it.
 static void free_long_index(fm_matrix* m, LongIndex* li)
 {
     for (void* p : {(void*)li->long_col, (void*)li->long_first, (void*)li->item_col, (void*)li->item_beg,
-                    (void*)li->item_len, (void*)li->short_col, (void*)li->order, (void*)li->ord_beg,
+                    (void*)li->item_len, (void*)li->short_col, (void*)li->short_beg, (void*)li->short_len, (void*)li->order, (void*)li->ord_beg,
                     (void*)li->ord_len, (void*)li->tile_ptr, (void*)li->vlong})
         if (p != nullptr) fm_dev_free(m, p);
     *li = LongIndex();
@@ -741,7 +778,7 @@ int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st)
     m->lfull_shape[0] = T.tile;
     m->lfull_shape[1] = T.tile_min;
     m->lfull_shape[2] = T.tile_seg;
-    FM_TRY(build_short_list(m, m->colptr, m->D, m->D, 1, m->tune.seg, out, st));
+    FM_TRY(build_short_list(m, m->colptr, nullptr, m->D, {0, m->D}, 1, m->tune.seg, false, out, st));
     out->nlong = out->nitems = 0;
     out->h_long_off.assign(2, 0);
     out->h_item_off.assign(2, 0);
@@ -769,7 +806,8 @@ int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st)
     FM_TRY(fm_dev_alloc(m, (void**)&out->long_col, (size_t)nlong * sizeof(int32_t)));
     FM_TRY(fm_dev_alloc(m, (void**)&out->long_first, (size_t)(nlong + 1) * sizeof(int64_t)));
     FM_TRY(fm_dev_alloc(m, (void**)&vcol, (size_t)nlong * sizeof(int64_t)));
-    hipLaunchKernelGGL(k_long_fill, dim3((unsigned)ntiles), dim3(LI_T), 0, st, (const int64_t*)m->colptr, D, D, T.seg, 0,
+    hipLaunchKernelGGL(k_long_fill, dim3((unsigned)ntiles), dim3(LI_T), 0, st, (const int64_t*)m->colptr, D,
+                       (const int32_t*)nullptr, T.seg, 0,
                        (const int64_t*)tl, (const int64_t*)ti, out->long_col, vcol, (int64_t*)nullptr,
                        (int32_t*)nullptr, (int64_t*)nullptr, (int32_t*)nullptr);
     FM_HIP(m, hipGetLastError());
@@ -917,47 +955,88 @@ extern "C" int fm_build_csc(fm_matrix* m, void* hip_stream)
     return FM_OK;
 }
 
-// One orientation of the per-stratum matrices.
+static int partition_impl(fm_matrix* m, int32_t P, const int32_t* place, hipStream_t st);
+
+// One orientation of the per-stratum matrices: the entries in (stratum, major, minor) order, the list
+// of the (stratum, major) pairs that hold an entry with the offset of their first one, and where every
+// stratum starts in the entries (h_ent_off) and in that list (h_list_off).
 // (batches: the column orientation keyed by row block alone, P = number of batches)
-static int build_strata_side(fm_matrix* m, bool by_rows, hipStream_t st, int64_t** sptr_out, int32_t** sind_out,
-                             float** sval_out, int32_t P, bool batches = false)
+struct StrataSide {
+    int32_t* ind = nullptr;
+    float* val = nullptr;
+    int32_t* nz_major = nullptr;
+    int64_t* nz_beg = nullptr;  // [count + 1]
+    int64_t count = 0;
+    std::vector<int64_t> h_ent_off, h_list_off;  // [P + 1]
+};
+
+static int build_strata_side(fm_matrix* m, bool by_rows, hipStream_t st, StrataSide* out, int32_t P, bool batches = false)
 {
     const int64_t n = m->nnz;
     const int64_t nmajor = by_rows ? m->N : m->D;
     const int64_t* major = by_rows ? m->rowptr : m->colptr;
     const int32_t* minor = by_rows ? m->col : m->crow;
     const float* val = by_rows ? m->val : m->cval;
-    const size_t np = (size_t)P * (size_t)nmajor + 1;
-    FM_TRY(fm_dev_alloc(m, (void**)sptr_out, np * sizeof(int64_t)));
-    FM_TRY(fm_dev_alloc(m, (void**)sind_out, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
-    FM_TRY(fm_dev_alloc(m, (void**)sval_out, (size_t)(n > 0 ? n : 1) * sizeof(float)));
-    FM_HIP(m, hipMemsetAsync(*sptr_out, 0, np * sizeof(int64_t), st));
-    if (n == 0) return FM_OK;
+    out->h_ent_off.assign(P + 1, 0);
+    out->h_list_off.assign(P + 1, 0);
+    FM_TRY(fm_dev_alloc(m, (void**)&out->ind, (size_t)(n > 0 ? n : 1) * sizeof(int32_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&out->val, (size_t)(n > 0 ? n : 1) * sizeof(float)));
+    if (n == 0) {
+        FM_TRY(fm_dev_alloc(m, (void**)&out->nz_major, sizeof(int32_t)));
+        FM_TRY(fm_dev_alloc(m, (void**)&out->nz_beg, sizeof(int64_t)));
+        FM_HIP(m, hipMemsetAsync(out->nz_beg, 0, sizeof(int64_t), st));
+        return FM_OK;
+    }
     uint32_t *k0 = nullptr, *i0 = nullptr, *k1 = nullptr, *i1 = nullptr;
     FM_TRY(fm_dev_alloc(m, (void**)&k0, (size_t)n * 4));
     FM_TRY(fm_dev_alloc(m, (void**)&i0, (size_t)n * 4));
     FM_TRY(fm_dev_alloc(m, (void**)&k1, (size_t)n * 4));
     FM_TRY(fm_dev_alloc(m, (void**)&i1, (size_t)n * 4));
     hipLaunchKernelGGL(k_stratum_keys, dim3(blocks_for(n, 256)), dim3(256), 0, st, major, nmajor, minor, n, m->N,
-                       m->D, P, batches ? 2 : (by_rows ? 1 : 0), batches ? nullptr : (const int32_t*)m->d_place, k0, i0,
-                       (unsigned long long*)*sptr_out);
+                       m->D, P, batches ? 2 : (by_rows ? 1 : 0), batches ? nullptr : (const int32_t*)m->d_place, k0, i0);
     FM_HIP(m, hipGetLastError());
-    FM_TRY(fm_scan_exclusive_i64(m, *sptr_out, (int64_t)np, st));
     bool alt = false;
     FM_TRY(fm_sort_by_key_u32(m, k0, i0, k1, i1, n, bits_for(P - 1), st, &alt));
+    const uint32_t* keys = alt ? k1 : k0;
     const uint32_t* perm = alt ? i1 : i0;
-    hipLaunchKernelGGL(k_gather_pairs, dim3(blocks_for(n, 256)), dim3(256), 0, st, perm, minor, val, *sind_out,
-                       *sval_out, n);
+    hipLaunchKernelGGL(k_gather_pairs, dim3(blocks_for(n, 256)), dim3(256), 0, st, perm, minor, val, out->ind, out->val, n);
     FM_HIP(m, hipGetLastError());
+    // the stable sort keeps the entries of a stratum in the order of the source (by major index): the
+    // (stratum, major) pairs are runs, found by comparing neighbours
+    int32_t* maj = reinterpret_cast<int32_t*>(alt ? k0 : k1);  // the buffer the sort no longer needs
+    hipLaunchKernelGGL(k_major_of, dim3(blocks_for(n, 256)), dim3(256), 0, st, perm, major, nmajor, maj, n);
+    FM_HIP(m, hipGetLastError());
+    int64_t* pos = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&pos, (size_t)(n + 1) * sizeof(int64_t)));
+    hipLaunchKernelGGL(k_head_flags, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, (const int32_t*)maj, n, pos);
+    FM_HIP(m, hipGetLastError());
+    FM_HIP(m, hipMemsetAsync(pos + n, 0, sizeof(int64_t), st));
+    FM_TRY(fm_scan_exclusive_i64(m, pos, n + 1, st));
+    int64_t count = 0;
+    FM_HIP(m, hipMemcpyAsync(&count, pos + n, sizeof(int64_t), hipMemcpyDeviceToHost, st));
     FM_HIP(m, hipStreamSynchronize(st));
-    fm_dev_free(m, k0);
-    fm_dev_free(m, i0);
-    fm_dev_free(m, k1);
-    fm_dev_free(m, i1);
+    out->count = count;
+    FM_TRY(fm_dev_alloc(m, (void**)&out->nz_major, (size_t)count * sizeof(int32_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&out->nz_beg, (size_t)(count + 1) * sizeof(int64_t)));
+    hipLaunchKernelGGL(k_compact_heads, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, (const int32_t*)maj,
+                       (const int64_t*)pos, n, out->nz_major, out->nz_beg);
+    FM_HIP(m, hipGetLastError());
+    FM_HIP(m, hipMemcpyAsync(out->nz_beg + count, &n, sizeof(int64_t), hipMemcpyHostToDevice, st));
+    // where every stratum starts: in the entries (keys smaller than s), then in the list of pairs
+    int64_t *d_ent = nullptr, *d_list = nullptr;
+    FM_TRY(fm_dev_alloc(m, (void**)&d_ent, (size_t)(P + 1) * sizeof(int64_t)));
+    FM_TRY(fm_dev_alloc(m, (void**)&d_list, (size_t)(P + 1) * sizeof(int64_t)));
+    hipLaunchKernelGGL(k_ptr_from_sorted, dim3(blocks_for(P + 1, 256)), dim3(256), 0, st, keys, n, (int64_t)P, d_ent);
+    FM_HIP(m, hipGetLastError());
+    hipLaunchKernelGGL(k_lower_bounds, dim3(blocks_for(P + 1, 256)), dim3(256), 0, st, (const int64_t*)out->nz_beg, count,
+                       (const int64_t*)d_ent, (int64_t)(P + 1), d_list);
+    FM_HIP(m, hipGetLastError());
+    FM_HIP(m, hipMemcpyAsync(out->h_ent_off.data(), d_ent, (size_t)(P + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    FM_HIP(m, hipMemcpyAsync(out->h_list_off.data(), d_list, (size_t)(P + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+    FM_HIP(m, hipStreamSynchronize(st));
+    for (void* q : {(void*)k0, (void*)i0, (void*)k1, (void*)i1, (void*)pos, (void*)d_ent, (void*)d_list}) fm_dev_free(m, q);
     return FM_OK;
 }
-
-static int partition_impl(fm_matrix* m, int32_t P, const int32_t* place, hipStream_t st);
 
 extern "C" int fm_partition(fm_matrix* m, int32_t P, void* hip_stream)
 {
@@ -988,8 +1067,6 @@ static int partition_impl(fm_matrix* m, int32_t P, const int32_t* place, hipStre
         m->h_rb[b] = (int64_t)(((__int128)b * (__int128)m->N) / (__int128)P);
         m->h_cb[b] = (int64_t)(((__int128)b * (__int128)m->D) / (__int128)P);
     }
-    int64_t* d_cb = nullptr;
-    FM_TRY(fm_dev_alloc(m, (void**)&d_cb, (size_t)(P + 1) * sizeof(int64_t)));
     std::vector<float> h_rho((size_t)P);
     for (int32_t b = 0; b < P; ++b) h_rho[b] = (float)((double)(m->h_rb[b + 1] - m->h_rb[b]) / (double)m->N);
     FM_TRY(fm_dev_alloc(m, (void**)&m->d_rho, (size_t)P * sizeof(float)));
@@ -997,58 +1074,49 @@ static int partition_impl(fm_matrix* m, int32_t P, const int32_t* place, hipStre
     FM_TRY(fm_dev_alloc(m, (void**)&m->d_rb, (size_t)(P + 1) * sizeof(int64_t)));
     FM_HIP(m, hipMemcpy(m->d_rb, m->h_rb.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
     FM_TRY(fm_ensure_lazy(m));
-    std::vector<int64_t> h_cbk = m->h_cb;  // column bounds at which the cell table is read off the per-stratum CSC
     if (place != nullptr) {
         FM_TRY(fm_dev_alloc(m, (void**)&m->d_place, (size_t)m->D * sizeof(int32_t)));
         FM_HIP(m, hipMemcpy(m->d_place, place, (size_t)m->D * sizeof(int32_t), hipMemcpyHostToDevice));
-        for (int32_t b = 1; b <= P; ++b) h_cbk[b] = m->D;  // only the start of every stratum is read this way
     }
-    FM_HIP(m, hipMemcpy(d_cb, h_cbk.data(), (size_t)(P + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
+    FM_TRY(fm_dev_alloc(m, (void**)&m->col_mark, (size_t)m->D * sizeof(int32_t)));
+    FM_HIP(m, hipMemsetAsync(m->col_mark, 0, (size_t)m->D * sizeof(int32_t), st));
 
-    FM_TRY(build_strata_side(m, true, st, &m->s_rowptr, &m->s_col, &m->s_val, P));
-    FM_TRY(build_strata_side(m, false, st, &m->s_colptr, &m->s_row, &m->s_cval, P));
+    StrataSide rows, cols;
+    FM_TRY(build_strata_side(m, true, st, &rows, P));
+    FM_TRY(build_strata_side(m, false, st, &cols, P));
+    m->s_col = rows.ind;
+    m->s_val = rows.val;
+    // the rows that have an entry in stratum s: its refresh visits only these (a row's entries end
+    // where those of the next listed row begin)
+    m->s_touched = rows.nz_major;
+    m->s_touched_beg = rows.nz_beg;
+    m->ntouched = rows.count;
+    m->h_touch_off = rows.h_list_off;
+    m->s_row = cols.ind;
+    m->s_cval = cols.val;
+    m->s_ncol = cols.nz_major;
+    m->s_ncol_beg = cols.nz_beg;
+    m->nncol = cols.count;
+    m->h_ncol_off = cols.h_list_off;
+    m->h_strat_nnz_off = cols.h_ent_off;
 
-    // cell table: in stratum s column block q only holds entries of row block (q-s) mod P
-    const int64_t nt = (int64_t)P * (P + 1);
-    int64_t* d_starts = nullptr;
-    FM_TRY(fm_dev_alloc(m, (void**)&d_starts, (size_t)nt * sizeof(int64_t)));
-    hipLaunchKernelGGL(k_cell_starts, dim3(blocks_for(nt, 256)), dim3(256), 0, st, (const int64_t*)m->s_colptr,
-                       (const int64_t*)d_cb, m->D, P, d_starts);
-    FM_HIP(m, hipGetLastError());
-    std::vector<int64_t> h_starts((size_t)nt);
-    FM_HIP(m, hipMemcpyAsync(h_starts.data(), d_starts, (size_t)nt * sizeof(int64_t), hipMemcpyDeviceToHost, st));
-    FM_HIP(m, hipStreamSynchronize(st));
-    m->h_cell_nnz.assign((size_t)P * P, 0);
-    m->h_strat_nnz_off.assign(P + 1, 0);
-    for (int32_t s = 0; s < P; ++s) {
-        m->h_strat_nnz_off[s] = h_starts[(size_t)s * (P + 1)];
-        for (int32_t q = 0; q < P; ++q) {
-            const int32_t p = ((q - s) % P + P) % P;
-            m->h_cell_nnz[(size_t)p * P + q] = h_starts[(size_t)s * (P + 1) + q + 1] - h_starts[(size_t)s * (P + 1) + q];
-        }
-    }
-    m->h_strat_nnz_off[P] = m->nnz;
-    if (place != nullptr) {  // cells (row block, worker the column started at): counted entry by entry
+    // cell table (row block, column block or worker the column started at), counted entry by entry
+    m->h_cell_nnz.clear();
+    if (P <= FM_MAXP_CELLS) {
+        m->h_cell_nnz.assign((size_t)P * P, 0);
         unsigned long long* d_cell = nullptr;
         FM_TRY(fm_dev_alloc(m, (void**)&d_cell, (size_t)P * P * sizeof(unsigned long long)));
         FM_HIP(m, hipMemsetAsync(d_cell, 0, (size_t)P * P * sizeof(unsigned long long), st));
         if (m->nnz > 0) {
             hipLaunchKernelGGL(k_cell_count, dim3(blocks_for(m->nnz, 256)), dim3(256), 0, st, (const int64_t*)m->rowptr,
-                               m->N, (const int32_t*)m->col, m->nnz, (const int32_t*)m->d_place, P, d_cell);
+                               m->N, (const int32_t*)m->col, m->nnz, m->D, (const int32_t*)m->d_place, P, d_cell);
             FM_HIP(m, hipGetLastError());
         }
         FM_HIP(m, hipMemcpyAsync(m->h_cell_nnz.data(), d_cell, (size_t)P * P * sizeof(int64_t), hipMemcpyDeviceToHost, st));
         FM_HIP(m, hipStreamSynchronize(st));
         fm_dev_free(m, d_cell);
     }
-    fm_dev_free(m, d_starts);
-    fm_dev_free(m, d_cb);
-    FM_TRY(fm_build_long_index(m, m->s_colptr, (int64_t)P * m->D, m->D, P, &m->lstrat, st));
-    // rows that have an entry in stratum s: the refresh of that stratum visits only these
-    // (every entry of the per-stratum matrices belongs to a listed row, so a row's entries end where
-    // those of the next listed row begin)
-    FM_TRY(build_nonempty_list(m, m->s_rowptr, (int64_t)P * m->N, m->N, P, 0x7fffffff, &m->s_touched, &m->ntouched,
-                               &m->h_touch_off, st, &m->s_touched_beg));
+    FM_TRY(fm_build_long_index(m, m->s_ncol_beg, m->s_ncol, m->nncol, m->h_ncol_off, P, &m->lstrat, st));
     FM_HIP(m, hipStreamSynchronize(st));
     fm_drop_workspace(m);
     return FM_OK;
@@ -1078,15 +1146,20 @@ extern "C" int fm_partition_batches(fm_matrix* m, int32_t B, void* hip_stream)
     FM_TRY(fm_dev_alloc(m, (void**)&m->d_bb, (size_t)(B + 1) * sizeof(int64_t)));
     FM_HIP(m, hipMemcpy(m->d_bb, m->h_bb.data(), (size_t)(B + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
     FM_TRY(fm_ensure_lazy(m));
-    FM_TRY(build_strata_side(m, false, st, &m->b_colptr, &m->b_row, &m->b_cval, B, true));
-    // entries of batch b: from the start of its first column to the start of the next batch's
-    m->h_batch_nnz_off.assign(B + 1, 0);
-    for (int32_t b = 0; b < B; ++b)
-        FM_HIP(m, hipMemcpyAsync(&m->h_batch_nnz_off[b], m->b_colptr + (int64_t)b * m->D, sizeof(int64_t),
-                                 hipMemcpyDeviceToHost, st));
-    FM_HIP(m, hipStreamSynchronize(st));
-    m->h_batch_nnz_off[B] = m->nnz;
-    FM_TRY(fm_build_long_index(m, m->b_colptr, (int64_t)B * m->D, m->D, B, &m->lbatch, st));
+    if (m->col_mark == nullptr) {
+        FM_TRY(fm_dev_alloc(m, (void**)&m->col_mark, (size_t)m->D * sizeof(int32_t)));
+        FM_HIP(m, hipMemsetAsync(m->col_mark, 0, (size_t)m->D * sizeof(int32_t), st));
+    }
+    StrataSide cols;
+    FM_TRY(build_strata_side(m, false, st, &cols, B, true));
+    m->b_row = cols.ind;
+    m->b_cval = cols.val;
+    m->b_ncol = cols.nz_major;
+    m->b_ncol_beg = cols.nz_beg;
+    m->nbcol = cols.count;
+    m->h_bcol_off = cols.h_list_off;
+    m->h_batch_nnz_off = cols.h_ent_off;
+    FM_TRY(fm_build_long_index(m, m->b_ncol_beg, m->b_ncol, m->nbcol, m->h_bcol_off, B, &m->lbatch, st));
     FM_HIP(m, hipStreamSynchronize(st));
     fm_drop_workspace(m);
     return FM_OK;

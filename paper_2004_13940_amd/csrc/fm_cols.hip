@@ -185,6 +185,7 @@ __device__ __forceinline__ void finish_column(const ColArgs& A, int64_t j, int s
             A.w[j] = __fadd_rn(wj, d);
             if (A.dwn != nullptr) A.dwn[j] = make_float2(d, dn);
             if (A.lazy_last != nullptr) A.lazy_last[j] = A.s + 1;
+            if (A.mark != nullptr) A.mark[j] = 1;  // this column has taken its step from data
         } else {
             if (A.grad_w != nullptr) A.grad_w[j] = g;
         }
@@ -205,8 +206,13 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
     int64_t j = 0, beg = 0, end = 0;
     if (valid) {
         j = A.short_col[pos];
-        beg = A.ptr[j];
-        end = A.ptr[j + 1];
+        if (A.ptr != nullptr) {
+            beg = A.ptr[j];
+            end = A.ptr[j + 1];
+        } else {
+            beg = A.short_beg[pos];
+            end = beg + A.short_len[pos];
+        }
     }
     const int kbase = sub * VEC;
     const bool kact = kbase < A.K;
@@ -238,7 +244,13 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols_empty(const ColArgs A)
     const int grp = lane / LE;
     const int64_t j = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
     if (j >= A.D) return;              // whole groups leave together
-    if (A.ptr[j + 1] != A.ptr[j]) return;
+    if (A.ptr != nullptr) {
+        if (A.ptr[j + 1] != A.ptr[j]) return;
+    } else {  // a stratum or batch: the columns with entries marked themselves; the marks are left clear
+        const bool marked = A.mark[j] != 0;
+        if (marked && sub == 0) A.mark[j] = 0;
+        if (marked) return;
+    }
     const int kbase = sub * VEC;
     const bool kact = kbase < A.K;
     if constexpr (!UPDATE) {
@@ -720,6 +732,12 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     // k_cols and k_cols_tile go to two side streams so that the LDS-bound kernel overlaps the
     // memory-bound ones; the finish kernels wait for all three.
     const int64_t ntile_items = A.order != nullptr ? A.nitems - A.list_off[FM_XCDS] : 0;
+    // columns without entries only feel the regulariser (skipped when there is none and nothing records the
+    // change, or when such steps are postponed)
+    const bool need_empty =
+        (A.lambda_w != 0.f || A.lambda_v != 0.f || !update || A.dV != nullptr) && A.lazy_last == nullptr;
+    ColArgs Am = A;
+    if (!need_empty || A.ptr != nullptr) Am.mark = nullptr;  // marks are only set when a kernel will clear them
     // (not while per-kernel timing is on: each kernel is then timed alone on the launch stream)
     const bool side = (ntile_items > 0 || (A.nitems > 0 && A.nshort > 0)) && !m->prof && fm_side_streams(m);
     hipStream_t s_cols = st, s_tile = st;
@@ -768,15 +786,13 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
         if (g1 > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
         if (g1 > 0) {
             if (update)
-                hipLaunchKernelGGL((k_cols<VEC, L, true, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK), 0, s_cols, A);
+                hipLaunchKernelGGL((k_cols<VEC, L, true, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK), 0, s_cols, Am);
             else
-                hipLaunchKernelGGL((k_cols<VEC, L, false, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK), 0, s_cols, A);
+                hipLaunchKernelGGL((k_cols<VEC, L, false, PACKED>), dim3((unsigned)g1), dim3(FM_BLOCK), 0, s_cols, Am);
             FM_HIP(m, hipGetLastError());
         }
-        // empty columns: regulariser only (skipped when there is none and nothing records the change)
-        const bool need_empty =
-            (A.lambda_w != 0.f || A.lambda_v != 0.f || !update || A.dV != nullptr) && A.lazy_last == nullptr;
-        if (need_empty && A.D > 0) FM_TRY((launch_empty<VEC>(m, A, update, s_cols)));
+        // empty columns of the full matrix: regulariser only (a stratum's wait for the marks, below)
+        if (need_empty && A.ptr != nullptr && A.D > 0) FM_TRY((launch_empty<VEC>(m, A, update, s_cols)));
     }
     if (side) {
         FM_HIP(m, hipEventRecord(m->ev_join1, m->side1));
@@ -789,20 +805,25 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
             ProfScope ps(m, st, FMK_COLS_FINISH);
             const int64_t g3 = (A.nlong + FM_WAVES - 1) / FM_WAVES;
             if (update)
-                hipLaunchKernelGGL((k_cols_finish_wave<VEC, L, true>), dim3((unsigned)g3), dim3(FM_BLOCK), 0, st, A);
+                hipLaunchKernelGGL((k_cols_finish_wave<VEC, L, true>), dim3((unsigned)g3), dim3(FM_BLOCK), 0, st, Am);
             else
-                hipLaunchKernelGGL((k_cols_finish_wave<VEC, L, false>), dim3((unsigned)g3), dim3(FM_BLOCK), 0, st, A);
+                hipLaunchKernelGGL((k_cols_finish_wave<VEC, L, false>), dim3((unsigned)g3), dim3(FM_BLOCK), 0, st, Am);
             FM_HIP(m, hipGetLastError());
             if (A.vlong != nullptr && A.nvlong > 0) {
                 if (update)
                     hipLaunchKernelGGL((k_cols_finish_block<VEC, L, true>), dim3((unsigned)A.nvlong), dim3(FM_BLOCK),
-                                       0, st, A);
+                                       0, st, Am);
                 else
                     hipLaunchKernelGGL((k_cols_finish_block<VEC, L, false>), dim3((unsigned)A.nvlong), dim3(FM_BLOCK),
-                                       0, st, A);
+                                       0, st, Am);
                 FM_HIP(m, hipGetLastError());
             }
         }
+    }
+    // a stratum or batch whose steps are taken at once: every column that had entries has marked itself by now
+    if (need_empty && A.ptr == nullptr && A.D > 0) {
+        ProfScope ps(m, st, FMK_COLS);
+        FM_TRY((launch_empty<VEC>(m, Am, update, st)));
     }
     return FM_OK;
 }

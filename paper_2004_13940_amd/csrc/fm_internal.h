@@ -14,7 +14,8 @@
 constexpr int FM_WAVE = 64;
 constexpr int FM_BLOCK = 256;             // threads per workgroup of the pass kernels
 constexpr int FM_WAVES = FM_BLOCK / FM_WAVE;
-constexpr int FM_MAXP = 4096;
+constexpr int FM_MAXP = 1 << 20;       // row blocks / batches
+constexpr int FM_MAXP_CELLS = 4096;     // the P x P table of entries per cell is only kept up to this P
 constexpr int FM_XCDS = 8;                // L2 domains; workgroup b runs on XCD b % 8
 
 // Tunables of the column-side work decomposition, per handle (fm_set_tuning, fm_set_tile_tuning;
@@ -82,6 +83,8 @@ struct LongIndex {
     // non-empty columns with at most `seg` entries, in column order (per stratum: h_short_off)
     int64_t nshort = 0;
     int32_t* short_col = nullptr;
+    int64_t* short_beg = nullptr;   // per-stratum and per-batch indices only: first entry and number of
+    int32_t* short_len = nullptr;   // entries of every listed column (the full matrix has its colptr)
     std::vector<int64_t> h_short_off;
     // processing order of the full matrix: FM_XCDS lists of item ids, list x walked by the
     // workgroups that run on XCD x, heavy columns panel by panel (order == nullptr: id order)
@@ -126,10 +129,11 @@ struct fm_matrix {
     int64_t* d_rb = nullptr;       // [P+1] row block bounds
     int64_t* d_bb = nullptr;       // [B+1] batch bounds
     int32_t* lazy_last = nullptr;  // [D] see ColArgs::lazy_last
-    int64_t* s_rowptr = nullptr;  // [P*N+1] global offsets into s_col/s_val
+    // Per-stratum matrices: the entries of X ordered by (stratum, row, column) in s_col/s_val and by
+    // (stratum, column, row) in s_row/s_cval.  No pointer array over all P*N rows or P*D columns: only
+    // the rows (columns) that have an entry in a stratum are listed, with the offset of their entries.
     int32_t* s_col = nullptr;
     float* s_val = nullptr;
-    int64_t* s_colptr = nullptr;  // [P*D+1] global offsets into s_row/s_cval
     int32_t* s_row = nullptr;
     float* s_cval = nullptr;
     LongIndex lstrat;
@@ -137,12 +141,20 @@ struct fm_matrix {
     int64_t* s_touched_beg = nullptr;  // [ntouched+1] where the entries of each listed row begin
     int64_t ntouched = 0;
     std::vector<int64_t> h_touch_off;  // [P+1] offsets into s_touched
+    int32_t* s_ncol = nullptr;      // the same for the columns of every stratum
+    int64_t* s_ncol_beg = nullptr;  // [nncol+1]
+    int64_t nncol = 0;
+    std::vector<int64_t> h_ncol_off;  // [P+1]
+    int32_t* col_mark = nullptr;    // [D] zero between launches; see ColArgs::mark
     // row batches of the mini-batch epoch: per batch the CSC of the matrix restricted to its rows
     int32_t B = 0;
     std::vector<int64_t> h_bb, h_batch_nnz_off;  // [B+1] row bounds, [B+1] offsets into b_row/b_cval
-    int64_t* b_colptr = nullptr;  // [B*D+1] global offsets into b_row/b_cval
-    int32_t* b_row = nullptr;
+    int32_t* b_row = nullptr;     // entries ordered by (batch, column, row)
     float* b_cval = nullptr;
+    int32_t* b_ncol = nullptr;      // the columns with an entry in every batch, and where their entries begin
+    int64_t* b_ncol_beg = nullptr;  // [nbcol+1]
+    int64_t nbcol = 0;
+    std::vector<int64_t> h_bcol_off;  // [B+1]
     LongIndex lbatch;
     float* d_brho = nullptr;  // [B] share |I_b|/N
     // workspace, sized for wsK
@@ -216,8 +228,10 @@ struct ProfScope {
 int fm_scan_exclusive_i64(fm_matrix* m, int64_t* d, int64_t n, hipStream_t st);
 int fm_sort_by_key_u32(fm_matrix* m, uint32_t* keys, uint32_t* idx, uint32_t* keys_alt, uint32_t* idx_alt,
                        int64_t n, int bits, hipStream_t st, bool* result_in_alt);
-int fm_build_long_index(fm_matrix* m, const int64_t* ptr, int64_t ncols_total, int64_t D, int32_t nstrata,
-                        LongIndex* out, hipStream_t st);
+// ptr[c], ptr[c+1] bound the entries of list position c = 0..ncols_total-1; ids[c] is its column;
+// h_bounds[s] (nstrata+1 values) is the first list position of stratum s
+int fm_build_long_index(fm_matrix* m, const int64_t* ptr, const int32_t* ids, int64_t ncols_total,
+                        const std::vector<int64_t>& h_bounds, int32_t nstrata, LongIndex* out, hipStream_t st);
 // lfull, with the panel order of heavy columns and the LDS tiles shaped for latent size K (0: unknown)
 int fm_build_full_index(fm_matrix* m, int32_t K, hipStream_t st);
 void fm_tile_shape(const fm_matrix* m, int32_t K, int* tile_rows, int* tile_min, int* tile_seg);
@@ -258,7 +272,7 @@ int fm_unpack_aux(fm_matrix* m, float* a, float* G, float* q, float* r, hipStrea
 struct ColArgs {
     int64_t D;
     int32_t K;
-    const int64_t* ptr;  // [D+1] global offsets
+    const int64_t* ptr;  // [D+1] global offsets of the full matrix; nullptr for a stratum or batch (short_beg/len, items)
     const int32_t* row;
     const float* val;
     const float* r;
@@ -272,7 +286,12 @@ struct ColArgs {
     float* dV;       // delta outputs (nullable)
     float2* dwn;
     const int32_t* short_col;  // list of the short non-empty columns of this launch
+    const int64_t* short_beg;  // with ptr == nullptr: first entry and number of entries of every listed column
+    const int32_t* short_len;
     int64_t nshort;
+    // nullable, with ptr == nullptr and steps taken at once: every column that takes its step from data sets
+    // mark[j] = 1, and the kernel of the columns without entries skips the marked ones and clears the mark
+    int32_t* mark;
     float lambda_w, lambda_v, eta;
     // regulariser share: rho = 1 when rho == nullptr, else rho[p] = |I_p|/N with p = (c(j) - s) mod P, where
     // c(j) = place[j], or the column block of j when place == nullptr

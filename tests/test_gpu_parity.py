@@ -909,3 +909,48 @@ def test_half_gather_needs_a_latent_size_that_is_a_multiple_of_four():
         m.fm_forward(p, to_dev(y), d_w0, d_w, d_V)
     assert e.value.code == -1
     m.close()
+
+
+# ----------------------------------------------- many blocks, one example per step ----
+
+def test_per_example_steps_of_the_tiny_workload():
+    """B = N: every step of the mini-batch epoch takes one example (Section 4.1's stochastic updates as printed),
+    2,000 steps per epoch, against the oracle."""
+    B = _B()
+    wl = make_config(1)
+    m, _, _ = _run_minibatch_epochs(B, wl, wl.N, 1, update_w0=bool(wl.update_w0))
+    m.close()
+
+
+def test_more_blocks_than_the_cell_table_holds():
+    """P = 6,000 row and column blocks (most column blocks empty, one or two rows per row block): the structures
+    add up, the cell table is refused, and an epoch on stale aggregates without regulariser moves w exactly as the
+    full-gradient step does (the closed form that pins the oracle's stale epoch, whatever P is)."""
+    import torch
+    from paper_2004_13940_amd.workloads import Workload
+    B = _B()
+    N, D, K, P = 7000, 60, 4, 6000
+    rowptr, col, val, y, w0, w, V = _problem(321, N, D, K, 0.1, O.LOSS_LOGISTIC)
+    wl = Workload("manyblocks", N, D, K, rowptr, col, val, y, w0, w, V, O.LOSS_LOGISTIC, 0.0, 0.0, 0.3, 1.0 / N, 1, P, 1)
+    m, p, X, dev, host = _run_full_epochs(B, wl, 0)
+    m.fm_partition(P)
+    rb, cb, _ = (np.empty(P + 1, np.int64), np.empty(P + 1, np.int64), None)
+    m._check(B.load().fm_get_block_index(m._h, B._vp(rb), B._vp(cb), B._vp(None)))
+    np.testing.assert_array_equal(rb, O.block_bounds(N, P))
+    np.testing.assert_array_equal(cb, O.block_bounds(D, P))
+    with pytest.raises(B.FMError) as e:
+        m.fm_get_block_index()
+    assert e.value.code == -5
+    assert sum(m.fm_get_stratum_nnz(s) for s in range(0, P, 97)) <= len(col)
+    got = m.fm_get_stratum_csc(0)
+    want = O.stratum_csc(X, P, 0)
+    for g, wv in zip(got, want):
+        np.testing.assert_array_equal(g, wv.astype(g.dtype))
+    d_w0, d_w, d_V, d_y = dev
+    p.stale_aux = 1
+    m.fm_stratified_epoch(p, d_y, d_w0, d_w, d_V)
+    torch.cuda.synchronize()
+    ow0, ow, _, _ = O.full_epoch(X, y, float(w0), w, V, update_w0=True, **oracle_kw(wl))
+    assert_close(d_w.cpu().numpy(), ow, "w after a stale epoch over 6,000 strata")
+    assert abs(d_w0.item() - ow0) <= REL_TOL * max(abs(ow0), 1e-3)
+    m.close()
