@@ -295,6 +295,8 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain 1 GiB device copy three times (reference for the byte counters)")
     ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"))
+    ap.add_argument("--only-config", type=int, default=0, metavar="IDX",
+                    help="time workload IDX alone with the per-config protocol and print its entry (for kernel traces)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); nothing here uses a second device")
@@ -314,6 +316,10 @@ def main():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
     T = Timed(torch)
+    if args.only_config:
+        cw = make_config(args.only_config, scale=args.scale)
+        print(json.dumps({cw.name: time_config(torch, B, cw, 5, 0)}))
+        return
     t0 = time.time()
     wl = make_config(args.workload, scale=args.scale)
     t_gen = time.time() - t0
