@@ -227,6 +227,22 @@ def time_config(torch, B, wl, reps, oracle_rows):
         out["forward_half_gather"] = entry(ms, None)
         ms, _ = T.run(lambda: m.fm_sgd_epoch(ph, y, w0, w, V), reps, before=restore)
         out["epoch_half_gather"] = entry(ms, None)
+    if nnz == N * D and D in (32, 64) and K in (32, 64):
+        # every row stores all columns: the figures above are those of the dense (matrix-core) kernels, which
+        # do not read the column indices (they move 4 of the 8 bytes per entry that the algorithmic count
+        # holds); the same calls through the general sparse kernels, for comparison
+        out["kernels"] = "dense rows: fp32 MFMA contractions (column indices not read)"
+        m.fm_set_option(B.FM_OPT_DENSE_ROWS, 0)
+        fwd(), grad()
+        ms, _ = T.run(fwd, reps)
+        out["forward_sparse_kernels"] = entry(ms, b_fwd)
+        ms, _ = T.run(grad, reps)
+        out["gradient_sparse_kernels"] = entry(ms, b_grad)
+        restore()
+        m.fm_sgd_epoch(p, y, w0, w, V)
+        ms, _ = T.run(lambda: m.fm_sgd_epoch(p, y, w0, w, V), reps, before=restore)
+        out["epoch_sparse_kernels"] = entry(ms, b_epoch)
+        m.fm_set_option(B.FM_OPT_DENSE_ROWS, 1)
     del yhat, a, q, r, G, gw, gV
     torch.cuda.empty_cache()
     t0 = time.perf_counter()

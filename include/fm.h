@@ -253,8 +253,18 @@ int fm_profile_read(fm_matrix* m, int64_t* launches /*HOST nk*/, double* total_m
  *                        regulariser-only steps of columns without entries in a cell or batch; 0: every
  *                        column takes its step in every stratum or batch.
  *   FM_OPT_GRAPH         fm_stratified_epoch replayed from a captured HIP graph: 0 never, 1 (default)
- *                        when the strata are small enough for the launches to dominate, 2 always. */
-typedef enum { FM_OPT_AUX_PLANAR = 0, FM_OPT_SIDE_STREAMS = 1, FM_OPT_LAZY_REG = 2, FM_OPT_GRAPH = 3 } fm_option;
+ *                        when the strata are small enough for the launches to dominate, 2 always.
+ *   FM_OPT_DENSE_ROWS    1 (default): a matrix in which every row stores all D columns (D and K in
+ *                        {32, 64}) takes dense kernels on the matrix cores for fm_forward, fm_gradient and
+ *                        fm_sgd_epoch (G = XV and X^T(r.G) as fp32 contractions; the column indices are not
+ *                        read); 0: the sparse kernels, as for every other matrix. */
+typedef enum {
+    FM_OPT_AUX_PLANAR = 0,
+    FM_OPT_SIDE_STREAMS = 1,
+    FM_OPT_LAZY_REG = 2,
+    FM_OPT_GRAPH = 3,
+    FM_OPT_DENSE_ROWS = 4
+} fm_option;
 int fm_set_option(fm_matrix* m, int32_t option /*fm_option*/, int32_t value);
 
 /* Work-decomposition knobs of the column side, per handle, for callers that tune or test them; they

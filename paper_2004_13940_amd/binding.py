@@ -41,7 +41,7 @@ EXPORTS = ["fm_build_csr", "fm_build_csc", "fm_partition", "fm_partition_placed"
            "fm_stratified_end", "fm_get_aux", "fm_profile_enable", "fm_profile_kernels",
            "fm_profile_kernel_name", "fm_profile_read", "fm_set_option", "fm_set_tuning", "fm_set_tile_tuning", "fm_destroy",
            "fm_last_error"]
-FM_OPT_AUX_PLANAR, FM_OPT_SIDE_STREAMS, FM_OPT_LAZY_REG, FM_OPT_GRAPH = 0, 1, 2, 3
+FM_OPT_AUX_PLANAR, FM_OPT_SIDE_STREAMS, FM_OPT_LAZY_REG, FM_OPT_GRAPH, FM_OPT_DENSE_ROWS = 0, 1, 2, 3, 4
 
 _lib = None
 

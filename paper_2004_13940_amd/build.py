@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfm_mi355x.so")
 PROBE_LIB = os.path.join(HERE, "libfm_bench_probe.so")  # calibration probes of bench.py, not part of the product
-SOURCES = ["fm_api.hip", "fm_build.hip", "fm_rows.hip", "fm_cols.hip", "fm_reduce.hip", "fm_noalloc.hip"]
+SOURCES = ["fm_api.hip", "fm_build.hip", "fm_rows.hip", "fm_cols.hip", "fm_dense.hip", "fm_reduce.hip", "fm_noalloc.hip"]
 PROBE_SOURCES = ["bench_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

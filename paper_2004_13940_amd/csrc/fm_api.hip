@@ -166,6 +166,7 @@ extern "C" int fm_build_csr(int64_t N, int64_t D, int64_t nnz, const int64_t* ro
         rc = fm_fail(m, FM_ENOMEM, "pinned allocation failed");
     if (rc == FM_OK && hipStreamSynchronize(st) != hipSuccess) rc = fm_fail(m, FM_EHIP, "upload failed");
     if (rc == FM_OK) rc = fm_noalloc_init_device(m);  // set-up for fm_forward_noalloc on this device
+    if (rc == FM_OK) rc = fm_dense_detect(m, st);
     if (rc != FM_OK) {
         g_build_error = m->err;
         fm_destroy(m);
@@ -389,7 +390,8 @@ static int ensure_ws(fm_matrix* m, int32_t K)
     }
     const size_t D = (size_t)m->D;
     FM_TRY(fm_dev_alloc(m, (void**)&m->aux, (size_t)std::max<int64_t>(fm_aux_floats(m, K), 1) * sizeof(float)));
-    const int64_t items = std::max<int64_t>(std::max<int64_t>(m->lfull.nitems, m->lstrat.nitems), m->lbatch.nitems);
+    const int64_t items = std::max<int64_t>(std::max<int64_t>(m->lfull.nitems, m->lstrat.nitems),
+                                            std::max<int64_t>(m->lbatch.nitems, m->ldense.nitems));
     FM_TRY(fm_dev_alloc(m, (void**)&m->part,
                         (size_t)std::max<int64_t>(items, 1) * (size_t)fm_part_stride(K) * sizeof(float)));
     FM_TRY(fm_dev_alloc(m, (void**)&m->row_part, (size_t)std::max<int64_t>(fm_rows_grid(m->N, K), 1) * 2 * sizeof(float)));
@@ -505,8 +507,12 @@ static int run_forward(fm_matrix* m, const fm_params* p, const float* y, const f
     A.loss = p->loss;
     A.s = p->loss_scale;
     FM_TRY(half_copy(m, p, V, &A.Vh, st));
+    const bool dense = A.Vh == nullptr && fm_dense_shape_ok(m, p->K);
+    if (dense) A.dense_D = (int32_t)m->D;
     FM_TRY(fm_launch_rows(m, A, false, st));
-    if (A.row_part != nullptr) FM_TRY(fm_reduce_pairs(m, m->row_part, fm_rows_grid(m->N, p->K), m->scal + 0, st));
+    // one (loss, multiplier) pair per row block of the sparse kernel, per 32 rows of the dense one
+    const int64_t pairs = dense ? (m->N + 31) / 32 : fm_rows_grid(m->N, p->K);
+    if (A.row_part != nullptr) FM_TRY(fm_reduce_pairs(m, m->row_part, pairs, m->scal + 0, st));
     return FM_OK;
 }
 
@@ -580,6 +586,20 @@ extern "C" int fm_evaluate(fm_matrix* m, const fm_params* p, const float* y, con
 
 // --------------------------------------------------------------- gradient ----
 
+// Work decomposition of a column pass over the whole matrix: the items of the CSC copy, or, for a matrix that
+// stores every column in every row, chunks of rows of the dense matrix.
+static void full_long(fm_matrix* m, const fm_params* p, ColArgs& A)
+{
+    if (fm_dense_shape_ok(m, p->K) && m->ldense.long_col != nullptr) {
+        fill_long(m, A, m->ldense, 0, false);
+        A.X = m->val;
+        A.chunk_rows = m->dense_chunk_rows;
+        A.nchunks = m->dense_chunks;
+    } else {
+        fill_long(m, A, m->lfull, 0, false);
+    }
+}
+
 static void base_col_args(fm_matrix* m, const fm_params* p, ColArgs& A)
 {
     memset(&A, 0, sizeof(A));
@@ -635,7 +655,7 @@ extern "C" int fm_gradient(fm_matrix* m, const fm_params* p, const float* r, con
     A.V = const_cast<float*>(V);
     A.grad_w = grad_w;
     A.grad_V = grad_V;
-    fill_long(m, A, m->lfull, 0, false);
+    full_long(m, p, A);
     return fm_launch_cols(m, A, false, st);
 }
 
@@ -676,7 +696,7 @@ extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, fl
     A.packed = fm_cols_packed_mode(m, p->K);
     A.w = w;
     A.V = V;
-    fill_long(m, A, m->lfull, 0, false);
+    full_long(m, p, A);
     FM_TRY(fm_launch_cols(m, A, true, st));
     if (p->update_w0) FM_TRY(fm_bias_step(m, w0, m->scal + 1, p->eta, nullptr, st));
     if (objective != nullptr) {
@@ -1050,6 +1070,9 @@ extern "C" int fm_set_option(fm_matrix* m, int32_t option, int32_t value)
             return FM_OK;
         case FM_OPT_LAZY_REG:
             m->opt.lazy_reg = value != 0;
+            return FM_OK;
+        case FM_OPT_DENSE_ROWS:
+            m->opt.dense_rows = value != 0;
             return FM_OK;
         case FM_OPT_GRAPH:
             if (value < 0 || value > 2) return fm_fail(m, FM_EINVAL, "graph mode %d outside 0..2", value);

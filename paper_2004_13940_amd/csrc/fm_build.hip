@@ -949,6 +949,7 @@ extern "C" int fm_build_csc(fm_matrix* m, void* hip_stream)
         fm_dev_free(m, i1);
     }
     FM_TRY(fm_build_full_index(m, 0, st));
+    FM_TRY(fm_dense_build_index(m, st));  // nothing unless every row stores all columns
     FM_HIP(m, hipStreamSynchronize(st));
     m->has_csc = true;
     fm_drop_workspace(m);

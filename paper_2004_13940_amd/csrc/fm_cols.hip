@@ -739,7 +739,8 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
     ColArgs Am = A;
     if (!need_empty || A.ptr != nullptr) Am.mark = nullptr;  // marks are only set when a kernel will clear them
     // (not while per-kernel timing is on: each kernel is then timed alone on the launch stream)
-    const bool side = (ntile_items > 0 || (A.nitems > 0 && A.nshort > 0)) && !m->prof && fm_side_streams(m);
+    const bool dense = A.X != nullptr;  // one kernel leaves the partial sums of every column
+    const bool side = !dense && (ntile_items > 0 || (A.nitems > 0 && A.nshort > 0)) && !m->prof && fm_side_streams(m);
     hipStream_t s_cols = st, s_tile = st;
     if (side) {
         FM_HIP(m, hipEventRecord(m->ev_fork, st));
@@ -748,7 +749,11 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
         s_tile = m->side1;
         s_cols = m->side2;
     }
-    if (ntile_items > 0) {  // items of dense-ish columns, sorted by row tile
+    if (dense) {
+        ProfScope ps(m, st, FMK_COLS_LONG);
+        FM_TRY(fm_launch_cols_dense(m, A, st));
+    }
+    if (!dense && ntile_items > 0) {  // items of dense-ish columns, sorted by row tile
         ProfScope ps(m, s_tile, FMK_COLS_TILE);
         bool staged = false;
         if constexpr (VEC == 4) staged = launch_tile(m, A, s_tile);
@@ -763,7 +768,7 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
         }
         FM_HIP(m, hipGetLastError());
     }
-    if (A.nitems > 0) {
+    if (!dense && A.nitems > 0) {
         int64_t g2;
         if (A.order != nullptr) {
             int64_t longest = 0;
@@ -780,7 +785,7 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
             FM_HIP(m, hipGetLastError());
         }
     }
-    {
+    if (!dense) {
         ProfScope ps(m, s_cols, FMK_COLS);
         const int64_t g1 = (A.nshort + per - 1) / per;
         if (g1 > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "fm.h"
+
 #include <type_traits>
 
 template <int VEC>
@@ -86,6 +88,29 @@ __device__ __forceinline__ T fm_wave_sum(T v)
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
     return v;
+}
+
+// Loss value and multiplier for one example (cases after eq. updates_v; the loss
+// constants make the printed multiplier the exact derivative).  expf only ever sees
+// a non-positive argument.
+__device__ __forceinline__ void loss_and_multiplier(int32_t loss, float s, float yh, float y, float& l, float& r)
+{
+    if (loss == FM_LOSS_SQUARED) {
+        const float d = yh - y;
+        l = 0.5f * d * d;
+        r = s * d;
+    } else {
+        const float mg = y * yh;
+        if (mg > 0.f) {
+            const float e = expf(-mg);
+            l = log1pf(e);
+            r = -s * y * e / (1.f + e);
+        } else {
+            const float e = expf(mg);
+            l = -mg + log1pf(e);
+            r = -s * y / (1.f + e);
+        }
+    }
 }
 
 // Block b of the floor split of n items into P blocks that holds index i:

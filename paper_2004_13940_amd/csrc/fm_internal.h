@@ -38,6 +38,7 @@ struct FmOptions {
     bool side_streams = true;  // column kernels that touch disjoint columns overlap on internal side streams
     bool lazy_reg = true;      // regulariser-only steps of a stratified or mini-batch epoch are postponed
     int graph = 1;             // stratified epoch from a captured graph: 0 never, 1 when launch-bound, 2 always
+    bool dense_rows = true;    // matrices that store every column in every row take the dense (MFMA) kernels
 };
 
 // Where the handle keeps the aggregates.  Packed (when [G | r] fits one 128-byte line: K % 4 == 0,
@@ -162,6 +163,12 @@ struct fm_matrix {
     float* aux = nullptr;   // aggregates, see fm_aux_layout
     _Float16* Vh = nullptr; // [D*K] half-precision copy of V for passes with half_gather (allocated on first use)
     int32_t VhK = 0;        // the K it was sized for
+    // Every row stores all D columns in order (col[e] == e % D): `val` is then a dense row-major N x D
+    // matrix and whole-matrix passes can run as dense contractions.  ldense: the partial sums of column j
+    // over chunk c of the rows live at item j * dense_chunks + c.
+    bool is_dense = false;
+    LongIndex ldense;
+    int64_t dense_chunk_rows = 0, dense_chunks = 0;
     float* dV = nullptr;    // [D*K] last step's change of V
     float2* dwn = nullptr;  // [D] (change of w_j, change of |v_j|^2)
     float* part = nullptr;      // [max items * part_stride(K)] partial sums of the items, see fm_part_stride
@@ -255,6 +262,7 @@ struct RowArgs {
     int64_t ss;         // floats between consecutive rows of r, a, q (1, or the aggregate row stride)
     int32_t whole_rows; // forward into packed aggregate rows: write r, a, q and the padding with G
     float* row_part;    // nullable: [2*gridDim] loss and sum r per block
+    int32_t dense_D;      // forward: > 0 when `val` is a dense row-major N x dense_D matrix (col is then not read)
     const int32_t* rows;  // nullable: the launch covers rows[0..N) instead of rows 0..N-1, and
                           // rowptr[k], rowptr[k+1] bound the entries of rows[k]
     int32_t loss;
@@ -267,6 +275,13 @@ int64_t fm_rows_grid(int64_t N, int32_t K);
 int fm_noalloc_init_device(fm_matrix* m);
 int fm_pack_aux(fm_matrix* m, const float* r, const float* G, hipStream_t st);  // packed layout only
 int fm_to_half(fm_matrix* m, const float* x, _Float16* out, int64_t n, hipStream_t st);  // round to nearest even
+// dense matrices (fm_dense.hip)
+int fm_dense_detect(fm_matrix* m, hipStream_t st);           // sets is_dense
+bool fm_dense_shape_ok(const fm_matrix* m, int32_t K);       // the dense kernels exist for this D and K
+int fm_dense_build_index(fm_matrix* m, hipStream_t st);      // ldense, dense_chunk_rows, dense_chunks
+int fm_launch_rows_dense(fm_matrix* m, const RowArgs& A, hipStream_t st);
+struct ColArgs;
+int fm_launch_cols_dense(fm_matrix* m, const ColArgs& A, hipStream_t st);  // partial sums only; the finish kernels follow
 int fm_unpack_aux(fm_matrix* m, float* a, float* G, float* q, float* r, hipStream_t st);
 
 struct ColArgs {
@@ -278,6 +293,10 @@ struct ColArgs {
     const float* r;
     const float* G;
     int64_t gs, rs;  // row strides of G and r in floats
+    // dense matrices (every row stores all D columns): X = the CSR values as a row-major N x D matrix; wavefront c
+    // sums rows [c * chunk_rows, (c+1) * chunk_rows) and stores column j's partial sums at item j * nchunks + c
+    const float* X;
+    int64_t chunk_rows, nchunks;
     int32_t packed;  // FM_PLANAR, or FM_PACKED_LANE: G rows are packed aggregate rows [G | r | a | q | pad]
     float* w;        // updated in place when update
     float* V;

@@ -13,29 +13,6 @@ namespace {
 
 enum { MODE_FORWARD = 0, MODE_REFRESH = 1, MODE_FORWARD_HALF = 2 };  // the last: V rows from the half-precision copy
 
-// Loss value and multiplier for one example (cases after eq. updates_v; the loss
-// constants make the printed multiplier the exact derivative).  expf only ever sees
-// a non-positive argument.
-__device__ __forceinline__ void loss_and_multiplier(int32_t loss, float s, float yh, float y, float& l, float& r)
-{
-    if (loss == FM_LOSS_SQUARED) {
-        const float d = yh - y;
-        l = 0.5f * d * d;
-        r = s * d;
-    } else {
-        const float mg = y * yh;
-        if (mg > 0.f) {
-            const float e = expf(-mg);
-            l = log1pf(e);
-            r = -s * y * e / (1.f + e);
-        } else {
-            const float e = expf(mg);
-            l = -mg + log1pf(e);
-            r = -s * y / (1.f + e);
-        }
-    }
-}
-
 template <int VEC, int L, int MODE>
 __global__ __launch_bounds__(FM_BLOCK) void k_rows(const RowArgs A)
 {
@@ -355,6 +332,7 @@ int64_t fm_rows_grid(int64_t N, int32_t K)
 
 int fm_launch_rows(fm_matrix* m, const RowArgs& A, bool refresh, hipStream_t st)
 {
+    if (!refresh && A.dense_D > 0 && A.Vh == nullptr) return fm_launch_rows_dense(m, A, st);
     int vec, lanes;
     if (!fm_shape_for_K(A.K, &vec, &lanes)) return fm_fail(m, FM_EINVAL, "unsupported K=%d", A.K);
     switch (vec) {

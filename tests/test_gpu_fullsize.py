@@ -246,8 +246,9 @@ def test_full_size_minibatch_epoch_and_gradient_entry_point(full):
 
 @pytest.mark.parametrize("idx", [3, 2])
 def test_full_shape_every_epoch_of_the_config(idx):
-    """Configs 3 (text-like, 10 epochs, P=32: the stratified epochs are replayed from a graph) and 2 (dense,
-    K=32 planar aggregates through the LDS-staged kernel, 5 epochs, P=16) at their stated shapes: the stated
+    """Configs 3 (text-like, 10 epochs, P=32: the stratified epochs are replayed from a graph) and 2 (every
+    row stores all 64 columns: forward and gradient on the matrix cores, K=32 planar aggregates, 5 epochs,
+    P=16) at their stated shapes: the stated
     number of full-gradient epochs, then as many stratified epochs from where those ended, every epoch's
     objective, w, V, w0 against the oracle; gradients and the first step element by element."""
     import torch
@@ -263,6 +264,22 @@ def test_full_shape_every_epoch_of_the_config(idx):
     m.close()
     torch.cuda.empty_cache()
     _say(f"config {idx} done in {time.time() - t0:.1f}s")
+
+
+def test_full_shape_config2_on_the_sparse_kernels():
+    """Config 2 at its stated shape with the dense kernels switched off: the general sparse path (planar K=32
+    aggregates through the LDS-staged column kernel with its real tile sizes), two epochs, the gradient entry
+    point and the first step element by element."""
+    import torch
+    from paper_2004_13940_amd import binding as B
+    t0 = time.time()
+    wl = make_config(2)
+    m, p, X, dev, host = run_full_epochs(B, wl, 2, setup=lambda h: h.fm_set_option(B.FM_OPT_DENSE_ROWS, 0))
+    _check_gradient_entry_point(B, wl, m, X, *host)
+    _check_first_epoch_elementwise(B, wl, m, X)
+    m.close()
+    torch.cuda.empty_cache()
+    _say(f"config 2, sparse kernels, done in {time.time() - t0:.1f}s")
 
 
 def test_full_shape_config5():

@@ -913,6 +913,61 @@ def test_half_gather_needs_a_latent_size_that_is_a_multiple_of_four():
 
 # ----------------------------------------------- many blocks, one example per step ----
 
+@pytest.mark.parametrize("N,D,K,loss", [(1007, 64, 32, O.LOSS_SQUARED), (70, 32, 32, O.LOSS_LOGISTIC),
+                                        (5003, 32, 64, O.LOSS_LOGISTIC), (9001, 64, 64, O.LOSS_SQUARED)])
+def test_matrices_that_store_every_column_take_the_dense_kernels(N, D, K, loss):
+    """Every row stores all D columns: forward, gradient and epochs run on the matrix cores by default
+    and on the sparse kernels when the handle says so; both meet the oracle, and they are two paths
+    (their results differ in the last bits)."""
+    import torch
+    from types import SimpleNamespace
+    B = _B()
+    rng = np.random.default_rng(4000 + N + D + K)
+    val = (rng.standard_normal(N * D) * 0.5).astype(np.float32)
+    val[rng.random(N * D) < 0.05] = 0.0  # stored zeros
+    rowptr = np.arange(N + 1, dtype=np.int64) * D
+    col = np.tile(np.arange(D, dtype=np.int32), N)
+    y = (np.where(rng.random(N) < 0.5, 1.0, -1.0) if loss == O.LOSS_LOGISTIC else rng.standard_normal(N)).astype(np.float32)
+    w0 = np.float32(0.3)
+    w = (rng.standard_normal(D) * 0.1).astype(np.float32)
+    V = (rng.standard_normal((D, K)) * 0.1).astype(np.float32)
+    X = O.make_matrix(N, D, rowptr, col, val)
+    s = 1.0 / N
+    a, G, q, yhat = O.forward(X, float(w0), w, V)
+    l, r = O.loss_multiplier(loss, s, yhat, y)
+    want = dict(yhat=yhat, a=a, G=G, q=q, r=r)
+    got_G = {}
+    for dense in (1, 0):
+        _say("dense rows", N, D, K, loss, "matrix cores" if dense else "sparse kernels")
+        m = B.Matrix(N, D, rowptr, col, val)
+        m.fm_set_option(B.FM_OPT_DENSE_ROWS, dense)
+        p = B.make_params(K, loss, 0.01, 0.02, 0.1, loss_scale=s)
+        d_w0, d_w, d_V = dev_params(w0, w, V)
+        d_y = to_dev(y)
+        out = {k: torch.full((N * (K if k == "G" else 1),), float("nan"), device="cuda") for k in want}
+        loss_sum = m.fm_forward(p, d_y, d_w0, d_w, d_V, want_loss=True, **out)
+        torch.cuda.synchronize()
+        for k in want:
+            assert_close(out[k].cpu().numpy(), want[k], f"{k} dense={dense}")
+        assert abs(loss_sum - float(l.sum())) <= REL_TOL * abs(float(l.sum()))
+        # (G itself can agree bit for bit: both paths add the products of a row in column order)
+        got_G[dense] = np.concatenate([out[k].cpu().numpy() for k in ("a", "q", "yhat")])
+        m.fm_build_csc()
+        g0 = torch.zeros(1, device="cuda")
+        gw = torch.full((D,), float("nan"), device="cuda")
+        gV = torch.full((D * K,), float("nan"), device="cuda")
+        m.fm_gradient(p, out["r"], out["G"], d_w, d_V, g0, gw, gV)
+        torch.cuda.synchronize()
+        wg0, wgw, wgV = O.gradient(X, r, G, w, V, p.lambda_w, p.lambda_v)
+        assert_close(gw.cpu().numpy(), wgw, f"grad_w dense={dense}")
+        assert_close(gV.cpu().numpy(), wgV, f"grad_V dense={dense}")
+        wl = SimpleNamespace(N=N, D=D, K=K, rowptr=rowptr, col=col, val=val, y=y, w0=w0, w=w, V=V, loss=loss,
+                             lambda_w=0.01, lambda_v=0.02, eta=0.1, loss_scale=s, update_w0=1)
+        _run_full_epochs(B, wl, 3, m=m)
+        m.close()
+    assert not np.array_equal(got_G[0], got_G[1]), "the two settings ran the same kernels"
+
+
 def test_per_example_steps_of_the_tiny_workload():
     """B = N: every step of the mini-batch epoch takes one example (Section 4.1's stochastic updates as printed),
     2,000 steps per epoch, against the oracle."""
