@@ -233,55 +233,83 @@ __global__ __launch_bounds__(FM_BLOCK) void k_cols(const ColArgs A)
 // Columns with nothing stored (in this matrix or stratum) only feel the regulariser; one group
 // of LE = K/VEC lanes per column over all D columns, consecutive groups on consecutive columns
 // so that V is streamed.  The gradient is finish_column with zero data sums; the step is the
-// multiplication by the step factor.
+// multiplication by the step factor.  A group takes FM_EMPTY_U columns, one from each of as many
+// consecutive slabs of columns: the tests for emptiness are all issued before the first row of V
+// is asked for, and all rows before the first is written, so that the kernel is not one memory
+// round trip after the other per column.
+constexpr int FM_EMPTY_U = 4;
 template <int VEC, int LE, bool UPDATE>
 __global__ __launch_bounds__(FM_BLOCK) void k_cols_empty(const ColArgs A)
 {
     constexpr int R = FM_WAVE / LE;
+    constexpr int U = FM_EMPTY_U;
     const int lane = threadIdx.x & (FM_WAVE - 1);
     const int wave = threadIdx.x / FM_WAVE;
     const int sub = lane & (LE - 1);
     const int grp = lane / LE;
-    const int64_t j = (int64_t)blockIdx.x * (FM_WAVES * R) + wave * R + grp;
-    if (j >= A.D) return;              // whole groups leave together
-    if (A.ptr != nullptr) {
-        if (A.ptr[j + 1] != A.ptr[j]) return;
-    } else {  // a stratum or batch: the columns with entries marked themselves; the marks are left clear
-        const bool marked = A.mark[j] != 0;
-        if (marked && sub == 0) A.mark[j] = 0;
-        if (marked) return;
-    }
     const int kbase = sub * VEC;
     const bool kact = kbase < A.K;
-    if constexpr (!UPDATE) {
-        float acc[VEC];
+    int64_t j[U];
+    bool todo[U];  // uniform inside a group
 #pragma unroll
-        for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
-        finish_column<VEC, LE, false>(A, j, sub, kbase, kact, acc, 0.f, 0.f,
-                                      load_column<VEC, false>(A, j, sub, kbase, kact));
-    } else {
-        const int32_t qb = column_class(A, j);
-        const float rho = reg_share(A, qb, A.s);
-        float dn = 0.f;
-        if (kact) {
-            const float f = step_factor(rho, A.lambda_v, A.eta);
-            float v[VEC], vn[VEC], d[VEC];
-            fm_load_vec<VEC>(A.V + j * A.K + kbase, v);
-#pragma unroll
-            for (int z = 0; z < VEC; ++z) {
-                vn[z] = __fmul_rn(v[z], f);
-                d[z] = vn[z] - v[z];
-                dn += d[z] * (2.f * v[z] + d[z]);
+    for (int u = 0; u < U; ++u) {
+        j[u] = ((int64_t)blockIdx.x * U + u) * (FM_WAVES * R) + wave * R + grp;
+        todo[u] = j[u] < A.D;
+        if (todo[u]) {
+            if (A.ptr != nullptr) {
+                todo[u] = A.ptr[j[u] + 1] == A.ptr[j[u]];
+            } else {  // a stratum or batch: the columns with entries marked themselves; the marks are left clear
+                const bool marked = A.mark[j[u]] != 0;
+                if (marked && sub == 0) A.mark[j[u]] = 0;
+                todo[u] = !marked;
             }
-            fm_store_vec<VEC>(A.V + j * A.K + kbase, vn);
-            if (A.dV != nullptr) fm_store_vec<VEC>(A.dV + j * A.K + kbase, d);
         }
-        if (A.dwn != nullptr) dn = fm_group_sum<LE>(dn);
-        if (sub == 0) {
-            const float wj = A.w[j];
-            const float wn = __fmul_rn(wj, step_factor(rho, A.lambda_w, A.eta));
-            A.w[j] = wn;
-            if (A.dwn != nullptr) A.dwn[j] = make_float2(wn - wj, dn);
+    }
+    if constexpr (!UPDATE) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!todo[u]) continue;
+            float acc[VEC];
+#pragma unroll
+            for (int z = 0; z < VEC; ++z) acc[z] = 0.f;
+            finish_column<VEC, LE, false>(A, j[u], sub, kbase, kact, acc, 0.f, 0.f,
+                                          load_column<VEC, false>(A, j[u], sub, kbase, kact));
+        }
+    } else {
+        float v[U][VEC];
+        float wj[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int z = 0; z < VEC; ++z) v[u][z] = 0.f;
+            wj[u] = 0.f;
+            if (todo[u] && kact) fm_load_vec<VEC>(A.V + j[u] * A.K + kbase, v[u]);
+            if (todo[u] && sub == 0) wj[u] = A.w[j[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!todo[u]) continue;
+            const int32_t qb = column_class(A, j[u]);
+            const float rho = reg_share(A, qb, A.s);
+            float dn = 0.f;
+            if (kact) {
+                const float f = step_factor(rho, A.lambda_v, A.eta);
+                float vn[VEC], d[VEC];
+#pragma unroll
+                for (int z = 0; z < VEC; ++z) {
+                    vn[z] = __fmul_rn(v[u][z], f);
+                    d[z] = vn[z] - v[u][z];
+                    dn += d[z] * (2.f * v[u][z] + d[z]);
+                }
+                fm_store_vec<VEC>(A.V + j[u] * A.K + kbase, vn);
+                if (A.dV != nullptr) fm_store_vec<VEC>(A.dV + j[u] * A.K + kbase, d);
+            }
+            if (A.dwn != nullptr) dn = fm_group_sum<LE>(dn);
+            if (sub == 0) {
+                const float wn = __fmul_rn(wj[u], step_factor(rho, A.lambda_w, A.eta));
+                A.w[j[u]] = wn;
+                if (A.dwn != nullptr) A.dwn[j[u]] = make_float2(wn - wj[u], dn);
+            }
         }
     }
 }
@@ -665,7 +693,7 @@ inline bool launch_tile(fm_matrix* m, const ColArgs& A, hipStream_t st)
 template <int VEC, int LE>
 int launch_empty_l(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
 {
-    const int64_t per = (int64_t)FM_WAVES * (FM_WAVE / LE);
+    const int64_t per = (int64_t)FM_WAVES * (FM_WAVE / LE) * FM_EMPTY_U;
     const int64_t grid = (A.D + per - 1) / per;
     if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "column grid too large");
     if (update)
