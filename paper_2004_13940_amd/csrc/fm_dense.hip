@@ -17,6 +17,8 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int DT = 32;  // rows (forward) or columns (gradient) per tile
+constexpr int FM_DENSE_TILES = 8;      // 32-row tiles per wavefront of the forward kernel
+constexpr int FM_DENSE_CHUNKS = 4096;  // row chunks (one wavefront each) of the column kernel
 
 __device__ __forceinline__ int c_row(int v, int lane) { return 8 * (v / 4) + 4 * (lane / 32) + (v % 4); }
 
@@ -61,7 +63,9 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows_dense(const RowArgs A)
 #pragma unroll
         for (int t = 0; t < D / 2; ++t) vb[kb][t] = A.V[(int64_t)(2 * t + half) * K + kb * DT + lo];
 
-    const int64_t tid = (int64_t)blockIdx.x * FM_WAVES + wave;  // 32-row tile of this wavefront
+    // a wavefront takes FM_DENSE_TILES consecutive 32-row tiles, so that its share of V is loaded once for all of them
+    for (int tt = 0; tt < FM_DENSE_TILES; ++tt) {
+    const int64_t tid = ((int64_t)blockIdx.x * FM_WAVES + wave) * FM_DENSE_TILES + tt;
     const int64_t row0 = tid * DT;
     if (row0 >= A.N) return;  // whole wavefronts leave; no barrier follows
     const int nrows = (int)((A.N - row0) < DT ? (A.N - row0) : DT);
@@ -137,6 +141,8 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows_dense(const RowArgs A)
             A.row_part[2 * tid + 1] = rs;
         }
     }
+    __builtin_amdgcn_wave_barrier();  // the next tile overwrites the LDS tile
+    }  // tiles of this wavefront
 }
 
 // Partial sums of every column over one chunk of rows per wavefront: for column j and latent k
@@ -219,7 +225,8 @@ int launch_rows_dense_t(fm_matrix* m, const RowArgs& A, hipStream_t st)
     constexpr int S = (D > K ? D : K) + 1;
     const size_t lds = (size_t)(2 * D + FM_WAVES * DT * S) * sizeof(float);
     const int64_t tiles = (A.N + DT - 1) / DT;
-    const int64_t grid = (tiles + FM_WAVES - 1) / FM_WAVES;
+    const int64_t per = (int64_t)FM_WAVES * FM_DENSE_TILES;
+    const int64_t grid = (tiles + per - 1) / per;
     if (grid > 0x7fffffffLL) return fm_fail(m, FM_ERANGE, "row grid too large");
     ProfScope ps(m, st, FMK_ROWS_FORWARD);
     hipLaunchKernelGGL((k_rows_dense<DB, KB>), dim3((unsigned)grid), dim3(FM_BLOCK), lds, st, A);
@@ -279,14 +286,15 @@ bool fm_dense_shape_ok(const fm_matrix* m, int32_t K)
     return m->is_dense && m->opt.dense_rows && (m->D == 32 || m->D == 64) && (K == 32 || K == 64);
 }
 
-// One chunk of rows per wavefront, enough chunks to fill the chip a few times over; the index says
+// One chunk of rows per wavefront, FM_DENSE_CHUNKS of them (16 wavefronts per compute unit; with fewer the
+// kernel hides less latency than the shorter finish saves); the index says
 // that the partial sums of column j are the items j * nchunks .. (j+1) * nchunks - 1.
 int fm_dense_build_index(fm_matrix* m, hipStream_t st)
 {
     LongIndex* li = &m->ldense;
     if (li->long_col != nullptr || !m->is_dense) return FM_OK;
     const int64_t N = m->N, D = m->D;
-    int64_t rows = (N + 4095) / 4096;
+    int64_t rows = (N + FM_DENSE_CHUNKS - 1) / FM_DENSE_CHUNKS;
     rows = std::max<int64_t>(64, (rows + 7) / 8 * 8);
     m->dense_chunk_rows = rows;
     m->dense_chunks = (N + rows - 1) / rows;
