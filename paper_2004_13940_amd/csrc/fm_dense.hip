@@ -63,27 +63,41 @@ __global__ __launch_bounds__(FM_BLOCK) void k_rows_dense(const RowArgs A)
 #pragma unroll
         for (int t = 0; t < D / 2; ++t) vb[kb][t] = A.V[(int64_t)(2 * t + half) * K + kb * DT + lo];
 
-    // a wavefront takes FM_DENSE_TILES consecutive 32-row tiles, so that its share of V is loaded once for all of them
+    // A wavefront takes FM_DENSE_TILES consecutive 32-row tiles, so that its share of V is loaded once for all of
+    // them.  A tile's rows are contiguous in memory: coalesced float4 loads (rows past the end are zero), issued one
+    // tile ahead so that they are in flight while the tile before is worked on.
+    constexpr int NC = DT * (D / 4) / FM_WAVE;  // float4 per lane and tile
+    const int64_t tile0 = ((int64_t)blockIdx.x * FM_WAVES + wave) * FM_DENSE_TILES;
+    float4 xr[NC];
+    auto load_tile = [&](int64_t t) {
+        const int64_t r0 = t * DT;
+        const int64_t left = A.N - r0;
+        const int n4 = left <= 0 ? 0 : (int)((left < DT ? left : DT) * (D / 4));
+        const float4* __restrict__ src = reinterpret_cast<const float4*>(A.val + (left <= 0 ? 0 : r0 * D));
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            const int c = lane + i * FM_WAVE;
+            xr[i] = c < n4 ? src[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    load_tile(tile0);
+#pragma unroll 1
     for (int tt = 0; tt < FM_DENSE_TILES; ++tt) {
-    const int64_t tid = ((int64_t)blockIdx.x * FM_WAVES + wave) * FM_DENSE_TILES + tt;
+    const int64_t tid = tile0 + tt;
     const int64_t row0 = tid * DT;
     if (row0 >= A.N) return;  // whole wavefronts leave; no barrier follows
     const int nrows = (int)((A.N - row0) < DT ? (A.N - row0) : DT);
-    // the tile's rows are contiguous in memory: coalesced float4 loads, rows past the end are zero
-    {
-        const float4* __restrict__ src = reinterpret_cast<const float4*>(A.val + row0 * D);
-        const int n4 = nrows * (D / 4);
-        for (int c = lane; c < DT * (D / 4); c += FM_WAVE) {
-            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (c < n4) x = src[c];
-            const int r = c / (D / 4), k = (c % (D / 4)) * 4;
-            float* d = tile + r * S + k;
-            d[0] = x.x;
-            d[1] = x.y;
-            d[2] = x.z;
-            d[3] = x.w;
-        }
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = lane + i * FM_WAVE;
+        const int r = c / (D / 4), k = (c % (D / 4)) * 4;
+        float* d = tile + r * S + k;
+        d[0] = xr[i].x;
+        d[1] = xr[i].y;
+        d[2] = xr[i].z;
+        d[3] = xr[i].w;
     }
+    if (tt + 1 < FM_DENSE_TILES) load_tile(tid + 1);
     __builtin_amdgcn_wave_barrier();
     f32x16 acc[KB];
 #pragma unroll
