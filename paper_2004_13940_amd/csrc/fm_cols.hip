@@ -837,11 +837,14 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
         {
             ProfScope ps(m, st, FMK_COLS_FINISH);
             const int64_t g3 = (A.nlong + FM_WAVES - 1) / FM_WAVES;
-            if (update)
-                hipLaunchKernelGGL((k_cols_finish_wave<VEC, L, true>), dim3((unsigned)g3), dim3(FM_BLOCK), 0, st, Am);
-            else
-                hipLaunchKernelGGL((k_cols_finish_wave<VEC, L, false>), dim3((unsigned)g3), dim3(FM_BLOCK), 0, st, Am);
-            FM_HIP(m, hipGetLastError());
+            const bool all_by_block = A.vlong != nullptr && A.nvlong == A.nlong;  // nothing left for the wavefronts
+            if (!all_by_block) {
+                if (update)
+                    hipLaunchKernelGGL((k_cols_finish_wave<VEC, L, true>), dim3((unsigned)g3), dim3(FM_BLOCK), 0, st, Am);
+                else
+                    hipLaunchKernelGGL((k_cols_finish_wave<VEC, L, false>), dim3((unsigned)g3), dim3(FM_BLOCK), 0, st, Am);
+                FM_HIP(m, hipGetLastError());
+            }
             if (A.vlong != nullptr && A.nvlong > 0) {
                 if (update)
                     hipLaunchKernelGGL((k_cols_finish_block<VEC, L, true>), dim3((unsigned)A.nvlong), dim3(FM_BLOCK),
