@@ -571,8 +571,10 @@ extern "C" int fm_evaluate(fm_matrix* m, const fm_params* p, const float* y, con
     A.loss = p->loss;
     A.s = 1.f;
     FM_TRY(half_copy(m, p, V, &A.Vh, st));
+    const bool dense = A.Vh == nullptr && fm_dense_shape_ok(m, p->K);
+    if (dense) A.dense_D = (int32_t)m->D;
     FM_TRY(fm_launch_rows(m, A, false, st));
-    FM_TRY(fm_reduce_pairs(m, m->row_part, fm_rows_grid(m->N, p->K), m->scal + 0, st));
+    FM_TRY(fm_reduce_pairs(m, m->row_part, dense ? (m->N + 31) / 32 : fm_rows_grid(m->N, p->K), m->scal + 0, st));
     FM_TRY(fm_reduce_eval(m, m->aux, y, m->N, 0, m->scal + 4, st));
     FM_TRY(fm_reduce_eval(m, m->aux, y, m->N, 1, m->scal + 5, st));
     FM_HIP(m, hipMemcpyAsync(m->h_scal, m->scal, 6 * sizeof(double), hipMemcpyDeviceToHost, st));

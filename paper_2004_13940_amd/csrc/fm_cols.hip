@@ -825,7 +825,9 @@ int launch_cols_t(fm_matrix* m, const ColArgs& A, bool update, hipStream_t st)
             FM_HIP(m, hipGetLastError());
         }
         // empty columns of the full matrix: regulariser only (a stratum's wait for the marks, below)
-        if (need_empty && A.ptr != nullptr && A.D > 0) FM_TRY((launch_empty<VEC>(m, A, update, s_cols)));
+        // (nothing to launch when every column of the matrix is listed as short or long)
+        if (need_empty && A.ptr != nullptr && A.D > 0 && A.nshort + A.nlong < A.D)
+            FM_TRY((launch_empty<VEC>(m, A, update, s_cols)));
     }
     if (side) {
         FM_HIP(m, hipEventRecord(m->ev_join1, m->side1));

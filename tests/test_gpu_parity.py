@@ -952,6 +952,11 @@ def test_matrices_that_store_every_column_take_the_dense_kernels(N, D, K, loss):
         assert abs(loss_sum - float(l.sum())) <= REL_TOL * abs(float(l.sum()))
         # (G itself can agree bit for bit: both paths add the products of a row in column order)
         got_G[dense] = np.concatenate([out[k].cpu().numpy() for k in ("a", "q", "yhat")])
+        # the evaluation pass takes the same kernels
+        met = m.fm_evaluate(p, d_y, d_w0, d_w, d_V)
+        l1, _ = O.loss_multiplier(loss, 1.0, yhat, y)
+        assert abs(met["mean_loss"] - l1.mean()) <= REL_TOL * l1.mean()
+        assert abs(met["rmse"] - np.sqrt(np.mean((yhat - y) ** 2))) <= REL_TOL * np.sqrt(np.mean((yhat - y) ** 2))
         m.fm_build_csc()
         g0 = torch.zeros(1, device="cuda")
         gw = torch.full((D,), float("nan"), device="cuda")
