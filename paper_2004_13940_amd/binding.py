@@ -15,8 +15,9 @@ LIB_PATH = os.path.join(_HERE, "libfm_mi355x.so")
 FM_OK = 0
 FM_LOSS_SQUARED = 0
 FM_LOSS_LOGISTIC = 1
-STATUS_NAMES = {0: "FM_OK", -1: "FM_EINVAL", -2: "FM_ENOMEM", -3: "FM_EUNSORTED", -4: "FM_ERANGE",
-                -5: "FM_ESTATE", -6: "FM_EHIP"}
+FM_EINVAL, FM_ENOMEM, FM_EUNSORTED, FM_ERANGE, FM_ESTATE, FM_EHIP = -1, -2, -3, -4, -5, -6
+STATUS_NAMES = {FM_OK: "FM_OK", FM_EINVAL: "FM_EINVAL", FM_ENOMEM: "FM_ENOMEM", FM_EUNSORTED: "FM_EUNSORTED",
+                FM_ERANGE: "FM_ERANGE", FM_ESTATE: "FM_ESTATE", FM_EHIP: "FM_EHIP"}
 
 
 class fm_params(ctypes.Structure):

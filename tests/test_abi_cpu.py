@@ -37,6 +37,17 @@ def test_params_struct_layout_matches_header():
         "refresh_all_rows", "stale_aux", "half_gather"]
 
 
+def test_enumerators_of_the_binding_match_the_header():
+    """Every FM_* enumerator the header defines has the same value in the binding."""
+    from paper_2004_13940_amd import binding
+    header = open(os.path.join(ROOT, "include", "fm.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    found = dict(re.findall(r"\b(FM_[A-Z0-9_]+)\s*=\s*(-?\d+)", header))
+    assert {"FM_OK", "FM_LOSS_LOGISTIC", "FM_OPT_GRAPH", "FM_OPT_DENSE_ROWS"} <= set(found)
+    for name, value in found.items():
+        assert getattr(binding, name) == int(value), name
+
+
 def _try_build(lib, N, D, rowptr, col, val):
     rowptr = np.asarray(rowptr, np.int64)
     col = np.asarray(col, np.int32)
