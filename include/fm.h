@@ -2,7 +2,8 @@
  * fm.h -- C ABI of the MI355X factorization-machine (FM) pass of DS-FACTO.
  *
  * One GPU, gfx950.  Plain pointers and sizes only.  "HOST" marks host memory,
- * "DEVICE" marks device memory owned by the caller (fp32, contiguous).  The
+ * "DEVICE" marks device memory owned by the caller (fp32, contiguous; the arrays
+ * with K floats per row -- V, G, grad_V -- 16-byte aligned, FM_EINVAL otherwise).  The
  * library owns only what hangs off an fm_matrix handle.
  *
  * Notation (paper symbol in quotes where it differs):

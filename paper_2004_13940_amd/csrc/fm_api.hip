@@ -524,6 +524,7 @@ extern "C" int fm_forward(fm_matrix* m, const fm_params* p, const float* y, cons
     FM_TRY(check_params(m, p));
     if (w0 == nullptr || w == nullptr || V == nullptr) return fm_fail(m, FM_EINVAL, "w0, w, V must not be NULL");
     if ((r != nullptr || loss_sum != nullptr) && y == nullptr) return fm_fail(m, FM_EINVAL, "r and loss_sum need y");
+    FM_TRY(fm_check_vec_aligned(m, {V, G}));
     hipStream_t st = (hipStream_t)hip_stream;
     FM_TRY(ensure_ws(m, p->K));
     if (m->N == 0) {
@@ -546,6 +547,7 @@ extern "C" int fm_evaluate(fm_matrix* m, const fm_params* p, const float* y, con
     FM_TRY(check_params(m, p));
     if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr || metrics == nullptr)
         return fm_fail(m, FM_EINVAL, "y, w0, w, V, metrics must not be NULL");
+    FM_TRY(fm_check_vec_aligned(m, {V}));
     hipStream_t st = (hipStream_t)hip_stream;
     FM_TRY(ensure_ws(m, p->K));
     metrics[0] = metrics[1] = metrics[2] = 0.0;
@@ -623,6 +625,7 @@ extern "C" int fm_gradient(fm_matrix* m, const fm_params* p, const float* r, con
     if (!m->has_csc) return fm_fail(m, FM_ESTATE, "fm_gradient needs fm_build_csc first");
     if (r == nullptr || G == nullptr || w == nullptr || V == nullptr)
         return fm_fail(m, FM_EINVAL, "r, G, w, V must not be NULL");
+    FM_TRY(fm_check_vec_aligned(m, {G, V, grad_V}));
     hipStream_t st = (hipStream_t)hip_stream;
     FM_TRY(ensure_ws(m, p->K));
     if (grad_w0 != nullptr) {
@@ -671,6 +674,7 @@ extern "C" int fm_sgd_epoch(fm_matrix* m, const fm_params* p, const float* y, fl
     if (!m->has_csc) return fm_fail(m, FM_ESTATE, "fm_sgd_epoch needs fm_build_csc first");
     if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
         return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
+    FM_TRY(fm_check_vec_aligned(m, {V}));
     hipStream_t st = (hipStream_t)hip_stream;
     FM_TRY(ensure_ws(m, p->K));
     if (m->N == 0 || m->D == 0) {
@@ -721,6 +725,7 @@ extern "C" int fm_stratified_begin(fm_matrix* m, const fm_params* p, const float
     if (m->P == 0) return fm_fail(m, FM_ESTATE, "stratified calls need fm_partition first");
     if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
         return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
+    FM_TRY(fm_check_vec_aligned(m, {V}));
     hipStream_t st = (hipStream_t)hip_stream;
     FM_TRY(ensure_strat_ws(m, p->K));
     FM_TRY(run_forward(m, p, y, w0, w, V, nullptr, nullptr, nullptr, nullptr, nullptr, 2, false, st));
@@ -813,6 +818,7 @@ extern "C" int fm_stratified_step(fm_matrix* m, const fm_params* p, int32_t s, c
     if (s < 0 || s >= m->P) return fm_fail(m, FM_EINVAL, "stratum %d outside [0,%d)", s, m->P);
     if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
         return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
+    FM_TRY(fm_check_vec_aligned(m, {V}));
     if (m->wsK != p->K || !m->aux_full) return fm_fail(m, FM_ESTATE, "call fm_stratified_begin first");
     return stratified_step(m, p, s, y, w0, w, V, false, (hipStream_t)hip_stream);
 }
@@ -918,6 +924,7 @@ extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float
     if (m->P == 0) return fm_fail(m, FM_ESTATE, "stratified calls need fm_partition first");
     if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
         return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
+    FM_TRY(fm_check_vec_aligned(m, {V}));
     hipStream_t st = (hipStream_t)hip_stream;
     FM_TRY(ensure_strat_ws(m, p->K));
     // The refresh of a stratum reads the change of a column only where the column has entries in
@@ -961,6 +968,7 @@ extern "C" int fm_minibatch_epoch(fm_matrix* m, const fm_params* p, const float*
     if (m->B == 0) return fm_fail(m, FM_ESTATE, "fm_minibatch_epoch needs fm_partition_batches first");
     if (y == nullptr || w0 == nullptr || w == nullptr || V == nullptr)
         return fm_fail(m, FM_EINVAL, "y, w0, w, V must not be NULL");
+    FM_TRY(fm_check_vec_aligned(m, {V}));
     hipStream_t st = (hipStream_t)hip_stream;
     FM_TRY(ensure_ws(m, p->K));
     m->aux_full = false;

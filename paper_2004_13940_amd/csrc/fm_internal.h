@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <initializer_list>
 #include <string>
 #include <vector>
 
@@ -203,6 +204,14 @@ struct fm_matrix {
 
 // ---- helpers (fm_api.hip) ----
 int fm_fail(fm_matrix* m, int code, const char* fmt, ...);
+// the kernels read and write the arrays that hold K floats per row four floats at a time
+inline int fm_check_vec_aligned(fm_matrix* m, std::initializer_list<const void*> arrays)
+{
+    for (const void* a : arrays)
+        if ((reinterpret_cast<uintptr_t>(a) & 15u) != 0)
+            return fm_fail(m, FM_EINVAL, "device arrays with K floats per row (V, G, grad_V) must be 16-byte aligned");
+    return FM_OK;
+}
 int fm_dev_alloc(fm_matrix* m, void** p, size_t bytes);
 void fm_dev_free(fm_matrix* m, void* p);
 void fm_drop_workspace(fm_matrix* m);  // forces reallocation after the structures changed

@@ -47,6 +47,7 @@ extern "C" int fm_forward_noalloc(fm_matrix* m, const fm_params* p, const float*
     if (p->loss != FM_LOSS_SQUARED && p->loss != FM_LOSS_LOGISTIC) return fm_fail(m, FM_EINVAL, "unknown loss %d", p->loss);
     if (w0 == nullptr || w == nullptr || V == nullptr) return fm_fail(m, FM_EINVAL, "w0, w, V must not be NULL");
     if ((r != nullptr || sums != nullptr) && y == nullptr) return fm_fail(m, FM_EINVAL, "r and sums need y");
+    FM_TRY(fm_check_vec_aligned(m, {V, G}));
     if (p->half_gather) return fm_fail(m, FM_EINVAL, "half_gather needs a buffer for the copy of V: use fm_forward");
     if (m->prof) return fm_fail(m, FM_ESTATE, "per-kernel timing creates events: switch it off for this call");
     int dev = -1;

@@ -679,6 +679,17 @@ def test_state_and_argument_errors_are_reported():
     with pytest.raises(B.FMError) as e:
         m.fm_stratified_step(p, 0, d_y, d_w0, d_w, d_V)  # no begin yet
     assert e.value.code == -5
+    # arrays with K floats per row must be 16-byte aligned: a view that starts one float into a buffer is refused
+    skew = torch.zeros(41, device="cuda")[1:]
+    assert skew.data_ptr() % 16 == 4
+    for call in (lambda: m.fm_forward(p, d_y, d_w0, d_w, skew),
+                 lambda: m.fm_forward(p, d_y, d_w0, d_w, d_V, G=torch.zeros(81, device="cuda")[1:]),
+                 lambda: m.fm_sgd_epoch(p, d_y, d_w0, d_w, skew),
+                 lambda: m.fm_gradient(p, r, G, d_w, d_V, None, None, skew),
+                 lambda: m.fm_forward_noalloc(p, d_y, d_w0, d_w, skew)):
+        with pytest.raises(B.FMError) as e:
+            call()
+        assert e.value.code == B.FM_EINVAL and "aligned" in str(e.value)
     m.close()
 
 
