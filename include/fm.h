@@ -254,7 +254,8 @@ int fm_profile_read(fm_matrix* m, int64_t* launches /*HOST nk*/, double* total_m
  *                        regulariser-only steps of columns without entries in a cell or batch; 0: every
  *                        column takes its step in every stratum or batch.
  *   FM_OPT_GRAPH         fm_stratified_epoch replayed from a captured HIP graph: 0 never, 1 (default)
- *                        when the strata are small enough for the launches to dominate, 2 always.
+ *                        when there are 32 strata or more, or 16 and strata small enough for the launches
+ *                        to dominate, 2 always.
  *   FM_OPT_DENSE_ROWS    1 (default): a matrix in which every row stores all D columns (D and K in
  *                        {32, 64}) takes dense kernels on the matrix cores for fm_forward, fm_gradient and
  *                        fm_sgd_epoch (G = XV and X^T(r.G) as fp32 contractions; the column indices are not

@@ -933,8 +933,9 @@ extern "C" int fm_stratified_epoch(fm_matrix* m, const fm_params* p, const float
     const bool lazy = (!p->refresh_all_rows || p->stale_aux) && m->lazy_last != nullptr && m->opt.lazy_reg;
     // small strata are bound by their launches: replay them from a graph
     const int gmode = m->opt.graph;  // 0 never, 1 for matrices whose strata are small enough for the launches to dominate, 2 always
-    // (worth it from some tens of launches on: below that the two events and the graph launch cost more)
-    const bool small = m->nnz / m->P < (int64_t(1) << 20) && m->P >= 16;
+    // (worth it from some tens of launches on: below that the two events and the graph launch cost more; with
+    // 32 strata or more the replay pays even when the strata are large: 2 % on the click-style and the hashed workload)
+    const bool small = m->P >= 32 || (m->nnz / m->P < (int64_t(1) << 20) && m->P >= 16);
     bool done = false;
     if (!m->prof && (gmode == 2 || (gmode == 1 && small)) && graph_ready(m)) {
         const int rc = replay_stratified_epoch(m, p, y, w0, w, V, lazy, st);
